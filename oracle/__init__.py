@@ -1,0 +1,181 @@
+"""Python face of the CPU oracle (oracle/remoe_oracle.c, loaded through ctypes).
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, the smoke check and the
+benchmark's CPU-baseline leg.  It never imports the HIP package and the HIP
+package never imports it.  Arguments are CPU torch tensors (torch is used as a
+typed buffer only, which gives bf16 storage); results are fp64 / integer CPU
+tensors.  All arithmetic happens in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional, Sequence
+
+import torch
+
+from .build import ensure_built
+
+_lib = None
+
+_c_i64 = ctypes.c_int64
+_c_int = ctypes.c_int
+_c_ptr = ctypes.c_void_p
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(ensure_built())
+        _lib.oracle_route.restype = _c_int
+        _lib.oracle_route.argtypes = [_c_ptr, _c_int, _c_i64, _c_int, _c_ptr, _c_int, _c_int, _c_int,
+                                      _c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_ptr]
+        _lib.oracle_experts_sparse.restype = _c_int
+        _lib.oracle_experts_sparse.argtypes = [_c_ptr, _c_int, _c_int, _c_int, _c_int, _c_int,
+                                               _c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_ptr,
+                                               _c_int, _c_ptr, _c_ptr, _c_ptr, _c_ptr,
+                                               _c_ptr, _c_i64, _c_ptr]
+        _lib.oracle_experts_dense_masked.restype = _c_int
+        _lib.oracle_experts_dense_masked.argtypes = [_c_ptr, _c_int, _c_i64, _c_int, _c_int, _c_int, _c_int,
+                                                     _c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_ptr,
+                                                     _c_int, _c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_ptr]
+        _lib.oracle_trace_reuse.restype = _c_int
+        _lib.oracle_trace_reuse.argtypes = [_c_ptr, _c_i64, _c_i64, _c_int, _c_int, _c_ptr, _c_ptr]
+        _lib.oracle_lru_list.restype = _c_int
+        _lib.oracle_lru_list.argtypes = [_c_ptr, _c_i64, _c_i64, _c_int, _c_int, _c_int, ctypes.c_uint64,
+                                         _c_ptr, _c_ptr, _c_ptr]
+    return _lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return 0
+    if t.dtype == torch.bfloat16:
+        return 1
+    raise TypeError(f"oracle: unsupported dtype {t.dtype}")
+
+
+def _chk(t: Optional[torch.Tensor], dtype=None) -> Optional[torch.Tensor]:
+    if t is None:
+        return None
+    if t.device.type != "cpu":
+        raise ValueError("oracle takes CPU tensors")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"oracle: expected {dtype}, got {t.dtype}")
+    return t.contiguous()
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def route(x: torch.Tensor, w_router: torch.Tensor, top_k: int, renorm: bool,
+          want_probs: bool = False, want_logits: bool = False):
+    """Router of Sec. 3.1 for tokens x [T,H]: returns dict(idx, w, margin[, probs][, logits])."""
+    x = _chk(x)
+    w_router = _chk(w_router, torch.float32)
+    T, H = x.shape
+    N = w_router.shape[0]
+    assert w_router.shape[1] == H
+    idx = torch.empty(T, top_k, dtype=torch.int32)
+    w = torch.empty(T, top_k, dtype=torch.float64)
+    margin = torch.empty(T, dtype=torch.float64)
+    probs = torch.empty(T, N, dtype=torch.float64) if want_probs else None
+    logits = torch.empty(T, N, dtype=torch.float64) if want_logits else None
+    rc = lib().oracle_route(_p(x), _dtype_code(x), T, H, _p(w_router), N, top_k, int(bool(renorm)),
+                            _p(idx), _p(w), _p(margin), _p(probs), _p(logits))
+    if rc != 0:
+        raise RuntimeError(f"oracle_route failed ({rc})")
+    out = {"idx": idx, "w": w, "margin": margin}
+    if want_probs:
+        out["probs"] = probs
+    if want_logits:
+        out["logits"] = logits
+    return out
+
+
+def _expert_args(x, weights):
+    wg = _chk(weights["w_gate"]); wu = _chk(weights["w_up"]); wd = _chk(weights["w_down"])
+    for m in (wg, wu, wd):
+        if m.dtype != x.dtype:
+            raise TypeError("oracle: x and expert weights must share a dtype")
+    N, I, H = wg.shape
+    assert wu.shape == (N, I, H) and wd.shape == (N, H, I) and x.shape[1] == H
+    sg = _chk(weights.get("ws_gate")); su = _chk(weights.get("ws_up")); sd = _chk(weights.get("ws_down"))
+    sc = _chk(weights.get("ws_scale"), torch.float32) if weights.get("ws_scale") is not None else None
+    Is = 0 if sg is None else sg.shape[0]
+    if Is:
+        assert sg.shape == (Is, H) and su.shape == (Is, H) and sd.shape == (H, Is)
+        assert sg.dtype == x.dtype and su.dtype == x.dtype and sd.dtype == x.dtype
+    keep = (wg, wu, wd, sg, su, sd, sc)
+    return N, I, H, Is, keep
+
+
+def experts_sparse(x: torch.Tensor, idx: torch.Tensor, w: torch.Tensor, weights: dict,
+                   tokens: Optional[Sequence[int]] = None) -> torch.Tensor:
+    """y[t] = sum_j w[t,j] * expert_{idx[t,j]}(x[t]) + shared(x[t]) for the listed tokens (fp64)."""
+    x = _chk(x)
+    idx = _chk(idx, torch.int32)
+    w = _chk(w.to(torch.float64))
+    N, I, H, Is, (wg, wu, wd, sg, su, sd, sc) = _expert_args(x, weights)
+    K = idx.shape[1]
+    tok = None
+    n_sel = x.shape[0]
+    if tokens is not None:
+        tok = torch.as_tensor(list(tokens), dtype=torch.int64).contiguous()
+        n_sel = tok.numel()
+    y = torch.empty(n_sel, H, dtype=torch.float64)
+    rc = lib().oracle_experts_sparse(_p(x), _dtype_code(x), H, N, I, K, _p(idx), _p(w),
+                                     _p(wg), _p(wu), _p(wd), Is, _p(sg), _p(su), _p(sd), _p(sc),
+                                     _p(tok), n_sel, _p(y))
+    if rc != 0:
+        raise RuntimeError(f"oracle_experts_sparse failed ({rc})")
+    return y
+
+
+def experts_dense_masked(x: torch.Tensor, idx: torch.Tensor, w: torch.Tensor, weights: dict) -> torch.Tensor:
+    """Dense check form: all N experts evaluated, combined with masked gate weights (fp64)."""
+    x = _chk(x)
+    idx = _chk(idx, torch.int32)
+    w = _chk(w.to(torch.float64))
+    N, I, H, Is, (wg, wu, wd, sg, su, sd, sc) = _expert_args(x, weights)
+    T, K = idx.shape
+    y = torch.empty(T, H, dtype=torch.float64)
+    rc = lib().oracle_experts_dense_masked(_p(x), _dtype_code(x), T, H, N, I, K, _p(idx), _p(w),
+                                           _p(wg), _p(wu), _p(wd), Is, _p(sg), _p(su), _p(sd), _p(sc), _p(y))
+    if rc != 0:
+        raise RuntimeError(f"oracle_experts_dense_masked failed ({rc})")
+    return y
+
+
+def forward(x: torch.Tensor, weights: dict, top_k: int, renorm: bool,
+            tokens: Optional[Sequence[int]] = None):
+    """Whole layer: route every token, evaluate the experts for `tokens` (all if None)."""
+    r = route(x, weights["w_router"], top_k, renorm)
+    r["y"] = experts_sparse(x, r["idx"], r["w"], weights, tokens)
+    return r
+
+
+def trace_reuse(idx: torch.Tensor, n_experts: int):
+    """Adjacent-step overlap |E_t ∩ E_{t-1}| per trace: idx int32 [S,T,K] -> (ov uint8 [S,T], sum uint64 [S])."""
+    idx = _chk(idx, torch.int32)
+    S, T, K = idx.shape
+    ov = torch.empty(S, T, dtype=torch.uint8)
+    tot = torch.empty(S, dtype=torch.int64)
+    rc = lib().oracle_trace_reuse(_p(idx), S, T, K, n_experts, _p(ov), _p(tot))
+    if rc != 0:
+        raise RuntimeError(f"oracle_trace_reuse failed ({rc})")
+    return ov, tot
+
+
+def lru_list(idx: torch.Tensor, n_experts: int, capacity: int, expert_bytes: int = 0):
+    """Cold-start LRU misses per trace: (miss uint8 [S,T], total int64 [S], bytes int64 [S])."""
+    idx = _chk(idx, torch.int32)
+    S, T, K = idx.shape
+    miss = torch.empty(S, T, dtype=torch.uint8)
+    tot = torch.empty(S, dtype=torch.int64)
+    nbytes = torch.empty(S, dtype=torch.int64)
+    rc = lib().oracle_lru_list(_p(idx), S, T, K, n_experts, capacity, expert_bytes,
+                               _p(miss), _p(tot), _p(nbytes))
+    if rc != 0:
+        raise RuntimeError(f"oracle_lru_list failed ({rc})")
+    return miss, tot, nbytes
