@@ -1,0 +1,160 @@
+/*
+ * remoe.h — C ABI of the MI355X (gfx950) MoE-layer hot path and routing-trace statistics.
+ *
+ * Notation follows the paper's preliminaries (Sec. 3.1): N_r routed experts, router parameters
+ * theta_gate, hidden state h_t, routing distribution P_t, selected set E_t with |E_t| = K,
+ * per-layer expert-cache capacity C.  In this header: T = tokens in a call, H = hidden size,
+ * I = routed expert intermediate size, I_s = total shared-expert intermediate size.
+ *
+ * General conventions
+ *   - Every pointer is a DEVICE pointer owned by the caller unless marked "host".  The library
+ *     never allocates, frees or keeps caller-visible memory; scratch comes from the caller's
+ *     workspace (remoe_workspace_bytes).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null stream) and the
+ *     host is never synchronised; outputs are valid once the stream reaches the end of the call.
+ *   - Matrices are row-major [out_features, in_features] (reduction dimension contiguous).
+ *   - Expert ids are 0-based (the paper counts from 1).
+ *   - Every entry point validates its arguments before launching anything and returns a negative
+ *     remoe_status on error; remoe_last_error() then holds a message.  No exception crosses the ABI.
+ *   - Expert ids inside a trace handed to trace_reuse / lru_simulate must lie in [0, n_experts);
+ *     ids outside are ignored by the kernels (they never index memory with them).
+ */
+#ifndef REMOE_H
+#define REMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    REMOE_OK = 0,
+    REMOE_E_INVALID_ARG = -1,
+    REMOE_E_UNSUPPORTED = -2,
+    REMOE_E_WORKSPACE = -3,
+    REMOE_E_HIP = -4
+} remoe_status;
+
+typedef enum { REMOE_F32 = 0, REMOE_BF16 = 1 } remoe_dtype;
+
+/* Shape of one MoE layer. */
+typedef struct {
+    int32_t hidden;        /* H; multiple of 32 (of 128 when dtype is bf16)                         */
+    int32_t n_experts;     /* N_r, 1..128                                                            */
+    int32_t inter;         /* I; multiple of 64 when dtype is bf16                                   */
+    int32_t top_k;         /* K, 1..min(N_r, 8)                                                      */
+    int32_t renorm;        /* 0: w = P_t[E_t]; 1: w divided by the sum over the K selected           */
+    int32_t shared_inter;  /* I_s, 0 = no shared expert; multiple of 64 when dtype is bf16           */
+    int32_t shared_gate;   /* 1: shared expert output scaled by sigmoid(ws_scale . x)                */
+    int32_t dtype;         /* remoe_dtype of x, expert weights and y; the router is always fp32      */
+} remoe_layer_desc;
+
+/* Library version (major * 10000 + minor * 100 + patch). Host call, no GPU work. */
+int32_t remoe_version(void);
+
+/* Message of the calling thread's last failed call (static thread-local storage, never NULL). */
+const char *remoe_last_error(void);
+
+/* Bytes of workspace moe_forward needs for `n_tokens` tokens of this layer shape (0 on invalid
+ * arguments, with remoe_last_error set).  Host call, no GPU work. */
+size_t remoe_workspace_bytes(const remoe_layer_desc *desc, int64_t n_tokens);
+
+/*
+ * moe_route — the router of Sec. 3.1: P_t = Softmax(h_t^T theta_gate), E_t = Top-K(P_t).
+ *
+ *   x          [T, H]    hidden states, desc->dtype (bf16 values are widened exactly to fp32)
+ *   w_router   [N_r, H]  fp32 gate matrix, no bias
+ *   out_idx    [T, K]    int32 expert ids, ordered by descending logit, ties to the lower id
+ *   out_w      [T, K]    fp32 gate weights P_t[E_t] (softmax over all N_r experts), divided by
+ *                        their sum when desc->renorm
+ *   out_margin [T]       fp32 logit_(K) - logit_(K+1) (+inf when K == N_r), or NULL
+ *   out_probs  [T, N_r]  fp32 P_t, or NULL
+ *
+ * Products and sums are fp32 (fp32 matrix cores).  T may be 0 (nothing is launched).
+ * Only hidden, n_experts, top_k, renorm and dtype of `desc` are read.
+ */
+remoe_status moe_route(const remoe_layer_desc *desc, const void *x, int64_t n_tokens,
+                       const float *w_router, int32_t *out_idx, float *out_w,
+                       float *out_margin, float *out_probs, void *stream);
+
+/*
+ * moe_forward — one fine-grained MoE layer (Sec. 3.1 routing; Sec. 4.1 step 5: the selected
+ * Top-K experts execute as in the base model; shared experts always execute and lie outside P_t):
+ *
+ *   y[t] = sum_{j<K} out_w[t,j] * FFN_{out_idx[t,j]}(x[t])  +  s_t * FFN_shared(x[t])
+ *   FFN_e(x) = W_down[e] ( silu(W_gate[e] x) * (W_up[e] x) ),  silu(z) = z / (1 + exp(-z))
+ *   s_t = sigmoid(ws_scale . x[t]) when desc->shared_gate, else 1
+ *
+ *   x        [T, H]          desc->dtype
+ *   w_router [N_r, H]        fp32
+ *   w_gate   [N_r, I, H]     desc->dtype        w_up [N_r, I, H]      w_down [N_r, H, I]
+ *   ws_gate  [I_s, H]        desc->dtype        ws_up [I_s, H]        ws_down [H, I_s]
+ *                            (NULL when shared_inter == 0)
+ *   ws_scale [H]             fp32 (NULL unless shared_gate)
+ *   y        [T, H]          desc->dtype
+ *   out_idx  [T, K] int32,   out_w [T, K] fp32  — the routing, as moe_route returns it
+ *   workspace                at least remoe_workspace_bytes(desc, T) bytes, 256-byte aligned;
+ *                            contents are scratch and meaningless afterwards
+ *
+ * No residual connection and no normalisation.  bf16 layers multiply on the bf16 matrix cores
+ * with fp32 accumulation; the SwiGLU activations and the per-(token, expert) outputs are stored
+ * in bf16 between kernels and the K (+1) rows of a token are summed in fp32.  fp32 layers
+ * compute in fp32 throughout.  The result is deterministic (no floating-point atomics).
+ */
+remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_tokens,
+                         const float *w_router,
+                         const void *w_gate, const void *w_up, const void *w_down,
+                         const void *ws_gate, const void *ws_up, const void *ws_down,
+                         const float *ws_scale,
+                         void *y, int32_t *out_idx, float *out_w,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * trace_reuse — adjacent-step expert overlap, the numerator of IR_t in Eq. 1 (Sec. 3.2):
+ *
+ *   out_overlap[s, 0] = 0,  out_overlap[s, t] = |E_t ∩ E_{t-1}|  (sets of distinct ids)
+ *   out_sum[s]        = sum_t out_overlap[s, t]     (EOR = out_sum / (K (T-1)), left to the caller)
+ *
+ *   idx         [S, T, K]  int32 routing trace; S independent traces, one per (sequence, layer)
+ *   out_overlap [S, T]     uint8
+ *   out_sum     [S]        uint64
+ *
+ * Traces never see each other.  n_experts <= 128, top_k <= 64.  S or T may be 0.
+ */
+remoe_status trace_reuse(const int32_t *idx, int64_t n_seq, int64_t n_steps,
+                         int32_t top_k, int32_t n_experts,
+                         uint8_t *out_overlap, uint64_t *out_sum, void *stream);
+
+/*
+ * lru_simulate — per-layer LRU expert cache of capacity C (Sec. 5.1 "Expert-cache simulation",
+ * App. A cache model, App. E.2 unique-miss accounting):
+ *
+ *   out_miss[s, t]    = |U_t \ C_t|, U_t the distinct ids of step t, C_t the resident set BEFORE
+ *                       the step is served
+ *   out_total_miss[s] = sum_t out_miss[s, t]                         (#uMiss)
+ *   out_bytes[s]      = out_total_miss[s] * expert_bytes             (bytes fetched)
+ *
+ * After counting, the step's experts become the most recent ones (within a step in ascending id
+ * order) and the cache keeps the C most recent distinct experts.
+ *
+ *   state [S, N_r] uint32, or NULL.  Entry e holds (global step of e's last use) + 1, 0 = never
+ *         used.  NULL: every trace starts cold and the final state is discarded.  Non-NULL: the
+ *         state is read, updated and written back, so a trace can be fed in pieces (online decode:
+ *         n_steps = 1 per call); a zero-filled state is a cold cache.
+ *   step0 global index of the first step of this call (>= 0; step0 + n_steps must stay below
+ *         2^24 so that recency keys fit 32 bits).
+ *
+ * n_experts <= 128, top_k <= 64, capacity >= 1.  S or T may be 0.
+ */
+remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps,
+                          int32_t top_k, int32_t n_experts, int32_t capacity,
+                          uint64_t expert_bytes, int64_t step0, uint32_t *state,
+                          uint8_t *out_miss, uint64_t *out_total_miss, uint64_t *out_bytes,
+                          void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REMOE_H */

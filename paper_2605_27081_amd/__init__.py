@@ -1,0 +1,19 @@
+"""MI355X-native MoE-layer hot path and routing-trace statistics (thin binding over the C ABI).
+
+Every step runs in the HIP library `libremoe_hip.so` (sources in csrc/, declarations in
+include/remoe.h); this package only marshals arguments.  There is no CPU fallback: calls fail
+loudly when the library has not been built.
+"""
+from .binding import (  # noqa: F401
+    LayerDesc,
+    RemoeError,
+    library_path,
+    load_library,
+    lru_simulate,
+    moe_forward,
+    moe_route,
+    remoe_last_error,
+    remoe_version,
+    remoe_workspace_bytes,
+    trace_reuse,
+)

@@ -1,0 +1,136 @@
+"""ctypes binding of include/remoe.h: same names, argument marshalling only.
+
+torch supplies device memory and the current HIP stream; nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libremoe_hip.so")
+_lib: Optional[ctypes.CDLL] = None
+
+REMOE_F32, REMOE_BF16 = 0, 1
+
+
+class RemoeError(RuntimeError):
+    """A C-ABI call returned a negative status."""
+
+
+class LayerDesc(ctypes.Structure):
+    """Mirror of remoe_layer_desc."""
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("hidden", "n_experts", "inter", "top_k", "renorm", "shared_inter", "shared_gate", "dtype")]
+
+    @classmethod
+    def from_config(cls, cfg) -> "LayerDesc":
+        return cls(cfg.hidden, cfg.n_experts, cfg.inter, cfg.top_k, int(cfg.renorm), cfg.shared_inter,
+                   int(cfg.shared_gate), REMOE_F32 if cfg.dtype == "f32" else REMOE_BF16)
+
+    @property
+    def torch_dtype(self):
+        return torch.float32 if self.dtype == REMOE_F32 else torch.bfloat16
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libremoe_hip.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RemoeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2605_27081_amd.build` "
+                         "(hipcc, gfx950); there is no CPU fallback")
+    lib = ctypes.CDLL(_LIB_PATH)
+    P, I64, I32, U64, SZ = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_size_t
+    D = ctypes.POINTER(LayerDesc)
+    lib.remoe_version.restype = I32
+    lib.remoe_version.argtypes = []
+    lib.remoe_last_error.restype = ctypes.c_char_p
+    lib.remoe_last_error.argtypes = []
+    lib.remoe_workspace_bytes.restype = SZ
+    lib.remoe_workspace_bytes.argtypes = [D, I64]
+    lib.moe_route.restype = ctypes.c_int
+    lib.moe_route.argtypes = [D, P, I64, P, P, P, P, P, P]
+    lib.moe_forward.restype = ctypes.c_int
+    lib.moe_forward.argtypes = [D, P, I64, P, P, P, P, P, P, P, P, P, P, P, P, SZ, P]
+    lib.trace_reuse.restype = ctypes.c_int
+    lib.trace_reuse.argtypes = [P, I64, I64, I32, I32, P, P, P]
+    lib.lru_simulate.restype = ctypes.c_int
+    lib.lru_simulate.argtypes = [P, I64, I64, I32, I32, I32, U64, I64, P, P, P, P, P]
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise RemoeError(f"remoe status {status}: {remoe_last_error()}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise RemoeError("the library takes device tensors")
+    if not t.is_contiguous():
+        raise RemoeError("tensors must be contiguous")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def remoe_version() -> int:
+    return int(load_library().remoe_version())
+
+
+def remoe_last_error() -> str:
+    return load_library().remoe_last_error().decode()
+
+
+def remoe_workspace_bytes(desc: LayerDesc, n_tokens: int) -> int:
+    n = int(load_library().remoe_workspace_bytes(ctypes.byref(desc), n_tokens))
+    if n == 0 and n_tokens != 0:
+        raise RemoeError(f"remoe_workspace_bytes: {remoe_last_error()}")
+    return n
+
+
+def moe_route(desc: LayerDesc, x: torch.Tensor, w_router: torch.Tensor, out_idx: torch.Tensor,
+              out_w: torch.Tensor, out_margin: Optional[torch.Tensor] = None,
+              out_probs: Optional[torch.Tensor] = None) -> None:
+    n_tokens = x.shape[0]
+    _check(load_library().moe_route(ctypes.byref(desc), _ptr(x), n_tokens, _ptr(w_router), _ptr(out_idx),
+                                    _ptr(out_w), _ptr(out_margin), _ptr(out_probs), _stream()))
+
+
+def moe_forward(desc: LayerDesc, x: torch.Tensor, w_router, w_gate, w_up, w_down, ws_gate, ws_up, ws_down,
+                ws_scale, y: torch.Tensor, out_idx: torch.Tensor, out_w: torch.Tensor,
+                workspace: torch.Tensor) -> None:
+    n_tokens = x.shape[0]
+    _check(load_library().moe_forward(ctypes.byref(desc), _ptr(x), n_tokens, _ptr(w_router), _ptr(w_gate),
+                                      _ptr(w_up), _ptr(w_down), _ptr(ws_gate), _ptr(ws_up), _ptr(ws_down),
+                                      _ptr(ws_scale), _ptr(y), _ptr(out_idx), _ptr(out_w), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream()))
+
+
+def trace_reuse(idx: torch.Tensor, n_experts: int, out_overlap: torch.Tensor, out_sum: torch.Tensor) -> None:
+    n_seq, n_steps, top_k = idx.shape
+    _check(load_library().trace_reuse(_ptr(idx), n_seq, n_steps, top_k, n_experts, _ptr(out_overlap),
+                                      _ptr(out_sum), _stream()))
+
+
+def lru_simulate(idx: torch.Tensor, n_experts: int, capacity: int, expert_bytes: int, step0: int,
+                 state: Optional[torch.Tensor], out_miss: torch.Tensor, out_total_miss: torch.Tensor,
+                 out_bytes: torch.Tensor) -> None:
+    n_seq, n_steps, top_k = idx.shape
+    _check(load_library().lru_simulate(_ptr(idx), n_seq, n_steps, top_k, n_experts, capacity, expert_bytes,
+                                       step0, _ptr(state), _ptr(out_miss), _ptr(out_total_miss),
+                                       _ptr(out_bytes), _stream()))

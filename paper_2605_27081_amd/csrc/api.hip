@@ -1,0 +1,271 @@
+// C-ABI entry points: argument validation, workspace layout and kernel sequencing.
+#include <stdarg.h>
+#include <string.h>
+
+#include "common.h"
+
+namespace remoe {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+remoe_status fail(remoe_status code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+remoe_status check_hip(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return REMOE_OK;
+    return fail(REMOE_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+namespace {
+
+constexpr int MAX_EXPERTS = 128;
+constexpr int MAX_TOP_K = 8;
+constexpr int64_t MAX_TOKENS = 1 << 22;   // keeps T*K and every slot index inside int32
+
+remoe_status validate_route_desc(const remoe_layer_desc *d)
+{
+    if (!d) return fail(REMOE_E_INVALID_ARG, "desc is NULL");
+    if (d->dtype != REMOE_F32 && d->dtype != REMOE_BF16)
+        return fail(REMOE_E_INVALID_ARG, "dtype %d is neither REMOE_F32 nor REMOE_BF16", d->dtype);
+    if (d->n_experts < 1 || d->n_experts > MAX_EXPERTS)
+        return fail(REMOE_E_INVALID_ARG, "n_experts %d outside 1..%d", d->n_experts, MAX_EXPERTS);
+    if (d->top_k < 1 || d->top_k > MAX_TOP_K || d->top_k > d->n_experts)
+        return fail(REMOE_E_INVALID_ARG, "top_k %d outside 1..min(n_experts, %d)", d->top_k, MAX_TOP_K);
+    if (d->hidden < 32 || d->hidden % 32 != 0)
+        return fail(REMOE_E_INVALID_ARG, "hidden %d must be a positive multiple of 32", d->hidden);
+    if (d->renorm != 0 && d->renorm != 1) return fail(REMOE_E_INVALID_ARG, "renorm must be 0 or 1");
+    return REMOE_OK;
+}
+
+remoe_status validate_layer_desc(const remoe_layer_desc *d)
+{
+    remoe_status st = validate_route_desc(d);
+    if (st != REMOE_OK) return st;
+    if (d->inter < 1) return fail(REMOE_E_INVALID_ARG, "inter %d must be positive", d->inter);
+    if (d->shared_inter < 0) return fail(REMOE_E_INVALID_ARG, "shared_inter %d is negative", d->shared_inter);
+    if (d->shared_gate != 0 && d->shared_gate != 1)
+        return fail(REMOE_E_INVALID_ARG, "shared_gate must be 0 or 1");
+    if (d->shared_gate && d->shared_inter == 0)
+        return fail(REMOE_E_INVALID_ARG, "shared_gate set without a shared expert");
+    if (d->dtype == REMOE_BF16) {
+        if (d->hidden % 128 != 0)
+            return fail(REMOE_E_UNSUPPORTED, "bf16 layers need hidden %% 128 == 0 (got %d)", d->hidden);
+        if (d->inter % 64 != 0 || d->shared_inter % 64 != 0)
+            return fail(REMOE_E_UNSUPPORTED, "bf16 layers need inter and shared_inter %% 64 == 0 (got %d, %d)",
+                        d->inter, d->shared_inter);
+    }
+    return REMOE_OK;
+}
+
+// Workspace carving, shared by remoe_workspace_bytes and moe_forward.
+struct Workspace {
+    size_t total = 0;
+    PermuteBuffers pb{};
+    void *hbuf = nullptr;     // [T*K, I]            SwiGLU activations of the routed experts
+    void *hsbuf = nullptr;    // [T, I_s]            SwiGLU activations of the shared expert
+    void *rows = nullptr;     // [T*K (+T), H]       weighted per-(token, expert) outputs, then shared rows
+    int max_tiles = 0;
+};
+
+template <typename P> void carve(char *base, size_t &off, P *&ptr, size_t bytes)
+{
+    off = align_up(off, 256);
+    ptr = base ? reinterpret_cast<P *>(base + off) : nullptr;
+    off += bytes;
+}
+
+Workspace layout(const remoe_layer_desc *d, int64_t T, void *base_v)
+{
+    Workspace w;
+    char *base = static_cast<char *>(base_v);
+    const size_t es = d->dtype == REMOE_F32 ? 4 : 2;
+    const int64_t pairs = T * d->top_k;
+    const int64_t n_blk = ceil_div(T, permute_tokens_per_block());
+    w.max_tiles = (int)(ceil_div(pairs, gemm_tile_m()) + d->n_experts);
+    size_t off = 0;
+    carve(base, off, w.pb.blk_hist, sizeof(int32_t) * 2 * n_blk * d->n_experts);
+    carve(base, off, w.pb.offsets, sizeof(int32_t) * (d->n_experts + 1));
+    carve(base, off, w.pb.tile_expert, sizeof(int32_t) * w.max_tiles);
+    carve(base, off, w.pb.tile_row0, sizeof(int32_t) * w.max_tiles);
+    carve(base, off, w.pb.tile_rows, sizeof(int32_t) * w.max_tiles);
+    carve(base, off, w.pb.n_tiles, sizeof(int32_t));
+    carve(base, off, w.pb.pair_slot, sizeof(int32_t) * pairs);
+    carve(base, off, w.pb.slot_token, sizeof(int32_t) * pairs);
+    carve(base, off, w.pb.slot_w, sizeof(float) * pairs);
+    carve(base, off, w.hbuf, es * pairs * d->inter);
+    carve(base, off, w.hsbuf, es * T * d->shared_inter);
+    carve(base, off, w.rows, es * (pairs + (d->shared_inter ? T : 0)) * d->hidden);
+    w.total = align_up(off, 256);
+    return w;
+}
+
+}  // namespace
+}  // namespace remoe
+
+using namespace remoe;
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+int32_t remoe_version(void) { return 100; }
+
+const char *remoe_last_error(void) { return g_err; }
+
+size_t remoe_workspace_bytes(const remoe_layer_desc *desc, int64_t n_tokens)
+{
+    if (validate_layer_desc(desc) != REMOE_OK) return 0;
+    if (n_tokens < 0 || n_tokens > MAX_TOKENS) {
+        set_error("n_tokens %lld outside 0..%lld", (long long)n_tokens, (long long)MAX_TOKENS);
+        return 0;
+    }
+    return layout(desc, n_tokens, nullptr).total;
+}
+
+remoe_status moe_route(const remoe_layer_desc *desc, const void *x, int64_t n_tokens,
+                       const float *w_router, int32_t *out_idx, float *out_w, float *out_margin,
+                       float *out_probs, void *stream)
+{
+    remoe_status st = validate_route_desc(desc);
+    if (st != REMOE_OK) return st;
+    if (n_tokens < 0 || n_tokens > MAX_TOKENS)
+        return fail(REMOE_E_INVALID_ARG, "n_tokens %lld outside 0..%lld", (long long)n_tokens, (long long)MAX_TOKENS);
+    if (n_tokens == 0) return REMOE_OK;
+    if (!x || !w_router || !out_idx || !out_w)
+        return fail(REMOE_E_INVALID_ARG, "x, w_router, out_idx and out_w must not be NULL");
+    if (((uintptr_t)x | (uintptr_t)w_router) & 15)
+        return fail(REMOE_E_INVALID_ARG, "x and w_router must be 16-byte aligned");
+    return launch_route(x, desc->dtype, n_tokens, desc->hidden, w_router, desc->n_experts, desc->top_k,
+                        desc->renorm, out_idx, out_w, out_margin, out_probs, static_cast<hipStream_t>(stream));
+}
+
+remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_tokens,
+                         const float *w_router, const void *w_gate, const void *w_up,
+                         const void *w_down, const void *ws_gate, const void *ws_up,
+                         const void *ws_down, const float *ws_scale, void *y, int32_t *out_idx,
+                         float *out_w, void *workspace, size_t workspace_bytes, void *stream_v)
+{
+    remoe_status st = validate_layer_desc(desc);
+    if (st != REMOE_OK) return st;
+    const int64_t T = n_tokens;
+    if (T < 0 || T > MAX_TOKENS)
+        return fail(REMOE_E_INVALID_ARG, "n_tokens %lld outside 0..%lld", (long long)T, (long long)MAX_TOKENS);
+    if (T == 0) return REMOE_OK;
+    if (!x || !w_router || !w_gate || !w_up || !w_down || !y || !out_idx || !out_w)
+        return fail(REMOE_E_INVALID_ARG, "a required pointer is NULL");
+    if (desc->shared_inter > 0 && (!ws_gate || !ws_up || !ws_down))
+        return fail(REMOE_E_INVALID_ARG, "shared_inter > 0 but a shared-expert matrix is NULL");
+    if (desc->shared_gate && !ws_scale)
+        return fail(REMOE_E_INVALID_ARG, "shared_gate set but ws_scale is NULL");
+    const uintptr_t all = (uintptr_t)x | (uintptr_t)w_router | (uintptr_t)w_gate | (uintptr_t)w_up |
+                          (uintptr_t)w_down | (uintptr_t)ws_gate | (uintptr_t)ws_up |
+                          (uintptr_t)ws_down | (uintptr_t)ws_scale | (uintptr_t)y;
+    if (all & 15) return fail(REMOE_E_INVALID_ARG, "tensors must be 16-byte aligned");
+    if (!workspace || ((uintptr_t)workspace & 255))
+        return fail(REMOE_E_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+    const Workspace ws = layout(desc, T, workspace);
+    if (workspace_bytes < ws.total)
+        return fail(REMOE_E_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, ws.total);
+
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const int H = desc->hidden, I = desc->inter, Is = desc->shared_inter, K = desc->top_k, N = desc->n_experts;
+    const bool f32 = desc->dtype == REMOE_F32;
+    auto gemm = [&](int mode, const GroupedGemmArgs &g) {
+        return f32 ? launch_grouped_gemm_f32(mode, g, stream) : launch_grouped_gemm_bf16(mode, g, stream);
+    };
+
+    // 1. router: logits, top-k, softmax weights
+    st = launch_route(x, desc->dtype, T, H, w_router, N, K, desc->renorm, out_idx, out_w, nullptr, nullptr, stream);
+    if (st != REMOE_OK) return st;
+    // 2. sort (token, j) pairs by expert; build the GEMM tile list
+    st = launch_permute(out_idx, out_w, T, K, N, gemm_tile_m(), ws.max_tiles, ws.pb, stream);
+    if (st != REMOE_OK) return st;
+    // 3. routed experts: gate/up + SwiGLU, then down projection scaled by the gate weight
+    GroupedGemmArgs g{};
+    g.a = x; g.lda = H; g.row_gather = ws.pb.slot_token;
+    g.b0 = w_gate; g.b1 = w_up; g.k_dim = H; g.n_out = I;
+    g.tile_expert = ws.pb.tile_expert; g.tile_row0 = ws.pb.tile_row0; g.tile_rows = ws.pb.tile_rows;
+    g.n_tiles = ws.pb.n_tiles; g.max_tiles = ws.max_tiles;
+    g.c = ws.hbuf; g.ldc = I; g.c_row_offset = 0;
+    st = gemm(0, g);
+    if (st != REMOE_OK) return st;
+    g.a = ws.hbuf; g.lda = I; g.row_gather = nullptr;
+    g.b0 = w_down; g.b1 = nullptr; g.k_dim = I; g.n_out = H;
+    g.row_scale = ws.pb.slot_w; g.c = ws.rows; g.ldc = H;
+    st = gemm(1, g);
+    if (st != REMOE_OK) return st;
+    // 4. shared expert (dense, one group): rows T*K .. T*K+T-1 of the row buffer
+    if (Is > 0) {
+        GroupedGemmArgs s{};
+        s.a = x; s.lda = H; s.b0 = ws_gate; s.b1 = ws_up; s.k_dim = H; s.n_out = Is;
+        s.dense_rows = T; s.max_tiles = (int)ceil_div(T, gemm_tile_m());
+        s.c = ws.hsbuf; s.ldc = Is;
+        st = gemm(0, s);
+        if (st != REMOE_OK) return st;
+        s.a = ws.hsbuf; s.lda = Is; s.b0 = ws_down; s.b1 = nullptr; s.k_dim = Is; s.n_out = H;
+        s.c = ws.rows; s.ldc = H; s.c_row_offset = T * K;
+        st = gemm(1, s);
+        if (st != REMOE_OK) return st;
+    }
+    // 5. combine the K (+1) rows of every token
+    return launch_combine(desc->dtype, ws.rows, ws.pb.pair_slot, T, K, H, T * K, Is > 0, x,
+                          desc->shared_gate ? ws_scale : nullptr, y, stream);
+}
+
+static remoe_status validate_trace(const int32_t *idx, int64_t n_seq, int64_t n_steps, int32_t top_k,
+                                   int32_t n_experts)
+{
+    if (n_seq < 0 || n_steps < 0) return fail(REMOE_E_INVALID_ARG, "negative trace dimensions");
+    if (n_seq > 0x7FFFFFFF) return fail(REMOE_E_INVALID_ARG, "n_seq %lld too large", (long long)n_seq);
+    if (n_experts < 1 || n_experts > MAX_EXPERTS)
+        return fail(REMOE_E_INVALID_ARG, "n_experts %d outside 1..%d", n_experts, MAX_EXPERTS);
+    if (top_k < 1 || top_k > 64) return fail(REMOE_E_INVALID_ARG, "top_k %d outside 1..64", top_k);
+    if (n_seq > 0 && n_steps > 0 && !idx) return fail(REMOE_E_INVALID_ARG, "idx is NULL");
+    return REMOE_OK;
+}
+
+remoe_status trace_reuse(const int32_t *idx, int64_t n_seq, int64_t n_steps, int32_t top_k,
+                         int32_t n_experts, uint8_t *out_overlap, uint64_t *out_sum, void *stream)
+{
+    remoe_status st = validate_trace(idx, n_seq, n_steps, top_k, n_experts);
+    if (st != REMOE_OK) return st;
+    if (n_seq == 0) return REMOE_OK;
+    if (!out_sum || (n_steps > 0 && !out_overlap))
+        return fail(REMOE_E_INVALID_ARG, "out_overlap and out_sum must not be NULL");
+    return launch_trace_reuse(idx, n_seq, n_steps, top_k, n_experts, out_overlap, out_sum,
+                              static_cast<hipStream_t>(stream));
+}
+
+remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps, int32_t top_k,
+                          int32_t n_experts, int32_t capacity, uint64_t expert_bytes, int64_t step0,
+                          uint32_t *state, uint8_t *out_miss, uint64_t *out_total_miss,
+                          uint64_t *out_bytes, void *stream)
+{
+    if (capacity < 1) return fail(REMOE_E_INVALID_ARG, "capacity %d must be at least 1", capacity);
+    if (step0 < 0 || n_steps < 0 || step0 + n_steps >= (1 << 24))
+        return fail(REMOE_E_INVALID_ARG, "step0 + n_steps = %lld must stay in 0..2^24-1", (long long)(step0 + n_steps));
+    remoe_status st = validate_trace(idx, n_seq, n_steps, top_k, n_experts);
+    if (st != REMOE_OK) return st;
+    if (n_seq == 0) return REMOE_OK;
+    if (!out_total_miss || !out_bytes || (n_steps > 0 && !out_miss))
+        return fail(REMOE_E_INVALID_ARG, "out_miss, out_total_miss and out_bytes must not be NULL");
+    return launch_lru(idx, n_seq, n_steps, top_k, n_experts, capacity, expert_bytes, step0, state, out_miss,
+                      out_total_miss, out_bytes, static_cast<hipStream_t>(stream));
+}
+
+#pragma GCC visibility pop
+}  // extern "C"
