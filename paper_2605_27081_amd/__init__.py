@@ -12,7 +12,10 @@ from .binding import (  # noqa: F401
     lru_simulate,
     moe_forward,
     moe_route,
+    PROF_KINDS,
     remoe_last_error,
+    remoe_profile_enable,
+    remoe_profile_read,
     remoe_version,
     remoe_workspace_bytes,
     trace_reuse,

@@ -65,6 +65,10 @@ def load_library() -> ctypes.CDLL:
     lib.trace_reuse.argtypes = [P, I64, I64, I32, I32, P, P, P]
     lib.lru_simulate.restype = ctypes.c_int
     lib.lru_simulate.argtypes = [P, I64, I64, I32, I32, I32, U64, I64, P, P, P, P, P]
+    lib.remoe_profile_enable.restype = ctypes.c_int
+    lib.remoe_profile_enable.argtypes = [I32]
+    lib.remoe_profile_read.restype = ctypes.c_int
+    lib.remoe_profile_read.argtypes = [I32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(I64), I32]
     _lib = lib
     return lib
 
@@ -94,6 +98,21 @@ def remoe_version() -> int:
 
 def remoe_last_error() -> str:
     return load_library().remoe_last_error().decode()
+
+
+PROF_KINDS = ("route", "permute", "gate_up", "down", "shared_gate_up", "shared_down", "combine",
+              "trace_reuse", "lru", "decode")
+
+
+def remoe_profile_enable(on: bool) -> None:
+    _check(load_library().remoe_profile_enable(int(bool(on))))
+
+
+def remoe_profile_read(kind: int, reset: bool = True):
+    """(total milliseconds, launches) of one kernel kind; synchronise the device first."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+    _check(load_library().remoe_profile_read(kind, ctypes.byref(ms), ctypes.byref(n), int(bool(reset))))
+    return ms.value, n.value
 
 
 def remoe_workspace_bytes(desc: LayerDesc, n_tokens: int) -> int:

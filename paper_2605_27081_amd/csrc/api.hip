@@ -2,6 +2,10 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <mutex>
+#include <utility>
+#include <vector>
+
 #include "common.h"
 
 namespace remoe {
@@ -30,6 +34,51 @@ remoe_status check_hip(hipError_t e, const char *what)
     if (e == hipSuccess) return REMOE_OK;
     return fail(REMOE_E_HIP, "%s: %s", what, hipGetErrorString(e));
 }
+
+// ---- optional per-kernel timing (benchmarks only) --------------------------------------------
+// When enabled, every kernel group an entry point launches is bracketed by a pair of HIP events on
+// the caller's stream; remoe_profile_read sums the elapsed times per kind.  Off by default: the
+// entry points then record nothing.
+namespace {
+
+struct ProfRecord { int kind; hipEvent_t start, stop; };
+std::mutex g_prof_mutex;
+bool g_prof_on = false;
+std::vector<ProfRecord> g_prof_used;
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_free;
+
+class ProfScope {
+public:
+    ProfScope(int kind, hipStream_t stream) : stream_(stream)
+    {
+        std::lock_guard<std::mutex> lock(g_prof_mutex);
+        if (!g_prof_on) return;
+        ProfRecord r{kind, nullptr, nullptr};
+        if (!g_prof_free.empty()) {
+            r.start = g_prof_free.back().first;
+            r.stop = g_prof_free.back().second;
+            g_prof_free.pop_back();
+        } else if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) {
+            return;
+        }
+        if (hipEventRecord(r.start, stream_) != hipSuccess) return;
+        rec_ = r;
+        active_ = true;
+    }
+    ~ProfScope()
+    {
+        if (!active_) return;
+        std::lock_guard<std::mutex> lock(g_prof_mutex);
+        (void)hipEventRecord(rec_.stop, stream_);
+        g_prof_used.push_back(rec_);
+    }
+private:
+    hipStream_t stream_;
+    ProfRecord rec_{};
+    bool active_ = false;
+};
+
+}  // namespace
 
 namespace {
 
@@ -126,6 +175,40 @@ int32_t remoe_version(void) { return 100; }
 
 const char *remoe_last_error(void) { return g_err; }
 
+remoe_status remoe_profile_enable(int32_t on)
+{
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    g_prof_on = on != 0;
+    return REMOE_OK;
+}
+
+remoe_status remoe_profile_read(int32_t kind, double *total_ms, int64_t *launches, int32_t reset)
+{
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (kind < 0 || kind >= REMOE_PROF_KINDS) return fail(REMOE_E_INVALID_ARG, "profile kind %d out of range", kind);
+    double sum = 0.0;
+    int64_t n = 0;
+    for (const ProfRecord &r : g_prof_used) {
+        if (r.kind != kind) continue;
+        float ms = 0.f;
+        hipError_t e = hipEventElapsedTime(&ms, r.start, r.stop);
+        if (e != hipSuccess) return check_hip(e, "hipEventElapsedTime (synchronise the stream before reading)");
+        sum += ms;
+        ++n;
+    }
+    if (total_ms) *total_ms = sum;
+    if (launches) *launches = n;
+    if (reset) {
+        std::vector<ProfRecord> keep;
+        for (const ProfRecord &r : g_prof_used) {
+            if (r.kind == kind) g_prof_free.emplace_back(r.start, r.stop);
+            else keep.push_back(r);
+        }
+        g_prof_used.swap(keep);
+    }
+    return REMOE_OK;
+}
+
 size_t remoe_workspace_bytes(const remoe_layer_desc *desc, int64_t n_tokens)
 {
     if (validate_layer_desc(desc) != REMOE_OK) return 0;
@@ -149,6 +232,7 @@ remoe_status moe_route(const remoe_layer_desc *desc, const void *x, int64_t n_to
         return fail(REMOE_E_INVALID_ARG, "x, w_router, out_idx and out_w must not be NULL");
     if (((uintptr_t)x | (uintptr_t)w_router) & 15)
         return fail(REMOE_E_INVALID_ARG, "x and w_router must be 16-byte aligned");
+    ProfScope prof(REMOE_PROF_ROUTE, static_cast<hipStream_t>(stream));
     return launch_route(x, desc->dtype, n_tokens, desc->hidden, w_router, desc->n_experts, desc->top_k,
                         desc->renorm, out_idx, out_w, out_margin, out_probs, static_cast<hipStream_t>(stream));
 }
@@ -189,10 +273,16 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
     };
 
     // 1. router: logits, top-k, softmax weights
-    st = launch_route(x, desc->dtype, T, H, w_router, N, K, desc->renorm, out_idx, out_w, nullptr, nullptr, stream);
+    {
+        ProfScope prof(REMOE_PROF_ROUTE, stream);
+        st = launch_route(x, desc->dtype, T, H, w_router, N, K, desc->renorm, out_idx, out_w, nullptr, nullptr, stream);
+    }
     if (st != REMOE_OK) return st;
     // 2. sort (token, j) pairs by expert; build the GEMM tile list
-    st = launch_permute(out_idx, out_w, T, K, N, gemm_tile_m(), ws.max_tiles, ws.pb, stream);
+    {
+        ProfScope prof(REMOE_PROF_PERMUTE, stream);
+        st = launch_permute(out_idx, out_w, T, K, N, gemm_tile_m(), ws.max_tiles, ws.pb, stream);
+    }
     if (st != REMOE_OK) return st;
     // 3. routed experts: gate/up + SwiGLU, then down projection scaled by the gate weight
     GroupedGemmArgs g{};
@@ -201,12 +291,18 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
     g.tile_expert = ws.pb.tile_expert; g.tile_row0 = ws.pb.tile_row0; g.tile_rows = ws.pb.tile_rows;
     g.n_tiles = ws.pb.n_tiles; g.max_tiles = ws.max_tiles;
     g.c = ws.hbuf; g.ldc = I; g.c_row_offset = 0;
-    st = gemm(0, g);
+    {
+        ProfScope prof(REMOE_PROF_GATE_UP, stream);
+        st = gemm(0, g);
+    }
     if (st != REMOE_OK) return st;
     g.a = ws.hbuf; g.lda = I; g.row_gather = nullptr;
     g.b0 = w_down; g.b1 = nullptr; g.k_dim = I; g.n_out = H;
     g.row_scale = ws.pb.slot_w; g.c = ws.rows; g.ldc = H;
-    st = gemm(1, g);
+    {
+        ProfScope prof(REMOE_PROF_DOWN, stream);
+        st = gemm(1, g);
+    }
     if (st != REMOE_OK) return st;
     // 4. shared expert (dense, one group): rows T*K .. T*K+T-1 of the row buffer
     if (Is > 0) {
@@ -214,14 +310,21 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
         s.a = x; s.lda = H; s.b0 = ws_gate; s.b1 = ws_up; s.k_dim = H; s.n_out = Is;
         s.dense_rows = T; s.max_tiles = (int)ceil_div(T, gemm_tile_m());
         s.c = ws.hsbuf; s.ldc = Is;
-        st = gemm(0, s);
+        {
+            ProfScope prof(REMOE_PROF_SHARED_GATE_UP, stream);
+            st = gemm(0, s);
+        }
         if (st != REMOE_OK) return st;
         s.a = ws.hsbuf; s.lda = Is; s.b0 = ws_down; s.b1 = nullptr; s.k_dim = Is; s.n_out = H;
         s.c = ws.rows; s.ldc = H; s.c_row_offset = T * K;
-        st = gemm(1, s);
+        {
+            ProfScope prof(REMOE_PROF_SHARED_DOWN, stream);
+            st = gemm(1, s);
+        }
         if (st != REMOE_OK) return st;
     }
     // 5. combine the K (+1) rows of every token
+    ProfScope prof(REMOE_PROF_COMBINE, stream);
     return launch_combine(desc->dtype, ws.rows, ws.pb.pair_slot, T, K, H, T * K, Is > 0, x,
                           desc->shared_gate ? ws_scale : nullptr, y, stream);
 }
@@ -246,6 +349,7 @@ remoe_status trace_reuse(const int32_t *idx, int64_t n_seq, int64_t n_steps, int
     if (n_seq == 0) return REMOE_OK;
     if (!out_sum || (n_steps > 0 && !out_overlap))
         return fail(REMOE_E_INVALID_ARG, "out_overlap and out_sum must not be NULL");
+    ProfScope prof(REMOE_PROF_TRACE_REUSE, static_cast<hipStream_t>(stream));
     return launch_trace_reuse(idx, n_seq, n_steps, top_k, n_experts, out_overlap, out_sum,
                               static_cast<hipStream_t>(stream));
 }
@@ -263,6 +367,7 @@ remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps, in
     if (n_seq == 0) return REMOE_OK;
     if (!out_total_miss || !out_bytes || (n_steps > 0 && !out_miss))
         return fail(REMOE_E_INVALID_ARG, "out_miss, out_total_miss and out_bytes must not be NULL");
+    ProfScope prof(REMOE_PROF_LRU, static_cast<hipStream_t>(stream));
     return launch_lru(idx, n_seq, n_steps, top_k, n_experts, capacity, expert_bytes, step0, state, out_miss,
                       out_total_miss, out_bytes, static_cast<hipStream_t>(stream));
 }

@@ -110,19 +110,21 @@ def ar1_hidden_states(seed: int, n_seq: int, seq_len: int, hidden: int, rho: flo
     key = stream_key(seed, TENSOR_IDS["x"], 0, stream)
     out = torch.empty(n_seq, seq_len, hidden, dtype=dtype, device=device)
     c = math.sqrt(1.0 - rho * rho)
-    for s in range(n_seq):
-        eps = standard_normal(key, s * seq_len * hidden, seq_len * hidden, device)
-        eps = eps.reshape(seq_len, hidden)
-        if rho == 0.0:
-            out[s] = eps.to(dtype)
-            continue
-        xs = torch.empty_like(eps)
-        prev = eps[0]
-        xs[0] = prev
-        for t in range(1, seq_len):
-            prev = rho * prev + c * eps[t]
-            xs[t] = prev
-        out[s] = xs.to(dtype)
+    per_seq = seq_len * hidden
+    group = max(1, min(n_seq, (1 << 27) // max(per_seq, 1)))   # sequences advanced together
+    for s0 in range(0, n_seq, group):
+        g = min(group, n_seq - s0)
+        eps = torch.empty(g, seq_len, hidden, dtype=torch.float64, device=device)
+        flat = eps.view(-1)
+        for a in range(0, g * per_seq, _CHUNK):
+            m = min(_CHUNK, g * per_seq - a)
+            flat[a:a + m] = standard_normal(key, s0 * per_seq + a, m, device)
+        if rho != 0.0:
+            prev = eps[:, 0].clone()
+            for t in range(1, seq_len):
+                prev = rho * prev + c * eps[:, t]
+                eps[:, t] = prev
+        out[s0:s0 + g] = eps.to(dtype)
     return out
 
 
