@@ -11,9 +11,10 @@
 // Tiling: 128 x 128 x 64 per workgroup of 4 wavefronts (2 x 2, 64 x 64 each = 2 x 2 MFMA tiles).
 // In mode 0 the 128 B-rows are 64 gate rows + the 64 matching up rows, so a lane holds g and u of
 // the same (m, n) in two accumulators and applies SwiGLU in registers.  LDS rows are 8 chunks of
-// 16 bytes, chunk c of row r stored at c ^ (r & 7): conflict-free for the row-per-lane fragment
-// reads and for the 8-lanes-per-row global->LDS copies.  Global loads for tile k+1 are issued
-// before the MFMAs of tile k and written to the other LDS stage afterwards (one barrier per step).
+// 16 bytes in an XOR-swizzled layout (lds_slot) that keeps the row-per-lane fragment reads and the
+// 8-lanes-per-row global->LDS copies free of bank conflicts.  Global loads run two tiles ahead of the
+// MFMAs through two register sets and are copied to the other LDS stage after the MFMAs of the
+// current tile (one barrier per step).
 //
 // Rows of A are gathered through slot -> token, so no permuted copy of x is ever materialised.
 // The tile list (expert, first slot, valid rows) comes from the permute step and lives in device
@@ -30,6 +31,13 @@ namespace {
 constexpr int GM_BM = 128;
 constexpr int GM_BK = 64;
 constexpr int GM_STAGE = GM_BM * 8;  // 16-byte chunks per operand per stage
+
+// LDS tile layout: rows of 8 chunks (16 bytes each).  Chunk c of row r lives in row slot
+// r ^ ((r >> 3) & 1) at chunk position c ^ (r & 7).  A fragment read has lane i on row base+i with
+// one logical chunk: any 8 consecutive lanes then hit 8 different chunk positions (all 32 banks of
+// a 128-byte period), and rows r, r+8 land in row slots of opposite parity, so 16 consecutive
+// lanes also cover a full 256-byte period.  The 8-lanes-per-row copies into LDS stay conflict-free.
+__device__ __forceinline__ int lds_slot(int r, int c) { return ((r ^ ((r >> 3) & 1)) << 3) + (c ^ (r & 7)); }
 
 struct KArgs {
     const bf16_t *a;
@@ -105,17 +113,50 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_bf16_kernel(const KArgs p
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-    u32x4_t ga[4], gb[4];
-#define GM_LOAD_GLOBAL(k0)                                                              \
+    // Two register sets stage the global loads: while tile k is multiplied out of LDS, tile k+1 is
+    // already in (or on its way to) one set and the loads of tile k+2 are issued into the other,
+    // so every load has more than a full MFMA phase to arrive before it is copied into LDS.
+    u32x4_t ga0[4], gb0[4], ga1[4], gb1[4];
+#define GM_LOAD_GLOBAL(ga, gb, k0)                                                      \
     _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                      \
-        ga[i] = *reinterpret_cast<const u32x4_t *>(ap[i] + (k0));                          \
-        gb[i] = *reinterpret_cast<const u32x4_t *>(bp[i] + (k0));                          \
-    }
-#define GM_STORE_LDS(stage)                                                             \
+        ga[i] = *reinterpret_cast<const u32x4_t *>(ap[i] + (k0));                        \
+        gb[i] = *reinterpret_cast<const u32x4_t *>(bp[i] + (k0));                        \
+    }                                                                                   \
+    __builtin_amdgcn_sched_barrier(0);   /* keep the loads ahead of the MFMA phase */
+#define GM_STORE_LDS(ga, gb, stage)                                                     \
     _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                      \
         const int r_ = lr + 32 * i;                                                     \
-        lds_a[stage][r_ * 8 + (lc ^ (r_ & 7))] = ga[i];                                 \
-        lds_b[stage][r_ * 8 + (lc ^ (r_ & 7))] = gb[i];                                 \
+        lds_a[stage][lds_slot(r_, lc)] = ga[i];                                         \
+        lds_b[stage][lds_slot(r_, lc)] = gb[i];                                         \
+    }
+    // Fragments are double-buffered in registers: the LDS reads of k-step ks+1 are issued before
+    // the four MFMAs of k-step ks, so their latency hides behind matrix-core work.
+#define GM_READ_FRAGS(stage, ks, fa, fb)                                                \
+    _Pragma("unroll") for (int mi = 0; mi < 2; ++mi)                                     \
+        fa[mi] = *reinterpret_cast<const bf16x8_t *>(&lds_a[stage][lds_slot(a_row[mi], 2 * (ks) + lh)]); \
+    _Pragma("unroll") for (int ni = 0; ni < 2; ++ni)                                     \
+        fb[ni] = *reinterpret_cast<const bf16x8_t *>(&lds_b[stage][lds_slot(b_row[ni], 2 * (ks) + lh)]);
+#define GM_MFMA(fa, fb)                                                                 \
+    _Pragma("unroll") for (int mi = 0; mi < 2; ++mi)                                     \
+        _Pragma("unroll") for (int ni = 0; ni < 2; ++ni)                                 \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+#define GM_COMPUTE(stage)                                                               \
+    {                                                                                   \
+        bf16x8_t fa0[2], fb0[2], fa1[2], fb1[2];                                        \
+        GM_READ_FRAGS(stage, 0, fa0, fb0)                                               \
+        GM_READ_FRAGS(stage, 1, fa1, fb1)                                               \
+        __builtin_amdgcn_sched_barrier(0);                                              \
+        GM_MFMA(fa0, fb0)                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                              \
+        GM_READ_FRAGS(stage, 2, fa0, fb0)                                               \
+        __builtin_amdgcn_sched_barrier(0);                                              \
+        GM_MFMA(fa1, fb1)                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                              \
+        GM_READ_FRAGS(stage, 3, fa1, fb1)                                               \
+        __builtin_amdgcn_sched_barrier(0);                                              \
+        GM_MFMA(fa0, fb0)                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                              \
+        GM_MFMA(fa1, fb1)                                                               \
     }
 
     int a_row[2], b_row[2];
@@ -129,30 +170,33 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_bf16_kernel(const KArgs p
         b_row[1] = wn * 64 + 32 + li;
     }
 
-    const int nk = p.k_dim / GM_BK;
-    GM_LOAD_GLOBAL(0)
-    GM_STORE_LDS(0)
+    const int nk = p.k_dim / GM_BK;   // >= 1
+    GM_LOAD_GLOBAL(ga0, gb0, 0)
+    if (nk > 1) { GM_LOAD_GLOBAL(ga1, gb1, GM_BK) }
+    GM_STORE_LDS(ga0, gb0, 0)
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) { GM_LOAD_GLOBAL((kt + 1) * GM_BK) }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int cc = (2 * ks + lh) ^ (li & 7);
-            bf16x8_t af[2], bfr[2];
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-                af[mi] = *reinterpret_cast<const bf16x8_t *>(&lds_a[cur][a_row[mi] * 8 + cc]);
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-                bfr[ni] = *reinterpret_cast<const bf16x8_t *>(&lds_b[cur][b_row[ni] * 8 + cc]);
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
-        }
-        if (kt + 1 < nk) { GM_STORE_LDS(cur ^ 1) }
+    // tile kt sits in LDS stage kt & 1; even kt: set 1 holds tile kt+1, set 0 is free (and vice versa).
+    // The steady-state loop issues its loads unconditionally, so the waits before the LDS copies
+    // cover only the older set; the last (up to three) tiles run through the guarded copy below.
+    int kt = 0;
+    for (; kt + 3 < nk; kt += 2) {
+        GM_LOAD_GLOBAL(ga0, gb0, (kt + 2) * GM_BK)
+        GM_COMPUTE(0)
+        GM_STORE_LDS(ga1, gb1, 1)
+        __syncthreads();
+        GM_LOAD_GLOBAL(ga1, gb1, (kt + 3) * GM_BK)
+        GM_COMPUTE(1)
+        GM_STORE_LDS(ga0, gb0, 0)
+        __syncthreads();
+    }
+    for (; kt < nk; kt += 2) {
+        if (kt + 2 < nk) { GM_LOAD_GLOBAL(ga0, gb0, (kt + 2) * GM_BK) }
+        GM_COMPUTE(0)
+        if (kt + 1 < nk) { GM_STORE_LDS(ga1, gb1, 1) }
+        __syncthreads();
+        if (kt + 1 >= nk) break;
+        GM_COMPUTE(1)
+        if (kt + 2 < nk) { GM_STORE_LDS(ga0, gb0, 0) }
         __syncthreads();
     }
 

@@ -15,9 +15,13 @@ namespace {
 constexpr int RT_BM = 128;  // tokens per workgroup
 constexpr int RT_BK = 32;   // reduction slice per LDS stage (fp32 elements)
 
-// LDS tiles hold rows of 32 floats = 8 chunks of 16 bytes; chunk c of row r lives at position
-// c ^ (r & 7) so that the 32 rows a half-wavefront reads at once spread over all banks.
-__device__ __forceinline__ int swz(int r, int c) { return r * RT_BK + ((c ^ (r & 7)) << 2); }
+// LDS tiles hold rows of 32 floats = 8 chunks of 16 bytes; chunk c of row r lives in row slot
+// r ^ ((r >> 3) & 1) at chunk position c ^ (r & 7), so that the rows a wavefront reads at once
+// spread over all banks whether 8 or 16 lanes are served per cycle.
+__device__ __forceinline__ int swz(int r, int c)
+{
+    return (r ^ ((r >> 3) & 1)) * RT_BK + ((c ^ (r & 7)) << 2);
+}
 
 template <typename XT> struct XLoad;
 
