@@ -286,7 +286,7 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
     if (st != REMOE_OK) return st;
     // 3. routed experts: gate/up + SwiGLU, then down projection scaled by the gate weight
     GroupedGemmArgs g{};
-    g.a = x; g.lda = H; g.row_gather = ws.pb.slot_token;
+    g.a = x; g.lda = H; g.a_rows = T; g.row_gather = ws.pb.slot_token;
     g.b0 = w_gate; g.b1 = w_up; g.k_dim = H; g.n_out = I;
     g.tile_expert = ws.pb.tile_expert; g.tile_row0 = ws.pb.tile_row0; g.tile_rows = ws.pb.tile_rows;
     g.n_tiles = ws.pb.n_tiles; g.max_tiles = ws.max_tiles;
@@ -296,7 +296,7 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
         st = gemm(0, g);
     }
     if (st != REMOE_OK) return st;
-    g.a = ws.hbuf; g.lda = I; g.row_gather = nullptr;
+    g.a = ws.hbuf; g.lda = I; g.a_rows = T * K; g.row_gather = nullptr;
     g.b0 = w_down; g.b1 = nullptr; g.k_dim = I; g.n_out = H;
     g.row_scale = ws.pb.slot_w; g.c = ws.rows; g.ldc = H;
     {
@@ -307,7 +307,7 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
     // 4. shared expert (dense, one group): rows T*K .. T*K+T-1 of the row buffer
     if (Is > 0) {
         GroupedGemmArgs s{};
-        s.a = x; s.lda = H; s.b0 = ws_gate; s.b1 = ws_up; s.k_dim = H; s.n_out = Is;
+        s.a = x; s.lda = H; s.a_rows = T; s.b0 = ws_gate; s.b1 = ws_up; s.k_dim = H; s.n_out = Is;
         s.dense_rows = T; s.max_tiles = (int)ceil_div(T, gemm_tile_m());
         s.c = ws.hsbuf; s.ldc = Is;
         {
@@ -315,7 +315,7 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
             st = gemm(0, s);
         }
         if (st != REMOE_OK) return st;
-        s.a = ws.hsbuf; s.lda = Is; s.b0 = ws_down; s.b1 = nullptr; s.k_dim = Is; s.n_out = H;
+        s.a = ws.hsbuf; s.lda = Is; s.a_rows = T; s.b0 = ws_down; s.b1 = nullptr; s.k_dim = Is; s.n_out = H;
         s.c = ws.rows; s.ldc = H; s.c_row_offset = T * K;
         {
             ProfScope prof(REMOE_PROF_SHARED_DOWN, stream);

@@ -70,8 +70,9 @@ remoe_status launch_permute(const int32_t *idx, const float *w, int64_t T, int K
 
 // Grouped expert GEMMs.  mode 0: gate/up + SwiGLU, mode 1: down projection scaled per row.
 struct GroupedGemmArgs {
-    const void *a;            // activations [rows, lda]
+    const void *a;            // activations [a_rows, lda]
     int64_t lda;
+    int64_t a_rows;           // rows of a (bounds the gathered row indices)
     const int32_t *row_gather;  // slot -> row of a, or NULL (row = slot)
     const void *b0;           // mode 0: W_gate, mode 1: W_down   [E, n_out, k_dim]
     const void *b1;           // mode 0: W_up

@@ -8,13 +8,16 @@
 // operands, which is exactly the per-lane operand layout of the 32x32x16 MFMA (8 consecutive k per
 // lane), so LDS fragments are single 16-byte reads.
 //
-// Tiling: 128 x 128 x 64 per workgroup of 4 wavefronts (2 x 2, 64 x 64 each = 2 x 2 MFMA tiles).
-// In mode 0 the 128 B-rows are 64 gate rows + the 64 matching up rows, so a lane holds g and u of
+// Tiling: one workgroup of 8 wavefronts (2 x 4) owns a 256 x 256 x 64 tile; a wavefront owns
+// 128 x 64 of it as 4 x 2 MFMA tiles (128 accumulator registers).  The large tile is what keeps the
+// kernel off the L2 -> CU bandwidth limit: each 64-deep slice costs 64 KB of loads for 8.4 MFLOP.
+// In mode 0 the 256 B-rows are 128 gate rows + the 128 matching up rows, so a lane holds g and u of
 // the same (m, n) in two accumulators and applies SwiGLU in registers.  LDS rows are 8 chunks of
 // 16 bytes in an XOR-swizzled layout (lds_slot) that keeps the row-per-lane fragment reads and the
-// 8-lanes-per-row global->LDS copies free of bank conflicts.  Global loads run two tiles ahead of the
-// MFMAs through two register sets and are copied to the other LDS stage after the MFMAs of the
-// current tile (one barrier per step).
+// global->LDS copies free of bank conflicts.  Slices move global -> LDS directly
+// (global_load_lds_dwordx4, no staging registers): the copy of slice k+1 into the other LDS stage is
+// issued before the MFMAs of slice k and has that whole MFMA phase to land (one barrier per slice);
+// MFMA fragments are double-buffered in registers so LDS latency hides behind matrix-core work.
 //
 // Rows of A are gathered through slot -> token, so no permuted copy of x is ever materialised.
 // The tile list (expert, first slot, valid rows) comes from the permute step and lives in device
@@ -28,9 +31,7 @@ namespace remoe {
 
 namespace {
 
-constexpr int GM_BM = 128;
 constexpr int GM_BK = 64;
-constexpr int GM_STAGE = GM_BM * 8;  // 16-byte chunks per operand per stage
 
 // LDS tile layout: rows of 8 chunks (16 bytes each).  Chunk c of row r lives in row slot
 // r ^ ((r >> 3) & 1) at chunk position c ^ (r & 7).  A fragment read has lane i on row base+i with
@@ -38,6 +39,18 @@ constexpr int GM_STAGE = GM_BM * 8;  // 16-byte chunks per operand per stage
 // a 128-byte period), and rows r, r+8 land in row slots of opposite parity, so 16 consecutive
 // lanes also cover a full 256-byte period.  The 8-lanes-per-row copies into LDS stay conflict-free.
 __device__ __forceinline__ int lds_slot(int r, int c) { return ((r ^ ((r >> 3) & 1)) << 3) + (c ^ (r & 7)); }
+
+// 64 lanes x 16 bytes, global -> LDS without passing through registers: lane l's 16 bytes land at
+// lds_base + 16 l (lds_base must be wave-uniform).  The builtin exists only in the device pass.
+__device__ __forceinline__ void copy16_to_lds(const void *gsrc, void *lds_base)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_global_load_lds(gsrc, lds_base, 16, 0, 0);
+#else
+    (void)gsrc;
+    (void)lds_base;
+#endif
+}
 
 struct KArgs {
     const bf16_t *a;
@@ -55,15 +68,24 @@ struct KArgs {
     int64_t c_row_offset;
 };
 
-template <int MODE>
-__global__ __launch_bounds__(256, 2) void grouped_gemm_bf16_kernel(const KArgs p)
+// WM x WN wavefronts, each owning TM x TN MFMA tiles of 32 x 32.
+template <int MODE, int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const KArgs p)
 {
-    constexpr int BN_OUT = (MODE == 0) ? 64 : 128;  // output columns per workgroup
-    __shared__ u32x4_t lds_a[2][GM_STAGE];
-    __shared__ u32x4_t lds_b[2][GM_STAGE];
+    static_assert(MODE == 1 || TN == 2, "mode 0 pairs one gate tile with one up tile per wavefront");
+    constexpr int THREADS = WM * WN * 64;
+    constexpr int BM = WM * TM * 32;           // rows of A per workgroup
+    constexpr int BN = WN * TN * 32;           // rows of B per workgroup
+    constexpr int BN_OUT = (MODE == 0) ? BN / 2 : BN;
+    constexpr int A_CH = BM * 8 / THREADS;     // 16-byte chunks each thread copies per slice
+    constexpr int B_CH = BN * 8 / THREADS;
+    // the two stages are separate arrays so that the compiler can tell a copy into one stage from
+    // the fragment reads of the other (no wait for the copy before those reads)
+    __shared__ u32x4_t lds_a0[BM * 8], lds_a1[BM * 8];
+    __shared__ u32x4_t lds_b0[BN * 8], lds_b1[BN * 8];
 
-    const int ntn = p.n_out / BN_OUT;
-    const int n_mt = p.tile_expert ? *p.n_tiles : (p.dense_rows + GM_BM - 1) / GM_BM;
+    const int ntn = (p.n_out + BN_OUT - 1) / BN_OUT;
+    const int n_mt = p.tile_expert ? *p.n_tiles : (p.dense_rows + BM - 1) / BM;
     const int nblk = n_mt * ntn;
     const int chunk = (nblk + 7) >> 3;
     const int q = blockIdx.x >> 3;
@@ -72,166 +94,174 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_bf16_kernel(const KArgs p
     if (logical >= nblk) return;
     const int mt = logical / ntn, nt = logical - mt * ntn;
 
-    int expert = 0, row0 = mt * GM_BM, rows = p.dense_rows - row0;
+    int expert = 0, row0 = mt * BM, rows = p.dense_rows - row0;
     if (p.tile_expert) {
         expert = p.tile_expert[mt];
         row0 = p.tile_row0[mt];
         rows = p.tile_rows[mt];
     }
-    if (rows > GM_BM) rows = GM_BM;
+    if (rows > BM) rows = BM;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lh = lane >> 5;
-    const int lc = tid & 7;   // 16-byte chunk this thread copies
-    const int lr = tid >> 3;  // first of its 4 rows (stride 32)
 
-    const bf16_t *ap[4];
-    const bf16_t *bp[4];
-    const int64_t estride = (int64_t)p.n_out * p.k_dim;
+    // Direct-to-LDS copies: one instruction moves 64 lanes x 16 bytes into 1 KB of contiguous LDS
+    // (lane l lands at base + 16 l), i.e. into 8 row slots x 8 chunk positions.  Each lane therefore
+    // inverts the swizzle of ITS landing slot to find which (row, chunk) of the tile to fetch.
+    // Wavefront w issues the copies of row-slot groups w, w + NWAVES, ...  Offsets are 32-bit byte
+    // offsets from wave-uniform bases: gathered rows index all of A (the launcher checks that A
+    // spans less than 4 GiB), contiguous rows are relative to the tile's first row, and B offsets
+    // stay inside one expert matrix.
+    constexpr int NWAVES = WM * WN;
+    uint32_t a_off[A_CH], b_off[B_CH];
+    const char *a_base = reinterpret_cast<const char *>(p.row_gather ? p.a : p.a + (int64_t)row0 * p.lda);
+    const char *b_base0 = reinterpret_cast<const char *>(p.b0 + (int64_t)expert * p.n_out * p.k_dim);
+    const char *b_base1 = (MODE == 0) ? reinterpret_cast<const char *>(p.b1 + (int64_t)expert * p.n_out * p.k_dim)
+                                      : b_base0;
+    const int land_rs = lane >> 3, land_cp = lane & 7;   // landing row slot (within the group), chunk position
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int r = lr + 32 * i;
-        int rr = r < rows ? r : rows - 1;
-        int64_t arow = row0 + rr;
-        if (p.row_gather) arow = p.row_gather[arow];
-        ap[i] = p.a + arow * p.lda + lc * 8;
-        if (MODE == 0) {
-            const bf16_t *base = (r < 64) ? p.b0 : p.b1;
-            bp[i] = base + expert * estride + (int64_t)(nt * 64 + (r & 63)) * p.k_dim + lc * 8;
-        } else {
-            bp[i] = p.b0 + expert * estride + (int64_t)(nt * 128 + r) * p.k_dim + lc * 8;
-        }
+    for (int i = 0; i < A_CH; ++i) {
+        const int rs = (wave + NWAVES * i) * 8 + land_rs;
+        const int r = rs ^ ((rs >> 3) & 1);
+        const int c = land_cp ^ (r & 7);
+        const int rr = r < rows ? r : rows - 1;
+        const int64_t arow = p.row_gather ? p.row_gather[row0 + rr] : rr;
+        a_off[i] = (uint32_t)((arow * p.lda + c * 8) * 2);
+    }
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) {
+        const int rs = (wave + NWAVES * i) * 8 + land_rs;
+        const int r = rs ^ ((rs >> 3) & 1);
+        const int c = land_cp ^ (r & 7);
+        int brow = (MODE == 0) ? nt * (BN / 2) + (r & (BN / 2 - 1)) : nt * BN + r;
+        if (brow >= p.n_out) brow = p.n_out - 1;   // ragged last n-tile: loads stay in bounds, stores are masked
+        b_off[i] = (uint32_t)(((int64_t)brow * p.k_dim + c * 8) * 2);
     }
 
-    floatx16_t acc[2][2];
+    floatx16_t acc[TM][TN];
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-    // Two register sets stage the global loads: while tile k is multiplied out of LDS, tile k+1 is
-    // already in (or on its way to) one set and the loads of tile k+2 are issued into the other,
-    // so every load has more than a full MFMA phase to arrive before it is copied into LDS.
-    u32x4_t ga0[4], gb0[4], ga1[4], gb1[4];
-#define GM_LOAD_GLOBAL(ga, gb, k0)                                                      \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                      \
-        ga[i] = *reinterpret_cast<const u32x4_t *>(ap[i] + (k0));                        \
-        gb[i] = *reinterpret_cast<const u32x4_t *>(bp[i] + (k0));                        \
-    }                                                                                   \
-    __builtin_amdgcn_sched_barrier(0);   /* keep the loads ahead of the MFMA phase */
-#define GM_STORE_LDS(ga, gb, stage)                                                     \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                      \
-        const int r_ = lr + 32 * i;                                                     \
-        lds_a[stage][lds_slot(r_, lc)] = ga[i];                                         \
-        lds_b[stage][lds_slot(r_, lc)] = gb[i];                                         \
-    }
-    // Fragments are double-buffered in registers: the LDS reads of k-step ks+1 are issued before
-    // the four MFMAs of k-step ks, so their latency hides behind matrix-core work.
-#define GM_READ_FRAGS(stage, ks, fa, fb)                                                \
-    _Pragma("unroll") for (int mi = 0; mi < 2; ++mi)                                     \
-        fa[mi] = *reinterpret_cast<const bf16x8_t *>(&lds_a[stage][lds_slot(a_row[mi], 2 * (ks) + lh)]); \
-    _Pragma("unroll") for (int ni = 0; ni < 2; ++ni)                                     \
-        fb[ni] = *reinterpret_cast<const bf16x8_t *>(&lds_b[stage][lds_slot(b_row[ni], 2 * (ks) + lh)]);
-#define GM_MFMA(fa, fb)                                                                 \
-    _Pragma("unroll") for (int mi = 0; mi < 2; ++mi)                                     \
-        _Pragma("unroll") for (int ni = 0; ni < 2; ++ni)                                 \
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
-#define GM_COMPUTE(stage)                                                               \
-    {                                                                                   \
-        bf16x8_t fa0[2], fb0[2], fa1[2], fb1[2];                                        \
-        GM_READ_FRAGS(stage, 0, fa0, fb0)                                               \
-        GM_READ_FRAGS(stage, 1, fa1, fb1)                                               \
-        __builtin_amdgcn_sched_barrier(0);                                              \
-        GM_MFMA(fa0, fb0)                                                               \
-        __builtin_amdgcn_sched_barrier(0);                                              \
-        GM_READ_FRAGS(stage, 2, fa0, fb0)                                               \
-        __builtin_amdgcn_sched_barrier(0);                                              \
-        GM_MFMA(fa1, fb1)                                                               \
-        __builtin_amdgcn_sched_barrier(0);                                              \
-        GM_READ_FRAGS(stage, 3, fa1, fb1)                                               \
-        __builtin_amdgcn_sched_barrier(0);                                              \
-        GM_MFMA(fa0, fb0)                                                               \
-        __builtin_amdgcn_sched_barrier(0);                                              \
-        GM_MFMA(fa1, fb1)                                                               \
-    }
+    // mode 0: row-slot groups below BN/2 rows hold gate rows, the others up rows (a group never straddles)
+#define GM_COPY_SLICE(la, lb, k0)                                                                   \
+    _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                                                 \
+        copy16_to_lds(a_base + a_off[i] + (k0) * 2, &la[(wave + NWAVES * i) * 64]);                 \
+    _Pragma("unroll") for (int i = 0; i < B_CH; ++i) {                                               \
+        const char *bb_ = (MODE == 0 && (wave + NWAVES * i) * 8 >= BN / 2) ? b_base1 : b_base0;     \
+        copy16_to_lds(bb_ + b_off[i] + (k0) * 2, &lb[(wave + NWAVES * i) * 64]);                    \
+    }                                                                                               \
+    __builtin_amdgcn_sched_barrier(0);   /* keep the copies ahead of the MFMA phase */
 
-    int a_row[2], b_row[2];
+    // fragment of k-step ks: row (tile base) + li, logical chunk 2 * ks + lh
+    int fr_idx[4];
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi) a_row[mi] = wm * 64 + mi * 32 + li;
-    if (MODE == 0) {
-        b_row[0] = wn * 32 + li;
-        b_row[1] = 64 + wn * 32 + li;
-    } else {
-        b_row[0] = wn * 64 + li;
-        b_row[1] = wn * 64 + 32 + li;
+    for (int ks = 0; ks < 4; ++ks) fr_idx[ks] = lds_slot(li, 2 * ks + lh);
+    const int a_tile0 = wm * TM * 32 * 8;                                       // + mi * 256
+    const int b_tile0 = (MODE == 0) ? wn * 32 * 8 : wn * TN * 32 * 8;            // + ni * B_TILE_STEP
+    constexpr int B_TILE_STEP = (MODE == 0) ? (BN / 2) * 8 : 32 * 8;
+
+#define GM_READ_FRAGS(la, lb, ks, fa, fb)                                                           \
+    _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
+        fa[mi] = *reinterpret_cast<const bf16x8_t *>(&la[a_tile0 + fr_idx[ks] + mi * 256]);          \
+    _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                                \
+        fb[ni] = *reinterpret_cast<const bf16x8_t *>(&lb[b_tile0 + fr_idx[ks] + ni * B_TILE_STEP]);
+#define GM_MFMA(fa, fb)                                                                             \
+    _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
+        _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                            \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+    // k-steps of one slice: fragments of step ks+1 are read while the MFMAs of step ks run
+#define GM_COMPUTE(la, lb)                                                                          \
+    {                                                                                               \
+        bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];                                                \
+        GM_READ_FRAGS(la, lb, 0, fa0, fb0)                                                           \
+        GM_READ_FRAGS(la, lb, 1, fa1, fb1)                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        GM_MFMA(fa0, fb0)                                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        GM_READ_FRAGS(la, lb, 2, fa0, fb0)                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        GM_MFMA(fa1, fb1)                                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        GM_READ_FRAGS(la, lb, 3, fa1, fb1)                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        GM_MFMA(fa0, fb0)                                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        GM_MFMA(fa1, fb1)                                                                           \
     }
 
     const int nk = p.k_dim / GM_BK;   // >= 1
-    GM_LOAD_GLOBAL(ga0, gb0, 0)
-    if (nk > 1) { GM_LOAD_GLOBAL(ga1, gb1, GM_BK) }
-    GM_STORE_LDS(ga0, gb0, 0)
-    __syncthreads();
-    // tile kt sits in LDS stage kt & 1; even kt: set 1 holds tile kt+1, set 0 is free (and vice versa).
-    // The steady-state loop issues its loads unconditionally, so the waits before the LDS copies
-    // cover only the older set; the last (up to three) tiles run through the guarded copy below.
     int kt = 0;
-    for (; kt + 3 < nk; kt += 2) {
-        GM_LOAD_GLOBAL(ga0, gb0, (kt + 2) * GM_BK)
-        GM_COMPUTE(0)
-        GM_STORE_LDS(ga1, gb1, 1)
+    if (nk & 1) {   // odd slice count: the first slice runs alone, without a copy behind it
+        GM_COPY_SLICE(lds_a0, lds_b0, 0)
         __syncthreads();
-        GM_LOAD_GLOBAL(ga1, gb1, (kt + 3) * GM_BK)
-        GM_COMPUTE(1)
-        GM_STORE_LDS(ga0, gb0, 0)
+        GM_COMPUTE(lds_a0, lds_b0)
         __syncthreads();
+        kt = 1;
     }
-    for (; kt < nk; kt += 2) {
-        if (kt + 2 < nk) { GM_LOAD_GLOBAL(ga0, gb0, (kt + 2) * GM_BK) }
-        GM_COMPUTE(0)
-        if (kt + 1 < nk) { GM_STORE_LDS(ga1, gb1, 1) }
-        __syncthreads();
-        if (kt + 1 >= nk) break;
-        GM_COMPUTE(1)
-        if (kt + 2 < nk) { GM_STORE_LDS(ga0, gb0, 0) }
-        __syncthreads();
+    if (kt < nk) {
+        GM_COPY_SLICE(lds_a0, lds_b0, kt * GM_BK)
+        __syncthreads();   // waits for this wavefront's copies (vmcnt) and then for everyone's
+        // pairs of slices: first in stage 0, second in stage 1; a stage is refilled right after the
+        // barrier that ends its last reads
+        for (; kt < nk; kt += 2) {
+            GM_COPY_SLICE(lds_a1, lds_b1, (kt + 1) * GM_BK)
+            GM_COMPUTE(lds_a0, lds_b0)
+            __syncthreads();
+            if (kt + 2 < nk) { GM_COPY_SLICE(lds_a0, lds_b0, (kt + 2) * GM_BK) }
+            GM_COMPUTE(lds_a1, lds_b1)
+            __syncthreads();
+        }
     }
 
     // epilogue: a lane holds column li of 16 rows per accumulator
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
+    for (int mi = 0; mi < TM; ++mi) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int m = wm * 64 + mi * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+            const int m = (wm * TM + mi) * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
             if (m >= rows) continue;
             const int64_t crow = (p.c_row_offset + row0 + m) * p.ldc;
             if (MODE == 0) {
                 const float g = acc[mi][0][r], u = acc[mi][1][r];
                 const float h = g / (1.0f + __expf(-g)) * u;
-                p.c[crow + nt * 64 + wn * 32 + li] = f32_to_bf16(h);
+                const int col = nt * BN_OUT + wn * 32 + li;
+                if (col < p.n_out) p.c[crow + col] = f32_to_bf16(h);
             } else {
                 const float sc = p.row_scale ? p.row_scale[row0 + m] : 1.0f;
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-                    p.c[crow + nt * 128 + wn * 64 + ni * 32 + li] = f32_to_bf16(acc[mi][ni][r] * sc);
+                for (int ni = 0; ni < TN; ++ni) {
+                    const int col = nt * BN_OUT + (wn * TN + ni) * 32 + li;
+                    if (col < p.n_out) p.c[crow + col] = f32_to_bf16(acc[mi][ni][r] * sc);
+                }
             }
         }
     }
 }
 
+// tile configuration in use: 2 x 4 wavefronts of 4 x 2 MFMA tiles = 256 x 256
+constexpr int CFG_WM = 2, CFG_WN = 4, CFG_TM = 4, CFG_TN = 2;
+constexpr int CFG_BM = CFG_WM * CFG_TM * 32;
+constexpr int CFG_BN = CFG_WN * CFG_TN * 32;
+
 }  // namespace
 
-int gemm_tile_m() { return GM_BM; }
+int gemm_tile_m() { return CFG_BM; }
 
 remoe_status launch_grouped_gemm_bf16(int mode, const GroupedGemmArgs &g, hipStream_t stream)
 {
-    const int bn = (mode == 0) ? 64 : 128;
-    if (g.k_dim % GM_BK != 0 || g.n_out % bn != 0)
-        return fail(REMOE_E_UNSUPPORTED, "bf16 GEMM needs k %% 64 == 0 and n %% %d == 0 (k=%d n=%d)", bn,
-                    g.k_dim, g.n_out);
+    const int bn = (mode == 0) ? CFG_BN / 2 : CFG_BN;
+    if (g.k_dim % GM_BK != 0 || g.n_out < 1)
+        return fail(REMOE_E_UNSUPPORTED, "bf16 GEMM needs k %% 64 == 0 (k=%d n=%d)", g.k_dim, g.n_out);
+    if (g.row_gather && g.a_rows * g.lda * 2 >= (int64_t)1 << 32)
+        return fail(REMOE_E_UNSUPPORTED, "gathered GEMM operand spans 4 GiB or more (%lld rows)", (long long)g.a_rows);
+    if ((int64_t)g.n_out * g.k_dim * 2 >= (int64_t)1 << 32)
+        return fail(REMOE_E_UNSUPPORTED, "one expert matrix spans 4 GiB or more");
     if (g.max_tiles <= 0) return REMOE_OK;
     KArgs p;
     p.a = static_cast<const bf16_t *>(g.a);
@@ -250,12 +280,12 @@ remoe_status launch_grouped_gemm_bf16(int mode, const GroupedGemmArgs &g, hipStr
     p.c = static_cast<bf16_t *>(g.c);
     p.ldc = g.ldc;
     p.c_row_offset = g.c_row_offset;
-    const int64_t nblk = (int64_t)g.max_tiles * (g.n_out / bn);
-    const dim3 grid((unsigned)(ceil_div(nblk, 8) * 8)), block(256);
+    const int64_t nblk = (int64_t)g.max_tiles * ceil_div(g.n_out, bn);
+    const dim3 grid((unsigned)(ceil_div(nblk, 8) * 8)), block(CFG_WM * CFG_WN * 64);
     if (mode == 0)
-        hipLaunchKernelGGL(grouped_gemm_bf16_kernel<0>, grid, block, 0, stream, p);
+        hipLaunchKernelGGL((grouped_gemm_bf16_kernel<0, CFG_WM, CFG_WN, CFG_TM, CFG_TN>), grid, block, 0, stream, p);
     else
-        hipLaunchKernelGGL(grouped_gemm_bf16_kernel<1>, grid, block, 0, stream, p);
+        hipLaunchKernelGGL((grouped_gemm_bf16_kernel<1, CFG_WM, CFG_WN, CFG_TM, CFG_TN>), grid, block, 0, stream, p);
     return check_hip(hipGetLastError(), "grouped_gemm_bf16 launch");
 }
 
