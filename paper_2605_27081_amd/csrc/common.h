@@ -43,7 +43,25 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
+#if defined(__HIP_DEVICE_COMPILE__)
+    // one v_cvt_pk_bf16_f32 on gfx950 (round-to-nearest-even)
+    typedef __attribute__((ext_vector_type(2))) float f32x2_;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_;
+    const f32x2_ v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_));
+#else
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+#endif
+}
+
+// value held by the neighbouring lane (lane ^ 1), as a DPP quad permute: no LDS traffic
+__device__ __forceinline__ float swap_with_neighbour(float v)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true));
+#else
+    return v;
+#endif
 }
 
 // ---- kernel launchers (one per source file) -------------------------------------------------

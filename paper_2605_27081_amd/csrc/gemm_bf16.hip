@@ -83,6 +83,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // the fragment reads of the other (no wait for the copy before those reads)
     __shared__ u32x4_t lds_a0[BM * 8], lds_a1[BM * 8];
     __shared__ u32x4_t lds_b0[BN * 8], lds_b1[BN * 8];
+    __shared__ float lds_scale[BM];            // mode 1: gate weight of each tile row
 
     const int ntn = (p.n_out + BN_OUT - 1) / BN_OUT;
     const int n_mt = p.tile_expert ? *p.n_tiles : (p.dense_rows + BM - 1) / BM;
@@ -106,6 +107,11 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lh = lane >> 5;
+
+    if (MODE == 1) {
+        for (int r = tid; r < BM; r += THREADS)
+            lds_scale[r] = (p.row_scale && r < rows) ? p.row_scale[row0 + r] : 1.0f;
+    }
 
     // Direct-to-LDS copies: one instruction moves 64 lanes x 16 bytes into 1 KB of contiguous LDS
     // (lane l lands at base + 16 l), i.e. into 8 row slots x 8 chunk positions.  Each lane therefore
@@ -219,27 +225,61 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         }
     }
 
-    // epilogue: a lane holds column li of 16 rows per accumulator
+    // Epilogue.  A lane holds column li of 16 rows per accumulator, which would make 2-byte stores.
+    // Instead each 32-row band of the workgroup tile (both wm halves, all BN_OUT columns) is staged
+    // in LDS as bf16 and written out as 16-byte chunks, so every output row leaves as one
+    // contiguous run of full cache lines.  Neighbouring lanes first swap one value (lanes 2j and
+    // 2j+1 own adjacent columns) so that each lane packs two adjacent columns of one row into a
+    // dword.  A 64-byte segment s of band row r is stored at segment s ^ f(r), f = (r&1)|((r>>2)&1)<<1:
+    // the four rows one write instruction touches (r, r+1, r+4, r+5) then fall on different banks.
+    // Bands alternate between the two (now idle) A stages, so one barrier per band suffices.
+    constexpr int ROWB = BN_OUT * 2;        // bytes per staged row
+    constexpr int CPR = BN_OUT / 8;         // 16-byte chunks per staged row
+    const bool odd = li & 1;
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi) {
+        char *reg = reinterpret_cast<char *>((mi & 1) ? lds_a1 : lds_a0);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int m = (wm * TM + mi) * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-            if (m >= rows) continue;
-            const int64_t crow = (p.c_row_offset + row0 + m) * p.ldc;
-            if (MODE == 0) {
-                const float g = acc[mi][0][r], u = acc[mi][1][r];
-                const float h = g / (1.0f + __expf(-g)) * u;
-                const int col = nt * BN_OUT + wn * 32 + li;
-                if (col < p.n_out) p.c[crow + col] = f32_to_bf16(h);
-            } else {
-                const float sc = p.row_scale ? p.row_scale[row0 + m] : 1.0f;
-#pragma unroll
-                for (int ni = 0; ni < TN; ++ni) {
-                    const int col = nt * BN_OUT + (wn * TN + ni) * 32 + li;
-                    if (col < p.n_out) p.c[crow + col] = f32_to_bf16(acc[mi][ni][r] * sc);
-                }
+        for (int rp = 0; rp < 8; ++rp) {
+            const int r0 = 2 * rp;
+            const int rr0 = (r0 >> 2) * 8 + lh * 4 + (r0 & 3);   // band row of acc[..][r0]; r0 + 1 is the next row
+            const int row = odd ? rr0 + 1 : rr0;
+            const int f = (row & 1) | (((row >> 2) & 1) << 1);
+            float sc0 = 1.0f, sc1 = 1.0f;
+            if (MODE == 1) {
+                sc0 = lds_scale[(wm * TM + mi) * 32 + rr0];
+                sc1 = lds_scale[(wm * TM + mi) * 32 + rr0 + 1];
             }
+#pragma unroll
+            for (int ni = 0; ni < ((MODE == 0) ? 1 : TN); ++ni) {
+                float va, vb;
+                if (MODE == 0) {
+                    const float g0 = acc[mi][0][r0], u0 = acc[mi][1][r0];
+                    const float g1 = acc[mi][0][r0 + 1], u1 = acc[mi][1][r0 + 1];
+                    va = g0 / (1.0f + __expf(-g0)) * u0;
+                    vb = g1 / (1.0f + __expf(-g1)) * u1;
+                } else {
+                    va = acc[mi][ni][r0] * sc0;
+                    vb = acc[mi][ni][r0 + 1] * sc1;
+                }
+                const float recv = swap_with_neighbour(odd ? va : vb);
+                const uint32_t packed = odd ? pack_bf16x2(recv, vb) : pack_bf16x2(va, recv);
+                const int seg = (MODE == 0) ? wn : wn * TN + ni;
+                *reinterpret_cast<uint32_t *>(reg + (wm * 32 + row) * ROWB + ((seg ^ f) << 6) + ((li & ~1) << 1)) = packed;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 64 * CPR / THREADS; ++j) {
+            const int q2 = tid + THREADS * j;
+            const int R = q2 / CPR, ch = q2 % CPR;     // band row over both wm halves, chunk in the row
+            const int row = R & 31;
+            const int f = (row & 1) | (((row >> 2) & 1) << 1);
+            const u32x4_t v = *reinterpret_cast<const u32x4_t *>(reg + R * ROWB + ((((ch >> 2) ^ f) << 6) + ((ch & 3) << 4)));
+            const int m = ((R >> 5) * TM + mi) * 32 + row;
+            const int col = nt * BN_OUT + ch * 8;
+            if (m < rows && col < p.n_out)
+                *reinterpret_cast<u32x4_t *>(p.c + (p.c_row_offset + row0 + m) * p.ldc + col) = v;
         }
     }
 }
