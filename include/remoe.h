@@ -178,6 +178,47 @@ remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps,
                           uint8_t *out_miss, uint64_t *out_total_miss, uint64_t *out_bytes,
                           void *stream);
 
+/*
+ * moe_decode — M = 1 decode: the MoE layer of every one of `n_layers` layers for `n_steps`
+ * consecutive single-token steps, as one persistent kernel bound by HBM bandwidth (the B = 1
+ * regime of Sec. 3: per layer-step the router matrix and the K selected experts' weights are read
+ * once), with the routing-trace statistics updated online after every step (adjacent overlap,
+ * Eq. 1; LRU misses of App. E.2 for up to 4 capacities at once).  Layers run in order.
+ *
+ *   desc            bf16 layers without shared expert; hidden in {512, 1024, 2048, 4096},
+ *                   inter % 8 == 0, top_k * inter <= 6144
+ *   layer_weights   DEVICE array [n_layers][4] of device pointers: w_router [N_r,H] fp32,
+ *                   w_gate [N_r,I,H], w_up [N_r,I,H], w_down [N_r,H,I] (bf16)
+ *   x               [steps_total, H] bf16; step g reads row g (every layer sees the same row)
+ *   step0, n_steps  the steps [step0, step0 + n_steps) of the run are executed by this call
+ *   y               [steps_total, n_layers, H] bf16, rows of the executed steps are written
+ *   out_idx, out_w  [n_layers, steps_total, K] int32 / fp32: the routing of every layer-step
+ *   capacities      HOST array [n_caps] of LRU capacities (n_caps 0..4)
+ *   lru_state       [n_layers, N_r] uint32, (step of last use) + 1, 0 = never; zero = cold cache;
+ *                   read and updated, so a run can be split over several calls
+ *   out_overlap     [n_layers, steps_total] uint8;  out_miss [n_caps, n_layers, steps_total] uint8
+ *   sum_overlap     [n_layers] uint64;  total_miss, bytes_fetched [n_caps, n_layers] uint64:
+ *                   running sums, ADDED to by every call (zero them before the first)
+ *   workspace       remoe_decode_workspace_bytes(desc) bytes, 256-byte aligned.  Its first word is the
+ *                   grid-barrier counter and the word at byte 128 an abort flag: non-zero after the
+ *                   call has completed means a wait inside the kernel exceeded `spin_limit_us` and
+ *                   the outputs of this call are invalid (every workgroup still exits).
+ *   spin_limit_us   upper bound of a single grid-barrier wait in microseconds (0 = 2 seconds)
+ *
+ * The launch is cooperative: one workgroup per compute unit, all resident.  Calls that share a
+ * workspace or the state arrays must not overlap in time.
+ */
+size_t remoe_decode_workspace_bytes(const remoe_layer_desc *desc);
+remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers,
+                        const void *const *layer_weights,
+                        const void *x, int64_t steps_total, int64_t step0, int64_t n_steps,
+                        void *y, int32_t *out_idx, float *out_w,
+                        int32_t n_caps, const int32_t *capacities, uint64_t expert_bytes,
+                        uint32_t *lru_state, uint8_t *out_overlap, uint8_t *out_miss,
+                        uint64_t *sum_overlap, uint64_t *total_miss, uint64_t *bytes_fetched,
+                        void *workspace, size_t workspace_bytes, uint64_t spin_limit_us,
+                        void *stream);
+
 #ifdef __cplusplus
 }
 #endif

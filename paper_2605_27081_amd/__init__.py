@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     lru_simulate,
+    moe_decode,
+    remoe_decode_workspace_bytes,
     moe_forward,
     moe_route,
     PROF_KINDS,

@@ -65,6 +65,11 @@ def load_library() -> ctypes.CDLL:
     lib.trace_reuse.argtypes = [P, I64, I64, I32, I32, P, P, P]
     lib.lru_simulate.restype = ctypes.c_int
     lib.lru_simulate.argtypes = [P, I64, I64, I32, I32, I32, U64, I64, P, P, P, P, P]
+    lib.remoe_decode_workspace_bytes.restype = SZ
+    lib.remoe_decode_workspace_bytes.argtypes = [D]
+    lib.moe_decode.restype = ctypes.c_int
+    lib.moe_decode.argtypes = [D, I32, P, P, I64, I64, I64, P, P, P, I32, ctypes.POINTER(I32), U64,
+                               P, P, P, P, P, P, P, SZ, U64, P]
     lib.remoe_profile_enable.restype = ctypes.c_int
     lib.remoe_profile_enable.argtypes = [I32]
     lib.remoe_profile_read.restype = ctypes.c_int
@@ -153,3 +158,26 @@ def lru_simulate(idx: torch.Tensor, n_experts: int, capacity: int, expert_bytes:
     _check(load_library().lru_simulate(_ptr(idx), n_seq, n_steps, top_k, n_experts, capacity, expert_bytes,
                                        step0, _ptr(state), _ptr(out_miss), _ptr(out_total_miss),
                                        _ptr(out_bytes), _stream()))
+
+
+def remoe_decode_workspace_bytes(desc: LayerDesc) -> int:
+    n = int(load_library().remoe_decode_workspace_bytes(ctypes.byref(desc)))
+    if n == 0:
+        raise RemoeError(f"remoe_decode_workspace_bytes: {remoe_last_error()}")
+    return n
+
+
+def moe_decode(desc: LayerDesc, layer_weights: torch.Tensor, x: torch.Tensor, step0: int, n_steps: int,
+               y: torch.Tensor, out_idx: torch.Tensor, out_w: torch.Tensor, capacities, expert_bytes: int,
+               lru_state: torch.Tensor, out_overlap: torch.Tensor, out_miss: Optional[torch.Tensor],
+               sum_overlap: torch.Tensor, total_miss: Optional[torch.Tensor],
+               bytes_fetched: Optional[torch.Tensor], workspace: torch.Tensor, spin_limit_us: int = 0) -> None:
+    """layer_weights: int64 device tensor [n_layers, 4] of data_ptr()s (w_router, w_gate, w_up, w_down)."""
+    n_layers = layer_weights.shape[0]
+    steps_total = x.shape[0]
+    caps = (ctypes.c_int32 * max(len(capacities), 1))(*capacities)
+    _check(load_library().moe_decode(ctypes.byref(desc), n_layers, _ptr(layer_weights), _ptr(x), steps_total,
+                                     step0, n_steps, _ptr(y), _ptr(out_idx), _ptr(out_w), len(capacities), caps,
+                                     expert_bytes, _ptr(lru_state), _ptr(out_overlap), _ptr(out_miss),
+                                     _ptr(sum_overlap), _ptr(total_miss), _ptr(bytes_fetched), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), spin_limit_us, _stream()))

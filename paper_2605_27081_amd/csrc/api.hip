@@ -372,5 +372,59 @@ remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps, in
                       out_total_miss, out_bytes, static_cast<hipStream_t>(stream));
 }
 
+size_t remoe_decode_workspace_bytes(const remoe_layer_desc *desc)
+{
+    if (validate_layer_desc(desc) != REMOE_OK) return 0;
+    return decode_workspace_bytes(desc->hidden, desc->n_experts, desc->inter, desc->top_k);
+}
+
+remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers, const void *const *layer_weights,
+                        const void *x, int64_t steps_total, int64_t step0, int64_t n_steps, void *y,
+                        int32_t *out_idx, float *out_w, int32_t n_caps, const int32_t *capacities,
+                        uint64_t expert_bytes, uint32_t *lru_state, uint8_t *out_overlap, uint8_t *out_miss,
+                        uint64_t *sum_overlap, uint64_t *total_miss, uint64_t *bytes_fetched, void *workspace,
+                        size_t workspace_bytes, uint64_t spin_limit_us, void *stream)
+{
+    remoe_status st = validate_layer_desc(desc);
+    if (st != REMOE_OK) return st;
+    if (desc->dtype != REMOE_BF16 || desc->shared_inter != 0)
+        return fail(REMOE_E_UNSUPPORTED, "moe_decode handles bf16 layers without a shared expert");
+    if (n_layers < 1) return fail(REMOE_E_INVALID_ARG, "n_layers %d must be positive", n_layers);
+    if (steps_total < 0 || step0 < 0 || n_steps < 0 || step0 + n_steps > steps_total || steps_total >= (1 << 24))
+        return fail(REMOE_E_INVALID_ARG, "step range [%lld, %lld) outside 0..steps_total = %lld (< 2^24)",
+                    (long long)step0, (long long)(step0 + n_steps), (long long)steps_total);
+    if (n_caps < 0 || n_caps > 4) return fail(REMOE_E_INVALID_ARG, "n_caps %d outside 0..4", n_caps);
+    if (n_caps > 0 && !capacities) return fail(REMOE_E_INVALID_ARG, "capacities is NULL");
+    for (int c = 0; c < n_caps; ++c)
+        if (capacities[c] < 1) return fail(REMOE_E_INVALID_ARG, "capacity %d must be at least 1", capacities[c]);
+    if (n_steps == 0) return REMOE_OK;
+    if (!layer_weights || !x || !y || !out_idx || !out_w || !lru_state || !out_overlap || !sum_overlap)
+        return fail(REMOE_E_INVALID_ARG, "a required pointer is NULL");
+    if (n_caps > 0 && (!out_miss || !total_miss || !bytes_fetched))
+        return fail(REMOE_E_INVALID_ARG, "miss outputs are NULL");
+    if (((uintptr_t)x | (uintptr_t)y) & 15) return fail(REMOE_E_INVALID_ARG, "x and y must be 16-byte aligned");
+    if (!workspace || ((uintptr_t)workspace & 255))
+        return fail(REMOE_E_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+    const size_t need = decode_workspace_bytes(desc->hidden, desc->n_experts, desc->inter, desc->top_k);
+    if (workspace_bytes < need) return fail(REMOE_E_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+
+    DecodeLaunch d{};
+    d.layers = layer_weights;
+    d.x = x;
+    d.steps_total = steps_total; d.step0 = step0; d.n_steps = n_steps;
+    d.n_layers = n_layers; d.H = desc->hidden; d.N = desc->n_experts; d.I = desc->inter; d.K = desc->top_k;
+    d.renorm = desc->renorm;
+    d.y = y; d.out_idx = out_idx; d.out_w = out_w;
+    d.n_caps = n_caps;
+    for (int c = 0; c < n_caps; ++c) d.caps[c] = capacities[c];
+    d.expert_bytes = expert_bytes;
+    d.lru_state = lru_state; d.out_overlap = out_overlap; d.out_miss = out_miss;
+    d.sum_overlap = sum_overlap; d.total_miss = total_miss; d.bytes_fetched = bytes_fetched;
+    d.workspace = workspace;
+    d.spin_limit_ticks = (spin_limit_us ? spin_limit_us : 2000000ull) * 100ull;   // 100 MHz wall clock
+    ProfScope prof(REMOE_PROF_DECODE, static_cast<hipStream_t>(stream));
+    return launch_decode(d, static_cast<hipStream_t>(stream));
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

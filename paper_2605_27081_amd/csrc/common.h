@@ -113,6 +113,27 @@ remoe_status launch_combine(int dtype, const void *rows, const int32_t *pair_slo
                             int H, int64_t shared_row0, int has_shared, const void *x,
                             const float *ws_scale, void *y, hipStream_t stream);
 
+// M = 1 decode over all layers and a range of steps (persistent cooperative kernel).
+struct DecodeLaunch {
+    const void *const *layers;   // device [L][4]: w_router, w_gate, w_up, w_down
+    const void *x;
+    int64_t steps_total, step0, n_steps;
+    int n_layers, H, N, I, K, renorm;
+    void *y;
+    int32_t *out_idx;
+    float *out_w;
+    int n_caps;
+    int caps[4];
+    uint64_t expert_bytes;
+    uint32_t *lru_state;
+    uint8_t *out_overlap, *out_miss;
+    uint64_t *sum_overlap, *total_miss, *bytes_fetched;
+    void *workspace;
+    uint64_t spin_limit_ticks;
+};
+size_t decode_workspace_bytes(int H, int N, int I, int K);
+remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream);
+
 // Trace statistics.
 remoe_status launch_trace_reuse(const int32_t *idx, int64_t S, int64_t T, int K, int N,
                                 uint8_t *ov, uint64_t *sum, hipStream_t stream);

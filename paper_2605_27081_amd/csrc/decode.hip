@@ -1,0 +1,408 @@
+// M = 1 decode: the whole MoE layer for one token per step, weights streamed once from HBM.
+//
+// At one token per step the layer (Sec. 3.1 routing, Sec. 4.1 step 5 expert execution) is a chain
+// of matrix-vector products with about one flop per byte, so the matrix cores are useless and the
+// only roofline is HBM bandwidth: per layer-step the fp32 router matrix (N_r x H) and the three
+// matrices of the K selected experts are read exactly once.  One persistent kernel runs all layers
+// of all steps of a call: one workgroup of 8 wavefronts per compute unit, three phases per
+// layer-step separated by grid-wide barriers (an atomic counter in device memory):
+//   1. router   : every wavefront dots one 256-wide segment of one router row with x; partial
+//                 logits go to device memory;                                       -- barrier --
+//      top-k    : wavefront 0 of every workgroup sums the partials and runs the wavefront-shuffle
+//                 top-k / softmax (identical result everywhere, so no broadcast is needed);
+//   2. gate/up  : the K*I SwiGLU activations are dealt out in contiguous runs, each wavefront
+//                 streams the gate and up rows of its activations with 16-byte coalesced loads;
+//                 h goes to device memory in fp32;                                  -- barrier --
+//   3. down     : every wavefront owns output rows; for each it streams the K down-projection rows
+//                 (already prefetched into registers before the barrier, since the experts are
+//                 known) against h staged in LDS, weighted by the gate weights.     -- barrier --
+// Layers run strictly in order, as a real decoder would.  The routing-trace statistics the paper
+// optimises are updated online in the same kernel (one wavefront, right after the top-k): the
+// adjacent-step overlap |E_t ∩ E_{t-1}| (Eq. 1) and the LRU misses |E_t \ C_t| (App. E.2) for up to
+// four cache capacities at once, from one per-expert "last used" table per layer.
+//
+// Every wait is bounded: a workgroup that waits longer than the limit raises an abort flag, every
+// other workgroup sees the flag at its next wait, and the whole grid drains.
+#include "common.h"
+#include "topk.h"
+
+namespace remoe {
+
+namespace {
+
+constexpr int DC_THREADS = 512;
+constexpr int DC_WAVES = DC_THREADS / 64;
+constexpr int DC_SEG = 256;          // router row segment per wavefront (floats)
+constexpr int DC_MAX_KI = 6144;      // K * I floats of h staged in LDS (24 KB)
+constexpr int DC_MAX_CAPS = 4;
+constexpr int DC_ITEM_BATCH = 3;     // gate/up activations a wavefront has in flight
+constexpr int DC_MAX_DCH = 12;       // down-projection chunks per lane per output row (K * I <= 6144)
+
+struct DecodeArgs {
+    const void *const *layers;   // [L][4] device pointers: w_router, w_gate, w_up, w_down
+    const bf16_t *x;             // [T_total, H]
+    int64_t steps_total, step0, n_steps;
+    int n_layers, H, N, I, K, renorm;
+    bf16_t *y;                   // [T_total, L, H]
+    int32_t *out_idx;            // [L, T_total, K]
+    float *out_w;                // [L, T_total, K]
+    int n_caps;
+    int caps[DC_MAX_CAPS];
+    unsigned long long expert_bytes;
+    uint32_t *lru_state;         // [L, N] last use (global step + 1), 0 = never
+    uint8_t *out_overlap;        // [L, T_total]
+    uint8_t *out_miss;           // [n_caps, L, T_total]
+    unsigned long long *sum_overlap;   // [L]
+    unsigned long long *total_miss;    // [n_caps, L]
+    unsigned long long *bytes_fetched; // [n_caps, L]
+    float *logit_part;           // [N * H / DC_SEG]
+    float *hbuf;                 // [K * I]
+    uint32_t *bar;               // grid barrier counter, zero at launch
+    uint32_t *abort_flag;        // zero at launch
+    unsigned long long spin_limit;   // wall-clock ticks (100 MHz) a single wait may last
+};
+
+// Grid-wide barrier: every workgroup adds 1 with release semantics, then waits (acquire) until the
+// counter reaches `target`.  Returns false when the grid is aborting.
+__device__ __forceinline__ bool grid_barrier(const DecodeArgs &a, uint32_t target, int *lds_flag)
+{
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int ok = 1;
+        __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long t0 = wall_clock64();
+        while (__hip_atomic_load(a.bar, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            if (__hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { ok = 0; break; }
+            if (wall_clock64() - t0 > a.spin_limit) {
+                __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        *lds_flag = ok;
+    }
+    __syncthreads();
+    return *lds_flag != 0;
+}
+
+__device__ __forceinline__ float dot8(const u32x4_t w, const float *xv, float acc)
+{
+    acc = fmaf(__uint_as_float(w.x << 16), xv[0], acc);
+    acc = fmaf(__uint_as_float(w.x & 0xFFFF0000u), xv[1], acc);
+    acc = fmaf(__uint_as_float(w.y << 16), xv[2], acc);
+    acc = fmaf(__uint_as_float(w.y & 0xFFFF0000u), xv[3], acc);
+    acc = fmaf(__uint_as_float(w.z << 16), xv[4], acc);
+    acc = fmaf(__uint_as_float(w.z & 0xFFFF0000u), xv[5], acc);
+    acc = fmaf(__uint_as_float(w.w << 16), xv[6], acc);
+    acc = fmaf(__uint_as_float(w.w & 0xFFFF0000u), xv[7], acc);
+    return acc;
+}
+
+// Online overlap and LRU misses of one layer-step (one wavefront).  Lane l owns experts l, l + 64.
+__device__ void online_trace_stats(const DecodeArgs &a, int layer, int64_t g, int sel_expert, int lane)
+{
+    const int N = a.N, K = a.K;
+    uint32_t *st = a.lru_state + (int64_t)layer * N;
+    const uint32_t last0 = (lane < N) ? st[lane] : 0u;
+    const uint32_t last1 = (lane + 64 < N) ? st[lane + 64] : 0u;
+    bool req0 = false, req1 = false;
+    for (int j = 0; j < K; ++j) {
+        const int e = __shfl(sel_expert, j, 64);
+        req0 |= (e == lane);
+        req1 |= (e == lane + 64);
+    }
+    // experts of the previous step carry last == g (they were stamped (g - 1) + 1)
+    const int ov = (g > 0) ? __popcll(__ballot(req0 && last0 == (uint32_t)g)) +
+                                 __popcll(__ballot(req1 && last1 == (uint32_t)g))
+                           : 0;
+    const uint32_t key0 = last0 ? ((last0 << 7) | (uint32_t)lane) : 0u;
+    const uint32_t key1 = last1 ? ((last1 << 7) | (uint32_t)(lane + 64)) : 0u;
+    unsigned long long m0 = __ballot(req0), m1 = __ballot(req1);
+    const int n_unique = __popcll(m0) + __popcll(m1);
+    int hits[DC_MAX_CAPS] = {0, 0, 0, 0};
+    while (m0 | m1) {
+        uint32_t ke;
+        if (m0) {
+            const int b = __ffsll((long long)m0) - 1;
+            m0 &= m0 - 1;
+            ke = __shfl(key0, b, 64);
+        } else {
+            const int b = __ffsll((long long)m1) - 1;
+            m1 &= m1 - 1;
+            ke = __shfl(key1, b, 64);
+        }
+        const int above = __popcll(__ballot(key0 > ke)) + __popcll(__ballot(key1 > ke));
+#pragma unroll
+        for (int c = 0; c < DC_MAX_CAPS; ++c) hits[c] += (c < a.n_caps && ke != 0u && above < a.caps[c]);
+    }
+    if (req0) st[lane] = (uint32_t)(g + 1);
+    if (req1) st[lane + 64] = (uint32_t)(g + 1);
+    if (lane == 0) {
+        a.out_overlap[(int64_t)layer * a.steps_total + g] = (uint8_t)ov;
+        a.sum_overlap[layer] += (unsigned long long)ov;
+        for (int c = 0; c < a.n_caps; ++c) {
+            const int miss = n_unique - hits[c];
+            const int64_t cl = (int64_t)c * a.n_layers + layer;
+            a.out_miss[cl * a.steps_total + g] = (uint8_t)miss;
+            a.total_miss[cl] += (unsigned long long)miss;
+            a.bytes_fetched[cl] += (unsigned long long)miss * a.expert_bytes;
+        }
+    }
+}
+
+template <int XCH>
+__global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
+{
+    __shared__ float hl[DC_MAX_KI];
+    __shared__ int sel_e[8];
+    __shared__ float sel_w[8];
+    __shared__ int bar_ok;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int G = gridDim.x;
+    const int W = G * DC_WAVES;                 // wavefronts in the grid
+    const int gw = blockIdx.x * DC_WAVES + wave;  // this wavefront's global index
+    const int H = a.H, N = a.N, I = a.I, K = a.K;
+    const int segs = H / DC_SEG;
+    constexpr int xch = XCH;                    // 16-byte x chunks per lane (H = 512 * XCH)
+    const int KI = K * I;
+    const int items_per_wave = (KI + W - 1) / W;
+    const int rows_per_wave = (H + W - 1) / W;
+    const int dchunks = KI / 8;                 // 16-byte chunks of one output row's K down rows
+    const int chunks_per_row = I / 8;
+    uint32_t phase = 0;
+
+#pragma unroll 1
+    for (int64_t s = 0; s < a.n_steps; ++s) {
+        const int64_t g = a.step0 + s;
+        const bf16_t *xg = a.x + g * H;
+#pragma unroll 1
+        for (int layer = 0; layer < a.n_layers; ++layer) {
+            const float *w_router = static_cast<const float *>(a.layers[layer * 4 + 0]);
+            const bf16_t *w_gate = static_cast<const bf16_t *>(a.layers[layer * 4 + 1]);
+            const bf16_t *w_up = static_cast<const bf16_t *>(a.layers[layer * 4 + 2]);
+            const bf16_t *w_down = static_cast<const bf16_t *>(a.layers[layer * 4 + 3]);
+
+            // ---- phase 1: partial router logits --------------------------------------------------
+#pragma unroll 1
+            for (int item = gw; item < N * segs; item += W) {
+                const int e = item / segs, sg = item - e * segs;
+                const int k0 = sg * DC_SEG + lane * 4;
+                const floatx4_t wv = *reinterpret_cast<const floatx4_t *>(w_router + (int64_t)e * H + k0);
+                const uint2 xb = *reinterpret_cast<const uint2 *>(xg + k0);
+                float p = wv.x * __uint_as_float(xb.x << 16);
+                p = fmaf(wv.y, __uint_as_float(xb.x & 0xFFFF0000u), p);
+                p = fmaf(wv.z, __uint_as_float(xb.y << 16), p);
+                p = fmaf(wv.w, __uint_as_float(xb.y & 0xFFFF0000u), p);
+                p = wave_sum(p);
+                if (lane == 0) a.logit_part[item] = p;
+            }
+            // this lane's share of x, widened once per layer-step: chunk c covers k = (c*64 + lane)*8 ..
+            float xr[XCH][8];
+#pragma unroll
+            for (int c = 0; c < XCH; ++c) {
+                if (c < xch) {
+                    const u32x4_t xb = *reinterpret_cast<const u32x4_t *>(xg + (c * 64 + lane) * 8);
+                    xr[c][0] = __uint_as_float(xb.x << 16); xr[c][1] = __uint_as_float(xb.x & 0xFFFF0000u);
+                    xr[c][2] = __uint_as_float(xb.y << 16); xr[c][3] = __uint_as_float(xb.y & 0xFFFF0000u);
+                    xr[c][4] = __uint_as_float(xb.z << 16); xr[c][5] = __uint_as_float(xb.z & 0xFFFF0000u);
+                    xr[c][6] = __uint_as_float(xb.w << 16); xr[c][7] = __uint_as_float(xb.w & 0xFFFF0000u);
+                }
+            }
+            if (!grid_barrier(a, ++phase * (uint32_t)G, &bar_ok)) return;
+
+            // ---- top-k and softmax (wavefront 0 of every workgroup, same result everywhere) ---------
+            if (wave == 0) {
+                const float NEG_INF = -__builtin_inff();
+                float v0 = NEG_INF, v1 = NEG_INF;
+                if (lane < N) {
+                    v0 = 0.f;
+                    for (int q = 0; q < segs; ++q) v0 += a.logit_part[lane * segs + q];
+                }
+                if (lane + 64 < N) {
+                    v1 = 0.f;
+                    for (int q = 0; q < segs; ++q) v1 += a.logit_part[(lane + 64) * segs + q];
+                }
+                const TopKResult r = wave_topk_softmax(v0, v1, N, K, a.renorm, lane);
+                if (lane < K) {
+                    sel_e[lane] = r.expert;
+                    sel_w[lane] = r.weight;
+                    if (blockIdx.x == 0) {
+                        const int64_t o = ((int64_t)layer * a.steps_total + g) * K + lane;
+                        a.out_idx[o] = r.expert;
+                        a.out_w[o] = r.weight;
+                    }
+                }
+            }
+            __syncthreads();
+            if (blockIdx.x == G - 1 && wave == DC_WAVES - 1)
+                online_trace_stats(a, layer, g, (lane < K) ? sel_e[lane] : -1, lane);
+
+            // ---- phase 2: gate / up rows of the selected experts, SwiGLU -----------------------------
+            // Row bases are wave-uniform (scalar registers); a lane adds its own 32-bit offset.
+            {
+                const int item0 = gw * items_per_wave;
+                const int loff = lane * 8;
+#pragma unroll 1
+                for (int ib = 0; ib < items_per_wave; ib += DC_ITEM_BATCH) {
+                    u32x4_t gv[DC_ITEM_BATCH][XCH], uv[DC_ITEM_BATCH][XCH];
+#pragma unroll
+                    for (int b = 0; b < DC_ITEM_BATCH; ++b) {
+                        const int item = item0 + ib + b;
+                        if (ib + b < items_per_wave && item < KI) {
+                            const int j = item / I, i = item - j * I;
+                            const int e = __builtin_amdgcn_readfirstlane(sel_e[j]);
+                            const bf16_t *gp = w_gate + ((int64_t)e * I + i) * H;
+                            const bf16_t *up = w_up + ((int64_t)e * I + i) * H;
+#pragma unroll
+                            for (int c = 0; c < XCH; ++c) {
+                                gv[b][c] = *reinterpret_cast<const u32x4_t *>(gp + loff + c * 512);
+                                uv[b][c] = *reinterpret_cast<const u32x4_t *>(up + loff + c * 512);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int b = 0; b < DC_ITEM_BATCH; ++b) {
+                        const int item = item0 + ib + b;
+                        if (ib + b < items_per_wave && item < KI) {
+                            float gs = 0.f, us = 0.f;
+#pragma unroll
+                            for (int c = 0; c < XCH; ++c) {
+                                gs = dot8(gv[b][c], xr[c], gs);
+                                us = dot8(uv[b][c], xr[c], us);
+                            }
+                            gs = wave_sum(gs);
+                            us = wave_sum(us);
+                            if (lane == 0) a.hbuf[item] = gs / (1.0f + expf(-gs)) * us;
+                        }
+                    }
+                }
+            }
+
+            // ---- phase 3 prefetch: the K down rows of this wavefront's first output row ---------------
+            // Chunk q = c * 64 + lane of the concatenated K rows belongs to expert j = q / (I / 8) and
+            // multiplies h[q * 8 .. q * 8 + 7]; its address is a 32-bit byte offset from w_down.
+            u32x4_t dv[DC_MAX_DCH];
+            uint32_t doff[DC_MAX_DCH];
+            const int row_first = gw * rows_per_wave;
+            const char *wd_bytes = reinterpret_cast<const char *>(w_down);
+#pragma unroll
+            for (int c = 0; c < DC_MAX_DCH; ++c) {
+                const int q = c * 64 + lane;
+                doff[c] = 0u;
+                if (q < dchunks && row_first < H) {
+                    const int j = q / chunks_per_row, pos = (q - j * chunks_per_row) * 8;
+                    doff[c] = (uint32_t)((((int64_t)sel_e[j] * H + row_first) * I + pos) * 2);
+                    dv[c] = *reinterpret_cast<const u32x4_t *>(wd_bytes + doff[c]);
+                }
+            }
+            if (!grid_barrier(a, ++phase * (uint32_t)G, &bar_ok)) return;
+
+            // ---- phase 3: down projection; h is staged in LDS already multiplied by the gate weight ----
+            for (int q = tid * 4; q < KI; q += DC_THREADS * 4) {
+                floatx4_t hv = *reinterpret_cast<const floatx4_t *>(&a.hbuf[q]);
+                const float wj = sel_w[q / I];      // I % 8 == 0: the four values belong to one expert
+                hv.x *= wj; hv.y *= wj; hv.z *= wj; hv.w *= wj;
+                *reinterpret_cast<floatx4_t *>(&hl[q]) = hv;
+            }
+            __syncthreads();
+#pragma unroll 1
+            for (int rw = 0; rw < rows_per_wave; ++rw) {
+                const int o = row_first + rw;
+                if (o >= H) break;
+                float acc = 0.f;
+#pragma unroll
+                for (int c = 0; c < DC_MAX_DCH; ++c) {
+                    const int q = c * 64 + lane;
+                    if (q < dchunks) {
+                        u32x4_t wv = dv[c];
+                        if (rw > 0) wv = *reinterpret_cast<const u32x4_t *>(wd_bytes + doff[c] + (uint32_t)(rw * I * 2));
+                        acc = dot8(wv, &hl[q * 8], acc);
+                    }
+                }
+                acc = wave_sum(acc);
+                if (lane == 0) a.y[(g * a.n_layers + layer) * H + o] = f32_to_bf16(acc);
+            }
+            if (!grid_barrier(a, ++phase * (uint32_t)G, &bar_ok)) return;
+        }
+    }
+}
+
+__global__ void decode_clear_flags(uint32_t *bar, uint32_t *abort_flag)
+{
+    *bar = 0u;
+    *abort_flag = 0u;
+}
+
+}  // namespace
+
+size_t decode_workspace_bytes(int H, int N, int I, int K)
+{
+    size_t off = 256;                                            // barrier counter + abort flag
+    off += align_up(sizeof(float) * (size_t)N * (H / DC_SEG), 256);
+    off += align_up(sizeof(float) * (size_t)K * I, 256);
+    return off;
+}
+
+remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream)
+{
+    if (d.H != 512 && d.H != 1024 && d.H != 2048 && d.H != 4096)
+        return fail(REMOE_E_UNSUPPORTED, "decode supports hidden in {512, 1024, 2048, 4096} (got %d)", d.H);
+    if (d.I % 8 != 0 || d.K * d.I > DC_MAX_KI)
+        return fail(REMOE_E_UNSUPPORTED, "decode needs inter %% 8 == 0 and top_k * inter <= %d", DC_MAX_KI);
+    if (d.n_caps < 0 || d.n_caps > DC_MAX_CAPS)
+        return fail(REMOE_E_INVALID_ARG, "n_caps %d outside 0..%d", d.n_caps, DC_MAX_CAPS);
+    int dev = 0, n_cu = 0;
+    REMOE_HIP_TRY(hipGetDevice(&dev));
+    REMOE_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (n_cu < 1) return fail(REMOE_E_HIP, "device reports no compute units");
+    // one workgroup per compute unit, all resident at once (the cooperative launch checks this)
+    const int G = n_cu;
+    const int W = G * DC_WAVES;
+    if ((d.K * d.I / 8 + 63) / 64 > DC_MAX_DCH)
+        return fail(REMOE_E_UNSUPPORTED, "decode: top_k * inter too large for the register prefetch");
+    (void)W;
+
+    DecodeArgs a;
+    a.layers = d.layers;
+    a.x = static_cast<const bf16_t *>(d.x);
+    a.steps_total = d.steps_total;
+    a.step0 = d.step0;
+    a.n_steps = d.n_steps;
+    a.n_layers = d.n_layers;
+    a.H = d.H; a.N = d.N; a.I = d.I; a.K = d.K; a.renorm = d.renorm;
+    a.y = static_cast<bf16_t *>(d.y);
+    a.out_idx = d.out_idx;
+    a.out_w = d.out_w;
+    a.n_caps = d.n_caps;
+    for (int c = 0; c < DC_MAX_CAPS; ++c) a.caps[c] = (c < d.n_caps) ? d.caps[c] : 0;
+    a.expert_bytes = d.expert_bytes;
+    a.lru_state = d.lru_state;
+    a.out_overlap = d.out_overlap;
+    a.out_miss = d.out_miss;
+    a.sum_overlap = reinterpret_cast<unsigned long long *>(d.sum_overlap);
+    a.total_miss = reinterpret_cast<unsigned long long *>(d.total_miss);
+    a.bytes_fetched = reinterpret_cast<unsigned long long *>(d.bytes_fetched);
+    char *ws = static_cast<char *>(d.workspace);
+    a.bar = reinterpret_cast<uint32_t *>(ws);
+    a.abort_flag = reinterpret_cast<uint32_t *>(ws + 128);
+    a.logit_part = reinterpret_cast<float *>(ws + 256);
+    a.hbuf = reinterpret_cast<float *>(ws + 256 + align_up(sizeof(float) * (size_t)d.N * (d.H / DC_SEG), 256));
+    a.spin_limit = d.spin_limit_ticks;
+
+    hipLaunchKernelGGL(decode_clear_flags, dim3(1), dim3(1), 0, stream, a.bar, a.abort_flag);
+    void *params[] = {&a};
+    const void *fn = nullptr;
+    switch (d.H / 512) {
+    case 1: fn = reinterpret_cast<const void *>(decode_kernel<1>); break;
+    case 2: fn = reinterpret_cast<const void *>(decode_kernel<2>); break;
+    case 4: fn = reinterpret_cast<const void *>(decode_kernel<4>); break;
+    case 8: fn = reinterpret_cast<const void *>(decode_kernel<8>); break;
+    default: return fail(REMOE_E_UNSUPPORTED, "decode supports hidden in {512, 1024, 2048, 4096} (got %d)", d.H);
+    }
+    REMOE_HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(G), dim3(DC_THREADS), params, 0, stream));
+    return REMOE_OK;
+}
+
+}  // namespace remoe

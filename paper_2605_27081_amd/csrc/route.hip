@@ -7,6 +7,7 @@
 // wavefront: every lane owns experts {lane, lane+64}, and K+1 rounds of a 6-step butterfly argmax
 // over (logit, -id) produce the ids in descending-logit order with ties to the lower id.
 #include "common.h"
+#include "topk.h"
 
 namespace remoe {
 
@@ -77,13 +78,6 @@ template <> struct XLoad<bf16_t> {
         }
     }
 };
-
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
-}
 
 template <int NT, typename XT>
 __global__ __launch_bounds__(256) void route_kernel(const XT *__restrict__ x, int64_t T, int H,
@@ -180,7 +174,6 @@ __global__ __launch_bounds__(256) void route_kernel(const XT *__restrict__ x, in
     __syncthreads();
 
     const float NEG_INF = -__builtin_inff();
-    const int rounds = (K < N) ? K + 1 : K;
 #pragma unroll 1
     for (int tl = 0; tl < 32; ++tl) {
         const int64_t t = t0 + wave * 32 + tl;
@@ -189,47 +182,15 @@ __global__ __launch_bounds__(256) void route_kernel(const XT *__restrict__ x, in
         const float v0 = (lane < N) ? L[lane] : NEG_INF;
         float v1 = NEG_INF;
         if (NE > 64) v1 = (lane + 64 < N) ? L[lane + 64] : NEG_INF;
-        float c0 = v0, c1 = v1;
-        float my_v = 0.f, zmax = 0.f, zk = 0.f, zk1 = 0.f;
-        int my_e = 0;
-#pragma unroll 1
-        for (int j = 0; j < rounds; ++j) {
-            const bool pick1 = c1 > c0;
-            float bvv = pick1 ? c1 : c0;
-            int be = pick1 ? lane + 64 : lane;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const float ov = __shfl_xor(bvv, off, 64);
-                const int oe = __shfl_xor(be, off, 64);
-                if (ov > bvv || (ov == bvv && oe < be)) { bvv = ov; be = oe; }
-            }
-            if (j < K) {
-                if (lane == j) { my_v = bvv; my_e = be; }
-                if (j == 0) zmax = bvv;
-                zk = bvv;
-                if (be == lane) c0 = NEG_INF;
-                if (be == lane + 64) c1 = NEG_INF;
-            } else {
-                zk1 = bvv;
-            }
-        }
-        const float e0 = (lane < N) ? expf(v0 - zmax) : 0.f;
-        const float e1 = (lane + 64 < N) ? expf(v1 - zmax) : 0.f;
-        const float den = wave_sum(e0 + e1);
-        const float my_p = (lane < K) ? expf(my_v - zmax) : 0.f;
-        float wgt = my_p / den;
-        if (renorm) {
-            const float sel = wave_sum(my_p);
-            wgt = my_p / sel;
-        }
+        const TopKResult r = wave_topk_softmax(v0, v1, N, K, renorm, lane);
         if (lane < K) {
-            out_idx[t * K + lane] = my_e;
-            out_w[t * K + lane] = wgt;
+            out_idx[t * K + lane] = r.expert;
+            out_w[t * K + lane] = r.weight;
         }
-        if (out_margin && lane == 0) out_margin[t] = (K < N) ? zk - zk1 : __builtin_inff();
+        if (out_margin && lane == 0) out_margin[t] = r.margin;
         if (out_probs) {
-            if (lane < N) out_probs[t * N + lane] = e0 / den;
-            if (lane + 64 < N) out_probs[t * N + lane + 64] = e1 / den;
+            if (lane < N) out_probs[t * N + lane] = r.e0 / r.den;
+            if (lane + 64 < N) out_probs[t * N + lane + 64] = r.e1 / r.den;
         }
     }
 }

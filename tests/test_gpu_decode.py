@@ -1,0 +1,126 @@
+"""GPU parity of the M = 1 decode kernel (moe_decode) against the CPU oracle.
+
+Every layer-step is checked: expert ids (tie window aside) and gate weights against the oracle's
+router, layer outputs against the oracle's expert evaluation, and the online overlap / LRU-miss
+statistics bit for bit against the oracle's trace functions run on the same expert ids.
+"""
+import pytest
+import torch
+
+import oracle
+import paper_2605_27081_amd as remoe
+import workload as wl
+from helpers import check_output, compare_routing
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _layers(seed, L, H, N, I, std):
+    out = []
+    for l in range(L):
+        g = lambda name, shape, dt: wl.gaussian(seed, name, shape, std, l, 0, dt, DEV)
+        out.append({"w_router": g("w_router", (N, H), torch.float32),
+                    "w_gate": g("w_gate", (N, I, H), torch.bfloat16),
+                    "w_up": g("w_up", (N, I, H), torch.bfloat16),
+                    "w_down": g("w_down", (N, H, I), torch.bfloat16)})
+    return out
+
+
+def _run_decode(desc, layers, x, caps, expert_bytes, pieces, spin_limit_us=0):
+    L, T = len(layers), x.shape[0]
+    K, N, H = desc.top_k, desc.n_experts, desc.hidden
+    table = torch.tensor([[w["w_router"].data_ptr(), w["w_gate"].data_ptr(), w["w_up"].data_ptr(),
+                           w["w_down"].data_ptr()] for w in layers], dtype=torch.int64, device=DEV)
+    out = {
+        "y": torch.full((T, L, H), float("nan"), dtype=torch.bfloat16, device=DEV),
+        "idx": torch.full((L, T, K), -1, dtype=torch.int32, device=DEV),
+        "w": torch.full((L, T, K), float("nan"), dtype=torch.float32, device=DEV),
+        "state": torch.zeros(L, N, dtype=torch.int32, device=DEV),
+        "ov": torch.full((L, T), 255, dtype=torch.uint8, device=DEV),
+        "miss": torch.full((len(caps), L, T), 255, dtype=torch.uint8, device=DEV),
+        "sum_ov": torch.zeros(L, dtype=torch.int64, device=DEV),
+        "tot": torch.zeros(len(caps), L, dtype=torch.int64, device=DEV),
+        "bytes": torch.zeros(len(caps), L, dtype=torch.int64, device=DEV),
+    }
+    ws = torch.zeros(remoe.remoe_decode_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    pos = 0
+    for n in pieces:
+        remoe.moe_decode(desc, table, x, pos, n, out["y"], out["idx"], out["w"], caps, expert_bytes, out["state"],
+                         out["ov"], out["miss"], out["sum_ov"], out["tot"], out["bytes"], ws, spin_limit_us)
+        torch.cuda.synchronize()
+        pos += n
+    assert pos == T
+    out["abort"] = int(ws[128:132].view(torch.int32)[0])
+    return out
+
+
+def _check_decode(desc, layers, x, caps, expert_bytes, out, renorm):
+    L, T = len(layers), x.shape[0]
+    K, N = desc.top_k, desc.n_experts
+    assert out["abort"] == 0, "a grid-barrier wait timed out"
+    xc = x.cpu()
+    worst = 0.0
+    for l in range(L):
+        wc = {k: v.cpu() for k, v in layers[l].items()}
+        orc = oracle.route(xc, wc["w_router"], K, renorm, want_probs=True)
+        _, exp_w = compare_routing(out["idx"][l], out["w"][l], orc, renorm)
+        y_ref = oracle.experts_sparse(xc, out["idx"][l].cpu(), exp_w, wc)
+        worst = max(worst, check_output(out["y"][:, l], y_ref, "bf16"))
+    tr = out["idx"].cpu()
+    rov, rsum = oracle.trace_reuse(tr, N)
+    assert torch.equal(out["ov"].cpu(), rov) and torch.equal(out["sum_ov"].cpu(), rsum)
+    for c, cap in enumerate(caps):
+        rmiss, rtot, rbytes = oracle.lru_list(tr, N, cap, expert_bytes)
+        assert torch.equal(out["miss"][c].cpu(), rmiss), f"LRU misses differ at capacity {cap}"
+        assert torch.equal(out["tot"][c].cpu(), rtot) and torch.equal(out["bytes"][c].cpu(), rbytes)
+    return worst
+
+
+@pytest.mark.parametrize("L,T,H,N,I,K,renorm,caps,pieces", [
+    (3, 40, 512, 16, 64, 4, True, [4, 8], [40]),
+    (2, 33, 1024, 60, 128, 4, False, [12], [1, 1, 7, 24]),          # online: fed in pieces
+    (4, 24, 2048, 128, 768, 8, True, [16, 32, 64], [10, 14]),       # the Qwen3-30B-A3B layer shape
+    (1, 17, 512, 8, 64, 8, False, [2, 8, 9, 3], [17]),              # K = N, C < K, four capacities
+])
+def test_decode_matches_oracle(L, T, H, N, I, K, renorm, caps, pieces):
+    _say(f"decode L={L} T={T} H={H} N={N} I={I} K={K} caps={caps} pieces={pieces}")
+    layers = _layers(70 + N, L, H, N, I, 0.05)
+    x = wl.ar1_hidden_states(70 + N, 1, T, H, 0.9, torch.bfloat16, DEV)[0].contiguous()
+    desc = remoe.LayerDesc(H, N, I, K, int(renorm), 0, 0, 1)
+    out = _run_decode(desc, layers, x, caps, 3 * H * I * 2, pieces)
+    err = _check_decode(desc, layers, x, caps, 3 * H * I * 2, out, renorm)
+    _say(f"  worst rel L2 {err:.3e}")
+
+
+def test_decode_wait_limit_aborts_cleanly():
+    """A wait limit the barrier cannot meet makes the kernel give up: it must still exit (no hang)
+    and report it through the abort flag."""
+    L, T, H, N, I, K = 2, 4, 512, 16, 64, 4
+    layers = _layers(81, L, H, N, I, 0.05)
+    x = wl.ar1_hidden_states(81, 1, T, H, 0.5, torch.bfloat16, DEV)[0].contiguous()
+    desc = remoe.LayerDesc(H, N, I, K, 1, 0, 0, 1)
+    ok = _run_decode(desc, layers, x, [4], 1, [T])
+    assert ok["abort"] == 0
+    # the limit is per wait; 10 ns cannot cover one atomic round trip of 256 workgroups
+    # (spin_limit_us is in whole microseconds, so this uses the smallest value, 1 us, and many layers)
+    aborted = _run_decode(desc, layers * 8, x, [4], 1, [T], spin_limit_us=1)
+    assert aborted["abort"] in (0, 1)      # either it kept up or it gave up; it returned either way
+
+
+def test_decode_rejects_unsupported_layers():
+    x = torch.zeros(4, 768, dtype=torch.bfloat16, device=DEV)
+    desc = remoe.LayerDesc(768, 16, 64, 4, 1, 0, 0, 1)
+    ws = torch.zeros(1 << 20, dtype=torch.uint8, device=DEV)
+    t = torch.zeros(1, 4, dtype=torch.int64, device=DEV)
+    z = torch.zeros(64, dtype=torch.int64, device=DEV)
+    with pytest.raises(remoe.RemoeError, match="hidden"):
+        remoe.moe_decode(desc, t, x, 0, 4, x, z, z, [4], 1, z, z, z, z, z, z, ws)
+    desc2 = remoe.LayerDesc(512, 16, 64, 4, 1, 64, 0, 1)
+    x2 = torch.zeros(4, 512, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(remoe.RemoeError, match="shared"):
+        remoe.moe_decode(desc2, t, x2, 0, 4, x2, z, z, [4], 1, z, z, z, z, z, z, ws)
