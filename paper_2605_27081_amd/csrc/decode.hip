@@ -35,6 +35,7 @@ constexpr int DC_WAVES = DC_THREADS / 64;
 constexpr int DC_SEG = 256;          // router row segment per wavefront (floats)
 constexpr int DC_MAX_KI = 6144;      // K * I floats of h staged in LDS (24 KB)
 constexpr int DC_MAX_CAPS = 4;
+constexpr int DC_MAX_LAYERS = 64;     // trace state of all layers is kept in LDS
 constexpr int DC_ITEM_BATCH = 3;     // gate/up activations a wavefront has in flight
 constexpr int DC_MAX_DCH = 12;       // down-projection chunks per lane per output row (K * I <= 6144)
 
@@ -62,23 +63,37 @@ struct DecodeArgs {
     unsigned long long spin_limit;   // wall-clock ticks (100 MHz) a single wait may last
 };
 
-// Grid-wide barrier: every workgroup adds 1 with release semantics, then waits (acquire) until the
-// counter reaches `target`.  Returns false when the grid is aborting.
+// Data that crosses workgroups inside the kernel (partial logits, SwiGLU activations) is written and
+// read with agent-scope relaxed atomics: such stores write through the per-XCD L2 and such loads
+// bypass it, so no cache write-back or invalidate is needed at the grid barriers.
+__device__ __forceinline__ void put_shared(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float get_shared(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Grid-wide barrier.  The workgroup barrier in front makes every wavefront wait for its own stores
+// (they are complete at agent scope then); one thread adds 1 to the counter and polls it until it
+// reaches `target`.  Returns false when the grid is aborting.
 __device__ __forceinline__ bool grid_barrier(const DecodeArgs &a, uint32_t target, int *lds_flag)
 {
     __syncthreads();
     if (threadIdx.x == 0) {
         int ok = 1;
-        __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long t0 = wall_clock64();
-        while (__hip_atomic_load(a.bar, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            if (__hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { ok = 0; break; }
-            if (wall_clock64() - t0 > a.spin_limit) {
-                __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ok = 0;
-                break;
+        __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (__hip_atomic_load(a.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            const unsigned long long t0 = wall_clock64();
+            while (__hip_atomic_load(a.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+                if (__hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { ok = 0; break; }
+                if (wall_clock64() - t0 > a.spin_limit) {
+                    __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ok = 0;
+                    break;
+                }
             }
-            __builtin_amdgcn_s_sleep(1);
         }
         *lds_flag = ok;
     }
@@ -99,19 +114,28 @@ __device__ __forceinline__ float dot8(const u32x4_t w, const float *xv, float ac
     return acc;
 }
 
+// Per-layer trace state of the one wavefront that keeps the statistics; it lives in LDS for the whole
+// kernel and is loaded from / stored to device memory at the kernel's ends.
+struct TraceLds {
+    uint32_t last[DC_MAX_LAYERS][128];                 // (step of last use) + 1, 0 = never
+    unsigned long long sum_ov[DC_MAX_LAYERS];
+    unsigned long long tot[DC_MAX_CAPS][DC_MAX_LAYERS];
+};
+
 // Online overlap and LRU misses of one layer-step (one wavefront).  Lane l owns experts l, l + 64.
-__device__ void online_trace_stats(const DecodeArgs &a, int layer, int64_t g, int sel_expert, int lane)
+__device__ __forceinline__ void online_trace_stats(const DecodeArgs &a, TraceLds &ts, int layer, int64_t g,
+                                                   const int *sel_e, int lane)
 {
     const int N = a.N, K = a.K;
-    uint32_t *st = a.lru_state + (int64_t)layer * N;
-    const uint32_t last0 = (lane < N) ? st[lane] : 0u;
-    const uint32_t last1 = (lane + 64 < N) ? st[lane + 64] : 0u;
+    const uint32_t last0 = ts.last[layer][lane], last1 = ts.last[layer][lane + 64];
     bool req0 = false, req1 = false;
     for (int j = 0; j < K; ++j) {
-        const int e = __shfl(sel_expert, j, 64);
+        const int e = sel_e[j];          // LDS broadcast
         req0 |= (e == lane);
         req1 |= (e == lane + 64);
     }
+    req0 &= lane < N;
+    req1 &= lane + 64 < N;
     // experts of the previous step carry last == g (they were stamped (g - 1) + 1)
     const int ov = (g > 0) ? __popcll(__ballot(req0 && last0 == (uint32_t)g)) +
                                  __popcll(__ballot(req1 && last1 == (uint32_t)g))
@@ -136,17 +160,15 @@ __device__ void online_trace_stats(const DecodeArgs &a, int layer, int64_t g, in
 #pragma unroll
         for (int c = 0; c < DC_MAX_CAPS; ++c) hits[c] += (c < a.n_caps && ke != 0u && above < a.caps[c]);
     }
-    if (req0) st[lane] = (uint32_t)(g + 1);
-    if (req1) st[lane + 64] = (uint32_t)(g + 1);
+    if (req0) ts.last[layer][lane] = (uint32_t)(g + 1);
+    if (req1) ts.last[layer][lane + 64] = (uint32_t)(g + 1);
     if (lane == 0) {
         a.out_overlap[(int64_t)layer * a.steps_total + g] = (uint8_t)ov;
-        a.sum_overlap[layer] += (unsigned long long)ov;
+        ts.sum_ov[layer] += (unsigned long long)ov;
         for (int c = 0; c < a.n_caps; ++c) {
             const int miss = n_unique - hits[c];
-            const int64_t cl = (int64_t)c * a.n_layers + layer;
-            a.out_miss[cl * a.steps_total + g] = (uint8_t)miss;
-            a.total_miss[cl] += (unsigned long long)miss;
-            a.bytes_fetched[cl] += (unsigned long long)miss * a.expert_bytes;
+            a.out_miss[((int64_t)c * a.n_layers + layer) * a.steps_total + g] = (uint8_t)miss;
+            ts.tot[c][layer] += (unsigned long long)miss;
         }
     }
 }
@@ -155,9 +177,12 @@ template <int XCH>
 __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
 {
     __shared__ float hl[DC_MAX_KI];
+    __shared__ float lz[128];      // logits of the current layer-step
     __shared__ int sel_e[8];
     __shared__ float sel_w[8];
+    __shared__ float sel_z[9];
     __shared__ int bar_ok;
+    __shared__ TraceLds ts;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int G = gridDim.x;
@@ -165,13 +190,32 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
     const int gw = blockIdx.x * DC_WAVES + wave;  // this wavefront's global index
     const int H = a.H, N = a.N, I = a.I, K = a.K;
     const int segs = H / DC_SEG;
-    constexpr int xch = XCH;                    // 16-byte x chunks per lane (H = 512 * XCH)
     const int KI = K * I;
     const int items_per_wave = (KI + W - 1) / W;
     const int rows_per_wave = (H + W - 1) / W;
     const int dchunks = KI / 8;                 // 16-byte chunks of one output row's K down rows
     const int chunks_per_row = I / 8;
+    const bool stats_wave = blockIdx.x == G - 1 && wave == DC_WAVES - 1;
+    const int n_items1 = N * segs;              // router work items: (expert, 256-wide segment)
     uint32_t phase = 0;
+
+    if (blockIdx.x == G - 1) {                  // trace state -> LDS
+        for (int q = tid; q < a.n_layers * 128; q += DC_THREADS) {
+            const int l = q >> 7, e = q & 127;
+            ts.last[l][e] = (e < N) ? a.lru_state[l * N + e] : 0u;
+        }
+        for (int q = tid; q < a.n_layers; q += DC_THREADS) {
+            ts.sum_ov[q] = a.sum_overlap[q];
+            for (int c = 0; c < a.n_caps; ++c) ts.tot[c][q] = a.total_miss[c * a.n_layers + q];
+        }
+    }
+    __syncthreads();
+
+    // the router row segment of this wavefront's first work item of the NEXT layer is fetched ahead
+    floatx4_t wr_pf = {0.f, 0.f, 0.f, 0.f};
+    const int e1 = gw / segs, k1 = (gw - e1 * segs) * DC_SEG + lane * 4;
+    if (gw < n_items1)
+        wr_pf = *reinterpret_cast<const floatx4_t *>(static_cast<const float *>(a.layers[0]) + (int64_t)e1 * H + k1);
 
 #pragma unroll 1
     for (int64_t s = 0; s < a.n_steps; ++s) {
@@ -186,58 +230,70 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
 
             // ---- phase 1: partial router logits --------------------------------------------------
 #pragma unroll 1
-            for (int item = gw; item < N * segs; item += W) {
+            for (int item = gw; item < n_items1; item += W) {
                 const int e = item / segs, sg = item - e * segs;
                 const int k0 = sg * DC_SEG + lane * 4;
-                const floatx4_t wv = *reinterpret_cast<const floatx4_t *>(w_router + (int64_t)e * H + k0);
+                floatx4_t wv = wr_pf;
+                if (item != gw) wv = *reinterpret_cast<const floatx4_t *>(w_router + (int64_t)e * H + k0);
                 const uint2 xb = *reinterpret_cast<const uint2 *>(xg + k0);
                 float p = wv.x * __uint_as_float(xb.x << 16);
                 p = fmaf(wv.y, __uint_as_float(xb.x & 0xFFFF0000u), p);
                 p = fmaf(wv.z, __uint_as_float(xb.y << 16), p);
                 p = fmaf(wv.w, __uint_as_float(xb.y & 0xFFFF0000u), p);
                 p = wave_sum(p);
-                if (lane == 0) a.logit_part[item] = p;
+                if (lane == 0) put_shared(&a.logit_part[item], p);
             }
             // this lane's share of x, widened once per layer-step: chunk c covers k = (c*64 + lane)*8 ..
             float xr[XCH][8];
 #pragma unroll
             for (int c = 0; c < XCH; ++c) {
-                if (c < xch) {
-                    const u32x4_t xb = *reinterpret_cast<const u32x4_t *>(xg + (c * 64 + lane) * 8);
-                    xr[c][0] = __uint_as_float(xb.x << 16); xr[c][1] = __uint_as_float(xb.x & 0xFFFF0000u);
-                    xr[c][2] = __uint_as_float(xb.y << 16); xr[c][3] = __uint_as_float(xb.y & 0xFFFF0000u);
-                    xr[c][4] = __uint_as_float(xb.z << 16); xr[c][5] = __uint_as_float(xb.z & 0xFFFF0000u);
-                    xr[c][6] = __uint_as_float(xb.w << 16); xr[c][7] = __uint_as_float(xb.w & 0xFFFF0000u);
-                }
+                const u32x4_t xb = *reinterpret_cast<const u32x4_t *>(xg + (c * 64 + lane) * 8);
+                xr[c][0] = __uint_as_float(xb.x << 16); xr[c][1] = __uint_as_float(xb.x & 0xFFFF0000u);
+                xr[c][2] = __uint_as_float(xb.y << 16); xr[c][3] = __uint_as_float(xb.y & 0xFFFF0000u);
+                xr[c][4] = __uint_as_float(xb.z << 16); xr[c][5] = __uint_as_float(xb.z & 0xFFFF0000u);
+                xr[c][6] = __uint_as_float(xb.w << 16); xr[c][7] = __uint_as_float(xb.w & 0xFFFF0000u);
             }
             if (!grid_barrier(a, ++phase * (uint32_t)G, &bar_ok)) return;
 
-            // ---- top-k and softmax (wavefront 0 of every workgroup, same result everywhere) ---------
+            // ---- top-k and softmax by rank counting (wavefront 0 of every workgroup) -----------------
+            // Expert e's rank is the number of experts that beat it (larger logit, or equal logit and
+            // lower id); ranks 0..K-1 are the selection, already in descending-logit order.
             if (wave == 0) {
                 const float NEG_INF = -__builtin_inff();
                 float v0 = NEG_INF, v1 = NEG_INF;
                 if (lane < N) {
                     v0 = 0.f;
-                    for (int q = 0; q < segs; ++q) v0 += a.logit_part[lane * segs + q];
+                    for (int q = 0; q < segs; ++q) v0 += get_shared(&a.logit_part[lane * segs + q]);
                 }
                 if (lane + 64 < N) {
                     v1 = 0.f;
-                    for (int q = 0; q < segs; ++q) v1 += a.logit_part[(lane + 64) * segs + q];
+                    for (int q = 0; q < segs; ++q) v1 += get_shared(&a.logit_part[(lane + 64) * segs + q]);
                 }
-                const TopKResult r = wave_topk_softmax(v0, v1, N, K, a.renorm, lane);
+                lz[lane] = v0;
+                lz[lane + 64] = v1;
+                int r0 = 0, r1 = 0;
+                for (int q = 0; q < N; ++q) {
+                    const float zq = lz[q];          // LDS broadcast
+                    r0 += (zq > v0) || (zq == v0 && q < lane);
+                    r1 += (zq > v1) || (zq == v1 && q < lane + 64);
+                }
+                if (lane < N && r0 <= K) { sel_z[r0] = v0; if (r0 < K) sel_e[r0] = lane; }
+                if (lane + 64 < N && r1 <= K) { sel_z[r1] = v1; if (r1 < K) sel_e[r1] = lane + 64; }
+                const float zmax = sel_z[0];
+                const float den = wave_sum(((lane < N) ? expf(v0 - zmax) : 0.f) + ((lane + 64 < N) ? expf(v1 - zmax) : 0.f));
+                const float my_p = (lane < K) ? expf(sel_z[lane] - zmax) : 0.f;
+                float wgt = my_p / den;
+                if (a.renorm) wgt = my_p / wave_sum(my_p);
                 if (lane < K) {
-                    sel_e[lane] = r.expert;
-                    sel_w[lane] = r.weight;
+                    sel_w[lane] = wgt;
                     if (blockIdx.x == 0) {
                         const int64_t o = ((int64_t)layer * a.steps_total + g) * K + lane;
-                        a.out_idx[o] = r.expert;
-                        a.out_w[o] = r.weight;
+                        a.out_idx[o] = sel_e[lane];
+                        a.out_w[o] = wgt;
                     }
                 }
             }
             __syncthreads();
-            if (blockIdx.x == G - 1 && wave == DC_WAVES - 1)
-                online_trace_stats(a, layer, g, (lane < K) ? sel_e[lane] : -1, lane);
 
             // ---- phase 2: gate / up rows of the selected experts, SwiGLU -----------------------------
             // Row bases are wave-uniform (scalar registers); a lane adds its own 32-bit offset.
@@ -262,6 +318,8 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                             }
                         }
                     }
+                    // the statistics ride on the latency of the loads just issued
+                    if (ib == 0 && stats_wave) online_trace_stats(a, ts, layer, g, sel_e, lane);
 #pragma unroll
                     for (int b = 0; b < DC_ITEM_BATCH; ++b) {
                         const int item = item0 + ib + b;
@@ -274,7 +332,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                             }
                             gs = wave_sum(gs);
                             us = wave_sum(us);
-                            if (lane == 0) a.hbuf[item] = gs / (1.0f + expf(-gs)) * us;
+                            if (lane == 0) put_shared(&a.hbuf[item], gs / (1.0f + expf(-gs)) * us);
                         }
                     }
                 }
@@ -284,27 +342,28 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
             // Chunk q = c * 64 + lane of the concatenated K rows belongs to expert j = q / (I / 8) and
             // multiplies h[q * 8 .. q * 8 + 7]; its address is a 32-bit byte offset from w_down.
             u32x4_t dv[DC_MAX_DCH];
-            uint32_t doff[DC_MAX_DCH];
             const int row_first = gw * rows_per_wave;
             const char *wd_bytes = reinterpret_cast<const char *>(w_down);
 #pragma unroll
             for (int c = 0; c < DC_MAX_DCH; ++c) {
                 const int q = c * 64 + lane;
-                doff[c] = 0u;
                 if (q < dchunks && row_first < H) {
                     const int j = q / chunks_per_row, pos = (q - j * chunks_per_row) * 8;
-                    doff[c] = (uint32_t)((((int64_t)sel_e[j] * H + row_first) * I + pos) * 2);
-                    dv[c] = *reinterpret_cast<const u32x4_t *>(wd_bytes + doff[c]);
+                    const uint32_t off = (uint32_t)((((int64_t)sel_e[j] * H + row_first) * I + pos) * 2);
+                    dv[c] = *reinterpret_cast<const u32x4_t *>(wd_bytes + off);
                 }
             }
             if (!grid_barrier(a, ++phase * (uint32_t)G, &bar_ok)) return;
 
             // ---- phase 3: down projection; h is staged in LDS already multiplied by the gate weight ----
-            for (int q = tid * 4; q < KI; q += DC_THREADS * 4) {
-                floatx4_t hv = *reinterpret_cast<const floatx4_t *>(&a.hbuf[q]);
-                const float wj = sel_w[q / I];      // I % 8 == 0: the four values belong to one expert
-                hv.x *= wj; hv.y *= wj; hv.z *= wj; hv.w *= wj;
-                *reinterpret_cast<floatx4_t *>(&hl[q]) = hv;
+            for (int q = tid; q < KI; q += DC_THREADS) hl[q] = get_shared(&a.hbuf[q]) * sel_w[q / I];
+            // router row segment of the next layer-step, in flight across the last barrier
+            {
+                int nl = layer + 1;
+                if (nl == a.n_layers) nl = 0;
+                if (gw < n_items1)
+                    wr_pf = *reinterpret_cast<const floatx4_t *>(static_cast<const float *>(a.layers[nl * 4]) +
+                                                                 (int64_t)e1 * H + k1);
             }
             __syncthreads();
 #pragma unroll 1
@@ -317,7 +376,11 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                     const int q = c * 64 + lane;
                     if (q < dchunks) {
                         u32x4_t wv = dv[c];
-                        if (rw > 0) wv = *reinterpret_cast<const u32x4_t *>(wd_bytes + doff[c] + (uint32_t)(rw * I * 2));
+                        if (rw > 0) {   // further rows of this wavefront are fetched on the spot
+                            const int j = q / chunks_per_row, pos = (q - j * chunks_per_row) * 8;
+                            const uint32_t off = (uint32_t)((((int64_t)sel_e[j] * H + o) * I + pos) * 2);
+                            wv = *reinterpret_cast<const u32x4_t *>(wd_bytes + off);
+                        }
                         acc = dot8(wv, &hl[q * 8], acc);
                     }
                 }
@@ -325,6 +388,21 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                 if (lane == 0) a.y[(g * a.n_layers + layer) * H + o] = f32_to_bf16(acc);
             }
             if (!grid_barrier(a, ++phase * (uint32_t)G, &bar_ok)) return;
+        }
+    }
+
+    if (blockIdx.x == G - 1) {                  // trace state back to device memory
+        __syncthreads();
+        for (int q = tid; q < a.n_layers * 128; q += DC_THREADS) {
+            const int l = q >> 7, e = q & 127;
+            if (e < N) a.lru_state[l * N + e] = ts.last[l][e];
+        }
+        for (int q = tid; q < a.n_layers; q += DC_THREADS) {
+            a.sum_overlap[q] = ts.sum_ov[q];
+            for (int c = 0; c < a.n_caps; ++c) {
+                a.total_miss[c * a.n_layers + q] = ts.tot[c][q];
+                a.bytes_fetched[c * a.n_layers + q] = ts.tot[c][q] * a.expert_bytes;
+            }
         }
     }
 }
@@ -351,6 +429,8 @@ remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream)
         return fail(REMOE_E_UNSUPPORTED, "decode supports hidden in {512, 1024, 2048, 4096} (got %d)", d.H);
     if (d.I % 8 != 0 || d.K * d.I > DC_MAX_KI)
         return fail(REMOE_E_UNSUPPORTED, "decode needs inter %% 8 == 0 and top_k * inter <= %d", DC_MAX_KI);
+    if (d.n_layers > DC_MAX_LAYERS)
+        return fail(REMOE_E_UNSUPPORTED, "decode keeps the trace state of at most %d layers (got %d)", DC_MAX_LAYERS, d.n_layers);
     if (d.n_caps < 0 || d.n_caps > DC_MAX_CAPS)
         return fail(REMOE_E_INVALID_ARG, "n_caps %d outside 0..%d", d.n_caps, DC_MAX_CAPS);
     int dev = 0, n_cu = 0;
