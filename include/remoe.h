@@ -199,8 +199,8 @@ remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps,
  *   out_overlap     [n_layers, steps_total] uint8;  out_miss [n_caps, n_layers, steps_total] uint8
  *   sum_overlap     [n_layers] uint64;  total_miss, bytes_fetched [n_caps, n_layers] uint64:
  *                   running sums, ADDED to by every call (zero them before the first)
- *   workspace       remoe_decode_workspace_bytes(desc) bytes, 256-byte aligned.  Its first word is the
- *                   grid-barrier counter and the word at byte 128 an abort flag: non-zero after the
+ *   workspace       remoe_decode_workspace_bytes(desc) bytes, 256-byte aligned.  The 32-bit word at
+ *                   byte 128 is an abort flag: non-zero after the
  *                   call has completed means a wait inside the kernel exceeded `spin_limit_us` and
  *                   the outputs of this call are invalid (every workgroup still exits).
  *   spin_limit_us   upper bound of a single grid-barrier wait in microseconds (0 = 2 seconds)

@@ -35,6 +35,8 @@ constexpr int DC_WAVES = DC_THREADS / 64;
 constexpr int DC_SEG = 256;          // router row segment per wavefront (floats)
 constexpr int DC_MAX_KI = 6144;      // K * I floats of h staged in LDS (24 KB)
 constexpr int DC_MAX_CAPS = 4;
+constexpr int DC_MAX_GRID = 1024;     // workgroups the flag barrier can hold
+constexpr int DC_FLAG_BYTES = 256 + DC_MAX_GRID * 4;   // abort flag at byte 128, flags from byte 256
 constexpr int DC_MAX_LAYERS = 64;     // trace state of all layers is kept in LDS
 constexpr int DC_ITEM_BATCH = 3;     // gate/up activations a wavefront has in flight
 constexpr int DC_MAX_DCH = 12;       // down-projection chunks per lane per output row (K * I <= 6144)
@@ -58,7 +60,7 @@ struct DecodeArgs {
     unsigned long long *bytes_fetched; // [n_caps, L]
     float *logit_part;           // [N * H / DC_SEG]
     float *hbuf;                 // [K * I]
-    uint32_t *bar;               // grid barrier counter, zero at launch
+    uint32_t *bar;               // grid barrier flags, one per workgroup, zero at launch
     uint32_t *abort_flag;        // zero at launch
     unsigned long long spin_limit;   // wall-clock ticks (100 MHz) a single wait may last
 };
@@ -75,27 +77,34 @@ __device__ __forceinline__ float get_shared(const float *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Grid-wide barrier.  The workgroup barrier in front makes every wavefront wait for its own stores
-// (they are complete at agent scope then); one thread adds 1 to the counter and polls it until it
-// reaches `target`.  Returns false when the grid is aborting.
-__device__ __forceinline__ bool grid_barrier(const DecodeArgs &a, uint32_t target, int *lds_flag)
+// Grid-wide barrier without read-modify-write traffic: workgroup b publishes the number of the phase
+// it has finished in flags[b]; wavefront 0 of every workgroup polls all flags (each lane a few of
+// them) until none is behind.  The workgroup barrier in front makes every wavefront wait for its own
+// stores first (they are complete at agent scope then).  Returns false when the grid is aborting.
+__device__ __forceinline__ bool grid_barrier(const DecodeArgs &a, uint32_t phase, int *lds_flag)
 {
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        const int G = gridDim.x;
+        if (lane == 0) __hip_atomic_store(&a.bar[blockIdx.x], phase, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int ok = 1;
-        __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (__hip_atomic_load(a.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            const unsigned long long t0 = wall_clock64();
-            while (__hip_atomic_load(a.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-                if (__hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { ok = 0; break; }
-                if (wall_clock64() - t0 > a.spin_limit) {
-                    __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    ok = 0;
-                    break;
-                }
+        unsigned long long t0 = 0;
+        bool timing = false;
+        for (;;) {
+            bool behind = false;
+            for (int q = lane; q < G; q += 64)
+                behind |= __hip_atomic_load(&a.bar[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < phase;
+            if (!__any(behind)) break;
+            if (!timing) { t0 = wall_clock64(); timing = true; }
+            if (__hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { ok = 0; break; }
+            if (wall_clock64() - t0 > a.spin_limit) {
+                __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
+                break;
             }
         }
-        *lds_flag = ok;
+        if (lane == 0) *lds_flag = ok;
     }
     __syncthreads();
     return *lds_flag != 0;
@@ -178,6 +187,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
 {
     __shared__ float hl[DC_MAX_KI];
     __shared__ float lz[128];      // logits of the current layer-step
+    __shared__ float lpart[128 * 16];   // their per-segment partial sums (H <= 4096)
     __shared__ int sel_e[8];
     __shared__ float sel_w[8];
     __shared__ float sel_z[9];
@@ -253,21 +263,24 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                 xr[c][4] = __uint_as_float(xb.z << 16); xr[c][5] = __uint_as_float(xb.z & 0xFFFF0000u);
                 xr[c][6] = __uint_as_float(xb.w << 16); xr[c][7] = __uint_as_float(xb.w & 0xFFFF0000u);
             }
-            if (!grid_barrier(a, ++phase * (uint32_t)G, &bar_ok)) return;
+            if (!grid_barrier(a, ++phase, &bar_ok)) return;
 
             // ---- top-k and softmax by rank counting (wavefront 0 of every workgroup) -----------------
             // Expert e's rank is the number of experts that beat it (larger logit, or equal logit and
             // lower id); ranks 0..K-1 are the selection, already in descending-logit order.
+            // all threads fetch the partial logits at once (one memory round trip), wavefront 0 sums them
+            for (int q = tid; q < n_items1; q += DC_THREADS) lpart[q] = get_shared(&a.logit_part[q]);
+            __syncthreads();
             if (wave == 0) {
                 const float NEG_INF = -__builtin_inff();
                 float v0 = NEG_INF, v1 = NEG_INF;
                 if (lane < N) {
                     v0 = 0.f;
-                    for (int q = 0; q < segs; ++q) v0 += get_shared(&a.logit_part[lane * segs + q]);
+                    for (int q = 0; q < segs; ++q) v0 += lpart[lane * segs + q];
                 }
                 if (lane + 64 < N) {
                     v1 = 0.f;
-                    for (int q = 0; q < segs; ++q) v1 += get_shared(&a.logit_part[(lane + 64) * segs + q]);
+                    for (int q = 0; q < segs; ++q) v1 += lpart[(lane + 64) * segs + q];
                 }
                 lz[lane] = v0;
                 lz[lane + 64] = v1;
@@ -353,10 +366,22 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                     dv[c] = *reinterpret_cast<const u32x4_t *>(wd_bytes + off);
                 }
             }
-            if (!grid_barrier(a, ++phase * (uint32_t)G, &bar_ok)) return;
+            if (!grid_barrier(a, ++phase, &bar_ok)) return;
 
             // ---- phase 3: down projection; h is staged in LDS already multiplied by the gate weight ----
-            for (int q = tid; q < KI; q += DC_THREADS) hl[q] = get_shared(&a.hbuf[q]) * sel_w[q / I];
+            for (int q0 = tid; q0 < KI; q0 += DC_THREADS * 4) {
+                float hv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {          // four loads in flight per thread
+                    const int q = q0 + u * DC_THREADS;
+                    hv[u] = (q < KI) ? get_shared(&a.hbuf[q]) : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = q0 + u * DC_THREADS;
+                    if (q < KI) hl[q] = hv[u] * sel_w[q / I];
+                }
+            }
             // router row segment of the next layer-step, in flight across the last barrier
             {
                 int nl = layer + 1;
@@ -387,7 +412,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                 acc = wave_sum(acc);
                 if (lane == 0) a.y[(g * a.n_layers + layer) * H + o] = f32_to_bf16(acc);
             }
-            if (!grid_barrier(a, ++phase * (uint32_t)G, &bar_ok)) return;
+            if (!grid_barrier(a, ++phase, &bar_ok)) return;
         }
     }
 
@@ -407,17 +432,17 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
     }
 }
 
-__global__ void decode_clear_flags(uint32_t *bar, uint32_t *abort_flag)
+__global__ void decode_clear_flags(uint32_t *bar, int n, uint32_t *abort_flag)
 {
-    *bar = 0u;
-    *abort_flag = 0u;
+    for (int q = threadIdx.x; q < n; q += blockDim.x) bar[q] = 0u;
+    if (threadIdx.x == 0) *abort_flag = 0u;
 }
 
 }  // namespace
 
 size_t decode_workspace_bytes(int H, int N, int I, int K)
 {
-    size_t off = 256;                                            // barrier counter + abort flag
+    size_t off = DC_FLAG_BYTES;                                  // abort flag + barrier flags
     off += align_up(sizeof(float) * (size_t)N * (H / DC_SEG), 256);
     off += align_up(sizeof(float) * (size_t)K * I, 256);
     return off;
@@ -465,13 +490,14 @@ remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream)
     a.total_miss = reinterpret_cast<unsigned long long *>(d.total_miss);
     a.bytes_fetched = reinterpret_cast<unsigned long long *>(d.bytes_fetched);
     char *ws = static_cast<char *>(d.workspace);
-    a.bar = reinterpret_cast<uint32_t *>(ws);
+    if (G > DC_MAX_GRID) return fail(REMOE_E_UNSUPPORTED, "decode: %d compute units exceed the barrier's %d flags", G, DC_MAX_GRID);
     a.abort_flag = reinterpret_cast<uint32_t *>(ws + 128);
-    a.logit_part = reinterpret_cast<float *>(ws + 256);
-    a.hbuf = reinterpret_cast<float *>(ws + 256 + align_up(sizeof(float) * (size_t)d.N * (d.H / DC_SEG), 256));
+    a.bar = reinterpret_cast<uint32_t *>(ws + 256);
+    a.logit_part = reinterpret_cast<float *>(ws + DC_FLAG_BYTES);
+    a.hbuf = reinterpret_cast<float *>(ws + DC_FLAG_BYTES + align_up(sizeof(float) * (size_t)d.N * (d.H / DC_SEG), 256));
     a.spin_limit = d.spin_limit_ticks;
 
-    hipLaunchKernelGGL(decode_clear_flags, dim3(1), dim3(1), 0, stream, a.bar, a.abort_flag);
+    hipLaunchKernelGGL(decode_clear_flags, dim3(1), dim3(256), 0, stream, a.bar, G, a.abort_flag);
     void *params[] = {&a};
     const void *fn = nullptr;
     switch (d.H / 512) {
