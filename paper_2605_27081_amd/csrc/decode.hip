@@ -92,12 +92,14 @@ __device__ __forceinline__ bool grid_barrier(const DecodeArgs &a, uint32_t phase
         unsigned long long t0 = 0;
         bool timing = false;
         for (;;) {
+            // one memory round trip per poll: the abort flag travels with the flags
+            const uint32_t ab = __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             bool behind = false;
             for (int q = lane; q < G; q += 64)
                 behind |= __hip_atomic_load(&a.bar[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < phase;
             if (!__any(behind)) break;
             if (!timing) { t0 = wall_clock64(); timing = true; }
-            if (__hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { ok = 0; break; }
+            if (ab) { ok = 0; break; }
             if (wall_clock64() - t0 > a.spin_limit) {
                 __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 ok = 0;
@@ -188,6 +190,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
     __shared__ float hl[DC_MAX_KI];
     __shared__ float lz[128];      // logits of the current layer-step
     __shared__ float lpart[128 * 16];   // their per-segment partial sums (H <= 4096)
+    __shared__ int rank_part[DC_WAVES][128];
     __shared__ int sel_e[8];
     __shared__ float sel_w[8];
     __shared__ float sel_z[9];
@@ -265,13 +268,14 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
             }
             if (!grid_barrier(a, ++phase, &bar_ok)) return;
 
-            // ---- top-k and softmax by rank counting (wavefront 0 of every workgroup) -----------------
+            // ---- top-k and softmax by rank counting (every workgroup, same result everywhere) -------
             // Expert e's rank is the number of experts that beat it (larger logit, or equal logit and
             // lower id); ranks 0..K-1 are the selection, already in descending-logit order.
-            // all threads fetch the partial logits at once (one memory round trip), wavefront 0 sums them
+            // All threads fetch the partial logits at once (one memory round trip); every wavefront sums
+            // all N logits (cheap) and counts, for its 1/8 of the experts q, how many beat expert e.
             for (int q = tid; q < n_items1; q += DC_THREADS) lpart[q] = get_shared(&a.logit_part[q]);
             __syncthreads();
-            if (wave == 0) {
+            {
                 const float NEG_INF = -__builtin_inff();
                 float v0 = NEG_INF, v1 = NEG_INF;
                 if (lane < N) {
@@ -282,14 +286,24 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                     v1 = 0.f;
                     for (int q = 0; q < segs; ++q) v1 += lpart[(lane + 64) * segs + q];
                 }
-                lz[lane] = v0;
-                lz[lane + 64] = v1;
+                if (wave == 0) { lz[lane] = v0; lz[lane + 64] = v1; }
+                // this wavefront compares against experts q = wave, wave + 8, ...; the logit of q sits in
+                // lane q & 63 (v0 or v1), so it is fetched with a lane read instead of LDS
                 int r0 = 0, r1 = 0;
-                for (int q = 0; q < N; ++q) {
-                    const float zq = lz[q];          // LDS broadcast
+                for (int q = wave; q < N; q += DC_WAVES) {
+                    const float zq = __shfl((q < 64) ? v0 : v1, q & 63, 64);
                     r0 += (zq > v0) || (zq == v0 && q < lane);
                     r1 += (zq > v1) || (zq == v1 && q < lane + 64);
                 }
+                rank_part[wave][lane] = r0;
+                rank_part[wave][lane + 64] = r1;
+            }
+            __syncthreads();
+            if (wave == 0) {
+                const float v0 = lz[lane], v1 = lz[lane + 64];
+                int r0 = 0, r1 = 0;
+#pragma unroll
+                for (int w = 0; w < DC_WAVES; ++w) { r0 += rank_part[w][lane]; r1 += rank_part[w][lane + 64]; }
                 if (lane < N && r0 <= K) { sel_z[r0] = v0; if (r0 < K) sel_e[r0] = lane; }
                 if (lane + 64 < N && r1 <= K) { sel_z[r1] = v1; if (r1 < K) sel_e[r1] = lane + 64; }
                 const float zmax = sel_z[0];
