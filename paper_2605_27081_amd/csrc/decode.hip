@@ -58,7 +58,7 @@ struct DecodeArgs {
     unsigned long long *sum_overlap;   // [L]
     unsigned long long *total_miss;    // [n_caps, L]
     unsigned long long *bytes_fetched; // [n_caps, L]
-    float *logit_part;           // [N * H / DC_SEG]
+    unsigned long long *logit_part;   // [N * H / DC_SEG] (phase tag << 32) | float bits
     float *hbuf;                 // [K * I]
     uint32_t *bar;               // grid barrier flags, one per workgroup, zero at launch
     uint32_t *abort_flag;        // zero at launch
@@ -75,6 +75,13 @@ __device__ __forceinline__ void put_shared(float *p, float v)
 __device__ __forceinline__ float get_shared(const float *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A value and the number of the phase that produced it, as one 8-byte word.
+__device__ __forceinline__ void put_tagged(unsigned long long *p, float v, uint32_t tag)
+{
+    __hip_atomic_store(p, ((unsigned long long)tag << 32) | __float_as_uint(v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Grid-wide barrier without read-modify-write traffic: workgroup b publishes the number of the phase
@@ -110,6 +117,38 @@ __device__ __forceinline__ bool grid_barrier(const DecodeArgs &a, uint32_t phase
     }
     __syncthreads();
     return *lds_flag != 0;
+}
+
+// Rendezvous on tagged values: every thread polls its share of the n words until all of them carry
+// `tag`, leaving the values in LDS.  Returns false when the grid is aborting.
+__device__ __forceinline__ bool gather_tagged(const DecodeArgs &a, float *dst, int n, uint32_t tag, int *lds_flag)
+{
+    unsigned long long t0 = 0;
+    bool timing = false;
+    for (;;) {
+        uint32_t ab = 0;
+        if (threadIdx.x == 0) ab = __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        bool behind = false;
+        for (int q = threadIdx.x; q < n; q += DC_THREADS) {
+            const unsigned long long w = __hip_atomic_load(&a.logit_part[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((uint32_t)(w >> 32) == tag) dst[q] = __uint_as_float((uint32_t)w);
+            else behind = true;
+        }
+        if (threadIdx.x == 0) {
+            int ok = 1;
+            if (ab) ok = 0;
+            if (!timing) { t0 = wall_clock64(); timing = true; }
+            else if (wall_clock64() - t0 > a.spin_limit) {
+                __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
+            }
+            *lds_flag = ok;
+        }
+        const int any_behind = __syncthreads_or(behind ? 1 : 0);
+        if (!*lds_flag) return false;
+        if (!any_behind) return true;
+        __syncthreads();      // lds_flag is rewritten in the next round
+    }
 }
 
 __device__ __forceinline__ float dot8(const u32x4_t w, const float *xv, float acc)
@@ -254,7 +293,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                 p = fmaf(wv.z, __uint_as_float(xb.y << 16), p);
                 p = fmaf(wv.w, __uint_as_float(xb.y & 0xFFFF0000u), p);
                 p = wave_sum(p);
-                if (lane == 0) put_shared(&a.logit_part[item], p);
+                if (lane == 0) put_tagged(&a.logit_part[item], p, phase + 1);
             }
             // this lane's share of x, widened once per layer-step: chunk c covers k = (c*64 + lane)*8 ..
             float xr[XCH][8];
@@ -266,15 +305,15 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                 xr[c][4] = __uint_as_float(xb.z << 16); xr[c][5] = __uint_as_float(xb.z & 0xFFFF0000u);
                 xr[c][6] = __uint_as_float(xb.w << 16); xr[c][7] = __uint_as_float(xb.w & 0xFFFF0000u);
             }
-            if (!grid_barrier(a, ++phase, &bar_ok)) return;
+            // ---- first grid-wide rendezvous: the partial logits carry the phase number as a tag, so
+            // polling for them IS the barrier (one memory round trip once the last one is written) ------
+            ++phase;
+            if (!gather_tagged(a, lpart, n_items1, phase, &bar_ok)) return;
 
             // ---- top-k and softmax by rank counting (every workgroup, same result everywhere) -------
-            // Expert e's rank is the number of experts that beat it (larger logit, or equal logit and
-            // lower id); ranks 0..K-1 are the selection, already in descending-logit order.
-            // All threads fetch the partial logits at once (one memory round trip); every wavefront sums
-            // all N logits (cheap) and counts, for its 1/8 of the experts q, how many beat expert e.
-            for (int q = tid; q < n_items1; q += DC_THREADS) lpart[q] = get_shared(&a.logit_part[q]);
-            __syncthreads();
+            // Every wavefront sums all N logits (cheap) and counts, for its 1/8 of the experts q, how many
+            // beat expert e (larger logit, or equal logit and lower id); ranks 0..K-1 are the selection,
+            // already in descending-logit order.
             {
                 const float NEG_INF = -__builtin_inff();
                 float v0 = NEG_INF, v1 = NEG_INF;
@@ -323,61 +362,66 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
             __syncthreads();
 
             // ---- phase 2: gate / up rows of the selected experts, SwiGLU -----------------------------
-            // Row bases are wave-uniform (scalar registers); a lane adds its own 32-bit offset.
-            {
-                const int item0 = gw * items_per_wave;
-                const int loff = lane * 8;
-#pragma unroll 1
-                for (int ib = 0; ib < items_per_wave; ib += DC_ITEM_BATCH) {
-                    u32x4_t gv[DC_ITEM_BATCH][XCH], uv[DC_ITEM_BATCH][XCH];
-#pragma unroll
-                    for (int b = 0; b < DC_ITEM_BATCH; ++b) {
-                        const int item = item0 + ib + b;
-                        if (ib + b < items_per_wave && item < KI) {
-                            const int j = item / I, i = item - j * I;
-                            const int e = __builtin_amdgcn_readfirstlane(sel_e[j]);
-                            const bf16_t *gp = w_gate + ((int64_t)e * I + i) * H;
-                            const bf16_t *up = w_up + ((int64_t)e * I + i) * H;
-#pragma unroll
-                            for (int c = 0; c < XCH; ++c) {
-                                gv[b][c] = *reinterpret_cast<const u32x4_t *>(gp + loff + c * 512);
-                                uv[b][c] = *reinterpret_cast<const u32x4_t *>(up + loff + c * 512);
-                            }
-                        }
-                    }
-                    // the statistics ride on the latency of the loads just issued
-                    if (ib == 0 && stats_wave) online_trace_stats(a, ts, layer, g, sel_e, lane);
-#pragma unroll
-                    for (int b = 0; b < DC_ITEM_BATCH; ++b) {
-                        const int item = item0 + ib + b;
-                        if (ib + b < items_per_wave && item < KI) {
-                            float gs = 0.f, us = 0.f;
-#pragma unroll
-                            for (int c = 0; c < XCH; ++c) {
-                                gs = dot8(gv[b][c], xr[c], gs);
-                                us = dot8(uv[b][c], xr[c], us);
-                            }
-                            gs = wave_sum(gs);
-                            us = wave_sum(us);
-                            if (lane == 0) put_shared(&a.hbuf[item], gs / (1.0f + expf(-gs)) * us);
-                        }
-                    }
-                }
-            }
-
-            // ---- phase 3 prefetch: the K down rows of this wavefront's first output row ---------------
-            // Chunk q = c * 64 + lane of the concatenated K rows belongs to expert j = q / (I / 8) and
-            // multiplies h[q * 8 .. q * 8 + 7]; its address is a 32-bit byte offset from w_down.
+            // Row bases are wave-uniform (scalar registers); a lane adds its own 32-bit offset.  Two
+            // register sets roll over the wavefront's activations (the loads of the next one or two are
+            // in flight while one is reduced), and the down-projection rows of phase 3 are requested
+            // right behind the last of them, so HBM keeps streaming across the coming barrier.
             u32x4_t dv[DC_MAX_DCH];
             const int row_first = gw * rows_per_wave;
             const char *wd_bytes = reinterpret_cast<const char *>(w_down);
-#pragma unroll
-            for (int c = 0; c < DC_MAX_DCH; ++c) {
-                const int q = c * 64 + lane;
-                if (q < dchunks && row_first < H) {
-                    const int j = q / chunks_per_row, pos = (q - j * chunks_per_row) * 8;
-                    const uint32_t off = (uint32_t)((((int64_t)sel_e[j] * H + row_first) * I + pos) * 2);
-                    dv[c] = *reinterpret_cast<const u32x4_t *>(wd_bytes + off);
+#define DC_ISSUE_DOWN()                                                                              \
+    _Pragma("unroll") for (int c = 0; c < DC_MAX_DCH; ++c) {                                          \
+        const int q_ = c * 64 + lane;                                                                \
+        if (q_ < dchunks && row_first < H) {                                                         \
+            const int j_ = q_ / chunks_per_row, pos_ = (q_ - j_ * chunks_per_row) * 8;               \
+            const uint32_t off_ = (uint32_t)((((int64_t)sel_e[j_] * H + row_first) * I + pos_) * 2); \
+            dv[c] = *reinterpret_cast<const u32x4_t *>(wd_bytes + off_);                             \
+        }                                                                                            \
+    }
+            {
+                const int item0 = gw * items_per_wave;
+                int nit = KI - item0;
+                if (nit > items_per_wave) nit = items_per_wave;
+                const int loff = lane * 8;
+                u32x4_t gA[XCH], uA[XCH], gB[XCH], uB[XCH];
+#define DC_LOAD_ITEM(gv, uv, it)                                                                     \
+    {                                                                                                \
+        const int item_ = item0 + (it);                                                              \
+        const int j_ = item_ / I, i_ = item_ - j_ * I;                                               \
+        const int e_ = __builtin_amdgcn_readfirstlane(sel_e[j_]);                                    \
+        const bf16_t *gp_ = w_gate + ((int64_t)e_ * I + i_) * H;                                     \
+        const bf16_t *up_ = w_up + ((int64_t)e_ * I + i_) * H;                                       \
+        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                             \
+            gv[c] = *reinterpret_cast<const u32x4_t *>(gp_ + loff + c * 512);                        \
+            uv[c] = *reinterpret_cast<const u32x4_t *>(up_ + loff + c * 512);                        \
+        }                                                                                            \
+    }
+#define DC_REDUCE_ITEM(gv, uv, it)                                                                   \
+    {                                                                                                \
+        float gs_ = 0.f, us_ = 0.f;                                                                  \
+        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                             \
+            gs_ = dot8(gv[c], xr[c], gs_);                                                           \
+            us_ = dot8(uv[c], xr[c], us_);                                                           \
+        }                                                                                            \
+        gs_ = wave_sum(gs_);                                                                         \
+        us_ = wave_sum(us_);                                                                         \
+        if (lane == 0) put_shared(&a.hbuf[item0 + (it)], gs_ / (1.0f + expf(-gs_)) * us_);           \
+    }
+                bool down_issued = false;
+                if (nit > 0) DC_LOAD_ITEM(gA, uA, 0)
+                if (nit > 1) DC_LOAD_ITEM(gB, uB, 1)
+                if (nit <= 2) { DC_ISSUE_DOWN() down_issued = true; }
+                // the statistics ride on the latency of the loads just issued
+                if (stats_wave) online_trace_stats(a, ts, layer, g, sel_e, lane);
+#pragma unroll 1
+                for (int it = 0; it < nit; it += 2) {
+                    DC_REDUCE_ITEM(gA, uA, it)
+                    if (it + 2 < nit) DC_LOAD_ITEM(gA, uA, it + 2)
+                    if (!down_issued && it + 3 >= nit) { DC_ISSUE_DOWN() down_issued = true; }
+                    if (it + 1 < nit) {
+                        DC_REDUCE_ITEM(gB, uB, it + 1)
+                        if (it + 3 < nit) DC_LOAD_ITEM(gB, uB, it + 3)
+                    }
                 }
             }
             if (!grid_barrier(a, ++phase, &bar_ok)) return;
@@ -446,9 +490,10 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
     }
 }
 
-__global__ void decode_clear_flags(uint32_t *bar, int n, uint32_t *abort_flag)
+__global__ void decode_clear_flags(uint32_t *bar, int n, uint32_t *abort_flag, unsigned long long *tagged, int n_tagged)
 {
     for (int q = threadIdx.x; q < n; q += blockDim.x) bar[q] = 0u;
+    for (int q = threadIdx.x; q < n_tagged; q += blockDim.x) tagged[q] = 0ull;   // tag 0 = no phase
     if (threadIdx.x == 0) *abort_flag = 0u;
 }
 
@@ -457,7 +502,7 @@ __global__ void decode_clear_flags(uint32_t *bar, int n, uint32_t *abort_flag)
 size_t decode_workspace_bytes(int H, int N, int I, int K)
 {
     size_t off = DC_FLAG_BYTES;                                  // abort flag + barrier flags
-    off += align_up(sizeof(float) * (size_t)N * (H / DC_SEG), 256);
+    off += align_up(sizeof(unsigned long long) * (size_t)N * (H / DC_SEG), 256);
     off += align_up(sizeof(float) * (size_t)K * I, 256);
     return off;
 }
@@ -507,11 +552,12 @@ remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream)
     if (G > DC_MAX_GRID) return fail(REMOE_E_UNSUPPORTED, "decode: %d compute units exceed the barrier's %d flags", G, DC_MAX_GRID);
     a.abort_flag = reinterpret_cast<uint32_t *>(ws + 128);
     a.bar = reinterpret_cast<uint32_t *>(ws + 256);
-    a.logit_part = reinterpret_cast<float *>(ws + DC_FLAG_BYTES);
-    a.hbuf = reinterpret_cast<float *>(ws + DC_FLAG_BYTES + align_up(sizeof(float) * (size_t)d.N * (d.H / DC_SEG), 256));
+    a.logit_part = reinterpret_cast<unsigned long long *>(ws + DC_FLAG_BYTES);
+    a.hbuf = reinterpret_cast<float *>(ws + DC_FLAG_BYTES + align_up(sizeof(unsigned long long) * (size_t)d.N * (d.H / DC_SEG), 256));
     a.spin_limit = d.spin_limit_ticks;
 
-    hipLaunchKernelGGL(decode_clear_flags, dim3(1), dim3(256), 0, stream, a.bar, G, a.abort_flag);
+    hipLaunchKernelGGL(decode_clear_flags, dim3(1), dim3(256), 0, stream, a.bar, G, a.abort_flag, a.logit_part,
+                       d.N * (d.H / DC_SEG));
     void *params[] = {&a};
     const void *fn = nullptr;
     switch (d.H / 512) {
