@@ -37,8 +37,8 @@ def parse_args():
                     help="workload name (workload/configs.py); the headline is qwen3_prefill")
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers (0 = all; debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=96)
-    ap.add_argument("--cpu-sample-layers", type=int, default=2)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-sample-layers", type=int, default=12)
     return ap.parse_args()
 
 
