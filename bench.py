@@ -31,8 +31,9 @@ HBM_PEAK_GBS = 8000.0
 def parse_args():
     ap = argparse.ArgumentParser(description=__doc__)
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default 5 batched passes, or 1024 decode steps)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 1, or 32 decode steps)")
     ap.add_argument("--config", default="qwen3_prefill",
                     help="workload name (workload/configs.py); the headline is qwen3_prefill")
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers (0 = all; debugging)")
@@ -70,6 +71,10 @@ def main():
     torch.cuda.set_device(dev)
 
     cfg = wl.get_config(args.config)
+    if args.steps is None:
+        args.steps = 1024 if cfg.decode else 5
+    if args.warmup is None:
+        args.warmup = 32 if cfg.decode else 1
     if cfg.decode:
         from bench_decode import run_decode  # M=1 decode has its own driver
         return run_decode(args, cfg)

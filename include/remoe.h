@@ -205,8 +205,9 @@ remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps,
  *                   the outputs of this call are invalid (every workgroup still exits).
  *   spin_limit_us   upper bound of a single grid-barrier wait in microseconds (0 = 2 seconds)
  *
- * The launch is cooperative: one workgroup per compute unit, all resident.  Calls that share a
- * workspace or the state arrays must not overlap in time.
+ * The kernel is persistent: one workgroup per compute unit, all of which must be resident at once,
+ * so other work that holds compute units for long while it runs can trip the wait limit.  Calls
+ * that share a workspace or the state arrays must not overlap in time.
  */
 size_t remoe_decode_workspace_bytes(const remoe_layer_desc *desc);
 remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers,

@@ -113,7 +113,7 @@ remoe_status launch_combine(int dtype, const void *rows, const int32_t *pair_slo
                             int H, int64_t shared_row0, int has_shared, const void *x,
                             const float *ws_scale, void *y, hipStream_t stream);
 
-// M = 1 decode over all layers and a range of steps (persistent cooperative kernel).
+// M = 1 decode over all layers and a range of steps (persistent kernel, one workgroup per compute unit).
 struct DecodeLaunch {
     const void *const *layers;   // device [L][4]: w_router, w_gate, w_up, w_down
     const void *x;

@@ -521,7 +521,7 @@ remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream)
     REMOE_HIP_TRY(hipGetDevice(&dev));
     REMOE_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
     if (n_cu < 1) return fail(REMOE_E_HIP, "device reports no compute units");
-    // one workgroup per compute unit, all resident at once (the cooperative launch checks this)
+    // one workgroup per compute unit, all resident at once (checked against the occupancy below)
     const int G = n_cu;
     const int W = G * DC_WAVES;
     if ((d.K * d.I / 8 + 63) / 64 > DC_MAX_DCH)
@@ -567,7 +567,21 @@ remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream)
     case 8: fn = reinterpret_cast<const void *>(decode_kernel<8>); break;
     default: return fail(REMOE_E_UNSUPPORTED, "decode supports hidden in {512, 1024, 2048, 4096} (got %d)", d.H);
     }
-    REMOE_HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(G), dim3(DC_THREADS), params, 0, stream));
+    // The grid barrier needs every workgroup resident.  An ordinary launch of one workgroup per
+    // compute unit gives that once the occupancy query confirms a workgroup fits; should other work
+    // hold compute units for long, the bounded waits end the kernel with the abort word set instead
+    // of hanging.  (A cooperative launch would check the same, but kernel tracing tools on this
+    // software stack crash at process exit after one.)
+    // Unused dynamic LDS lifts the workgroup above half a compute unit's 160 KB, so that no two
+    // workgroups share a compute unit while another one idles.
+    hipFuncAttributes attr;
+    REMOE_HIP_TRY(hipFuncGetAttributes(&attr, fn));
+    const size_t half_lds = 80 * 1024 + 256;
+    const size_t pad = attr.sharedSizeBytes < half_lds ? half_lds - attr.sharedSizeBytes : 0;
+    int per_cu = 0;
+    REMOE_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, DC_THREADS, pad));
+    if (per_cu < 1) return fail(REMOE_E_UNSUPPORTED, "decode: a workgroup does not fit one compute unit");
+    REMOE_HIP_TRY(hipLaunchKernel(fn, dim3(G), dim3(DC_THREADS), params, pad, stream));
     return REMOE_OK;
 }
 
