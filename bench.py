@@ -38,6 +38,9 @@ def parse_args():
                     help="workload name (workload/configs.py); the headline is qwen3_prefill")
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers (0 = all; debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="before the run, copy this many MiB three times with the library's plain copy kernel "
+                         "(the yardstick when the run is profiled with hardware byte counters)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
     ap.add_argument("--cpu-sample-layers", type=int, default=12)
     return ap.parse_args()
@@ -69,6 +72,17 @@ def main():
         return 3
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.zeros_like(src)
+        for _ in range(3):
+            remoe.remoe_copy_probe(dst, src)
+        torch.cuda.synchronize()
+        if not torch.equal(dst, src):
+            print("bench.py: copy probe produced a wrong copy", file=sys.stderr)
+            return 4
+        del src, dst
 
     cfg = wl.get_config(args.config)
     if args.steps is None:

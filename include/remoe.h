@@ -81,6 +81,14 @@ typedef enum {
 remoe_status remoe_profile_enable(int32_t on);
 remoe_status remoe_profile_read(int32_t kind, double *total_ms, int64_t *launches, int32_t reset);
 
+/*
+ * Measurement aid: a plain device-to-device copy of `bytes` bytes (a multiple of 16; dst and src
+ * are 16-byte aligned device pointers that do not overlap), enqueued on `stream`.  It reads and
+ * writes exactly `bytes` bytes of HBM, so the value a hardware byte counter reports for it gives
+ * the factor by which that counter's readings for the other kernels are scaled.
+ */
+remoe_status remoe_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
+
 /* Bytes of workspace moe_forward needs for `n_tokens` tokens of this layer shape (0 on invalid
  * arguments, with remoe_last_error set).  Host call, no GPU work. */
 size_t remoe_workspace_bytes(const remoe_layer_desc *desc, int64_t n_tokens);

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     load_library,
     lru_simulate,
     moe_decode,
+    remoe_copy_probe,
     remoe_decode_workspace_bytes,
     moe_forward,
     moe_route,

@@ -70,6 +70,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_decode.restype = ctypes.c_int
     lib.moe_decode.argtypes = [D, I32, P, P, I64, I64, I64, P, P, P, I32, ctypes.POINTER(I32), U64,
                                P, P, P, P, P, P, P, SZ, U64, P]
+    lib.remoe_copy_probe.restype = ctypes.c_int
+    lib.remoe_copy_probe.argtypes = [P, P, SZ, P]
     lib.remoe_profile_enable.restype = ctypes.c_int
     lib.remoe_profile_enable.argtypes = [I32]
     lib.remoe_profile_read.restype = ctypes.c_int
@@ -158,6 +160,14 @@ def lru_simulate(idx: torch.Tensor, n_experts: int, capacity: int, expert_bytes:
     _check(load_library().lru_simulate(_ptr(idx), n_seq, n_steps, top_k, n_experts, capacity, expert_bytes,
                                        step0, _ptr(state), _ptr(out_miss), _ptr(out_total_miss),
                                        _ptr(out_bytes), _stream()))
+
+
+def remoe_copy_probe(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Plain copy of src into dst (same byte size): the yardstick for hardware byte counters."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise RemoeError("remoe_copy_probe: dst and src differ in size")
+    _check(load_library().remoe_copy_probe(_ptr(dst), _ptr(src), nbytes, _stream()))
 
 
 def remoe_decode_workspace_bytes(desc: LayerDesc) -> int:

@@ -209,6 +209,17 @@ remoe_status remoe_profile_read(int32_t kind, double *total_ms, int64_t *launche
     return REMOE_OK;
 }
 
+remoe_status remoe_copy_probe(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (bytes == 0) return REMOE_OK;
+    if (!dst || !src) return fail(REMOE_E_INVALID_ARG, "dst and src must not be NULL");
+    if ((bytes & 15) || (((uintptr_t)dst | (uintptr_t)src) & 15))
+        return fail(REMOE_E_INVALID_ARG, "copy probe needs 16-byte aligned pointers and a multiple of 16 bytes");
+    const uintptr_t d = (uintptr_t)dst, s = (uintptr_t)src;
+    if (d < s + bytes && s < d + bytes) return fail(REMOE_E_INVALID_ARG, "copy probe ranges overlap");
+    return launch_copy_probe(dst, src, bytes, static_cast<hipStream_t>(stream));
+}
+
 size_t remoe_workspace_bytes(const remoe_layer_desc *desc, int64_t n_tokens)
 {
     if (validate_layer_desc(desc) != REMOE_OK) return 0;

@@ -141,4 +141,7 @@ remoe_status launch_lru(const int32_t *idx, int64_t S, int64_t T, int K, int N, 
                         uint64_t expert_bytes, int64_t step0, uint32_t *state, uint8_t *miss,
                         uint64_t *total, uint64_t *bytes, hipStream_t stream);
 
+// Plain copy of known size (yardstick for hardware byte counters).
+remoe_status launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t stream);
+
 }  // namespace remoe

@@ -83,35 +83,28 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // the fragment reads of the other (no wait for the copy before those reads)
     __shared__ u32x4_t lds_a0[BM * 8], lds_a1[BM * 8];
     __shared__ u32x4_t lds_b0[BN * 8], lds_b1[BN * 8];
-    __shared__ float lds_scale[BM];            // mode 1: gate weight of each tile row
+    __shared__ float lds_scale[2][BM];         // mode 1: gate weight of each tile row (this tile / next tile)
+    static_assert(BM == BN, "the epilogue stages its bands in the second A stage and the second B stage alike");
 
+    // Persistent workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs, so workgroup b is
+    // slot b / 8 of XCD b % 8.  XCD x owns the contiguous range [x * chunk, (x + 1) * chunk) of
+    // logical tiles (n-tile fastest) and its slots walk that range together: slot c takes tiles
+    // c, c + n_slots, ...  At any time the workgroups of one XCD therefore work on neighbouring
+    // tiles, which share A rows and expert weights through that XCD's L2.
     const int ntn = (p.n_out + BN_OUT - 1) / BN_OUT;
     const int n_mt = p.tile_expert ? *p.n_tiles : (p.dense_rows + BM - 1) / BM;
     const int nblk = n_mt * ntn;
     const int chunk = (nblk + 7) >> 3;
-    const int q = blockIdx.x >> 3;
-    if (q >= chunk) return;
-    const int logical = (blockIdx.x & 7) * chunk + q;
-    if (logical >= nblk) return;
-    const int mt = logical / ntn, nt = logical - mt * ntn;
-
-    int expert = 0, row0 = mt * BM, rows = p.dense_rows - row0;
-    if (p.tile_expert) {
-        expert = p.tile_expert[mt];
-        row0 = p.tile_row0[mt];
-        rows = p.tile_rows[mt];
-    }
-    if (rows > BM) rows = BM;
+    const int n_slots = gridDim.x >> 3;
+    const int tile0 = (blockIdx.x & 7) * chunk;                          // first logical tile of this XCD
+    const int q_end = (nblk - tile0 < chunk) ? nblk - tile0 : chunk;     // its tile count (may be <= 0)
+    int q = blockIdx.x >> 3;
+    if (q >= q_end) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lh = lane >> 5;
-
-    if (MODE == 1) {
-        for (int r = tid; r < BM; r += THREADS)
-            lds_scale[r] = (p.row_scale && r < rows) ? p.row_scale[row0 + r] : 1.0f;
-    }
 
     // Direct-to-LDS copies: one instruction moves 64 lanes x 16 bytes into 1 KB of contiguous LDS
     // (lane l lands at base + 16 l), i.e. into 8 row slots x 8 chunk positions.  Each lane therefore
@@ -121,38 +114,64 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // spans less than 4 GiB), contiguous rows are relative to the tile's first row, and B offsets
     // stay inside one expert matrix.
     constexpr int NWAVES = WM * WN;
-    uint32_t a_off[A_CH], b_off[B_CH];
-    const char *a_base = reinterpret_cast<const char *>(p.row_gather ? p.a : p.a + (int64_t)row0 * p.lda);
-    const char *b_base0 = reinterpret_cast<const char *>(p.b0 + (int64_t)expert * p.n_out * p.k_dim);
-    const char *b_base1 = (MODE == 0) ? reinterpret_cast<const char *>(p.b1 + (int64_t)expert * p.n_out * p.k_dim)
-                                      : b_base0;
     const int land_rs = lane >> 3, land_cp = lane & 7;   // landing row slot (within the group), chunk position
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-        const int rs = (wave + NWAVES * i) * 8 + land_rs;
-        const int r = rs ^ ((rs >> 3) & 1);
-        const int c = land_cp ^ (r & 7);
-        const int rr = r < rows ? r : rows - 1;
-        const int64_t arow = p.row_gather ? p.row_gather[row0 + rr] : rr;
-        a_off[i] = (uint32_t)((arow * p.lda + c * 8) * 2);
-    }
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-        const int rs = (wave + NWAVES * i) * 8 + land_rs;
-        const int r = rs ^ ((rs >> 3) & 1);
-        const int c = land_cp ^ (r & 7);
-        int brow = (MODE == 0) ? nt * (BN / 2) + (r & (BN / 2 - 1)) : nt * BN + r;
-        if (brow >= p.n_out) brow = p.n_out - 1;   // ragged last n-tile: loads stay in bounds, stores are masked
-        b_off[i] = (uint32_t)(((int64_t)brow * p.k_dim + c * 8) * 2);
-    }
+    const int nk = p.k_dim / GM_BK;   // >= 1
 
-    floatx16_t acc[TM][TN];
-#pragma unroll
-    for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+    // ---- state of the tile being computed
+    int expert, row0, rows, nt;
+    uint32_t a_off[A_CH], b_off[B_CH];
+    int a_row[A_CH];
+    const char *a_base, *b_base0, *b_base1;
+    int par = 0;
+
+#define GM_TILE_INFO(qq, E, R0, RS, NT)                                                             \
+    {                                                                                               \
+        const int logical_ = tile0 + (qq);                                                          \
+        const int mt_ = logical_ / ntn;                                                             \
+        NT = logical_ - mt_ * ntn;                                                                  \
+        if (p.tile_expert) {                                                                        \
+            E = p.tile_expert[mt_];                                                                 \
+            R0 = p.tile_row0[mt_];                                                                  \
+            RS = p.tile_rows[mt_];                                                                  \
+        } else {                                                                                    \
+            E = 0;                                                                                  \
+            R0 = mt_ * BM;                                                                          \
+            RS = p.dense_rows - R0;                                                                 \
+        }                                                                                           \
+        if (RS > BM) RS = BM;                                                                       \
+    }
+    // rows of A this thread copies (through slot -> token when gathered); issued early, used by GM_TILE_OFFSETS
+#define GM_TILE_ROWS()                                                                              \
+    _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                               \
+        const int rs_ = (wave + NWAVES * i) * 8 + land_rs;                                          \
+        const int r_ = rs_ ^ ((rs_ >> 3) & 1);                                                      \
+        const int rr_ = r_ < rows ? r_ : rows - 1;                                                  \
+        a_row[i] = p.row_gather ? p.row_gather[row0 + rr_] : rr_;                 \
+    }
+#define GM_TILE_OFFSETS()                                                                           \
+    a_base = reinterpret_cast<const char *>(p.row_gather ? p.a : p.a + (int64_t)row0 * p.lda);      \
+    b_base0 = reinterpret_cast<const char *>(p.b0 + (int64_t)expert * p.n_out * p.k_dim);           \
+    b_base1 = (MODE == 0) ? reinterpret_cast<const char *>(p.b1 + (int64_t)expert * p.n_out * p.k_dim) \
+                          : b_base0;                                                                \
+    _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                               \
+        const int rs_ = (wave + NWAVES * i) * 8 + land_rs;                                          \
+        const int r_ = rs_ ^ ((rs_ >> 3) & 1);                                                      \
+        const int c_ = land_cp ^ (r_ & 7);                                                          \
+        a_off[i] = (uint32_t)(((int64_t)a_row[i] * p.lda + c_ * 8) * 2);                                     \
+    }                                                                                               \
+    _Pragma("unroll") for (int i = 0; i < B_CH; ++i) {                                               \
+        const int rs_ = (wave + NWAVES * i) * 8 + land_rs;                                          \
+        const int r_ = rs_ ^ ((rs_ >> 3) & 1);                                                      \
+        const int c_ = land_cp ^ (r_ & 7);                                                          \
+        int brow_ = (MODE == 0) ? nt * (BN / 2) + (r_ & (BN / 2 - 1)) : nt * BN + r_;               \
+        if (brow_ >= p.n_out) brow_ = p.n_out - 1;   /* ragged last n-tile: loads stay in bounds, stores are masked */ \
+        b_off[i] = (uint32_t)(((int64_t)brow_ * p.k_dim + c_ * 8) * 2);                             \
+    }
+#define GM_FILL_SCALE(buf)                                                                          \
+    if (MODE == 1) {                                                                                \
+        for (int r_ = tid; r_ < BM; r_ += THREADS)                                                  \
+            lds_scale[buf][r_] = (p.row_scale && r_ < rows) ? p.row_scale[row0 + r_] : 1.0f;        \
+    }
 
     // mode 0: row-slot groups below BN/2 rows hold gate rows, the others up rows (a group never straddles)
 #define GM_COPY_SLICE(la, lb, k0)                                                                   \
@@ -201,86 +220,133 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         GM_MFMA(fa1, fb1)                                                                           \
     }
 
-    const int nk = p.k_dim / GM_BK;   // >= 1
-    int kt = 0;
-    if (nk & 1) {   // odd slice count: the first slice runs alone, without a copy behind it
-        GM_COPY_SLICE(lds_a0, lds_b0, 0)
-        __syncthreads();
-        GM_COMPUTE(lds_a0, lds_b0)
-        __syncthreads();
-        kt = 1;
-    }
-    if (kt < nk) {
-        GM_COPY_SLICE(lds_a0, lds_b0, kt * GM_BK)
-        __syncthreads();   // waits for this wavefront's copies (vmcnt) and then for everyone's
-        // pairs of slices: first in stage 0, second in stage 1; a stage is refilled right after the
-        // barrier that ends its last reads
-        for (; kt < nk; kt += 2) {
-            GM_COPY_SLICE(lds_a1, lds_b1, (kt + 1) * GM_BK)
-            GM_COMPUTE(lds_a0, lds_b0)
-            __syncthreads();
-            if (kt + 2 < nk) { GM_COPY_SLICE(lds_a0, lds_b0, (kt + 2) * GM_BK) }
-            GM_COMPUTE(lds_a1, lds_b1)
-            __syncthreads();
-        }
-    }
-
-    // Epilogue.  A lane holds column li of 16 rows per accumulator, which would make 2-byte stores.
-    // Instead each 32-row band of the workgroup tile (both wm halves, all BN_OUT columns) is staged
-    // in LDS as bf16 and written out as 16-byte chunks, so every output row leaves as one
-    // contiguous run of full cache lines.  Neighbouring lanes first swap one value (lanes 2j and
-    // 2j+1 own adjacent columns) so that each lane packs two adjacent columns of one row into a
-    // dword.  A 64-byte segment s of band row r is stored at segment s ^ f(r), f = (r&1)|((r>>2)&1)<<1:
-    // the four rows one write instruction touches (r, r+1, r+4, r+5) then fall on different banks.
-    // Bands alternate between the two (now idle) A stages, so one barrier per band suffices.
+    // Epilogue of one 32-row band per wavefront row (mi).  A lane holds column li of 16 rows per
+    // accumulator, which would make 2-byte stores.  Instead each band of the workgroup tile (both wm
+    // halves, all BN_OUT columns) is staged in LDS as bf16 and written out as 16-byte chunks, so
+    // every output row leaves as one contiguous run of full cache lines.  Neighbouring lanes first
+    // swap one value (lanes 2j and 2j+1 own adjacent columns) so that each lane packs two adjacent
+    // columns of one row into a dword.  A 64-byte segment s of band row r is stored at segment
+    // s ^ f(r), f = (r&1)|((r>>2)&1)<<1: the four rows one write instruction touches (r, r+1, r+4,
+    // r+5) then fall on different banks.  Bands alternate between the second A stage and the second
+    // B stage (idle after the last slice), so one barrier per band suffices and the first stage is
+    // free to receive the next tile's first slice meanwhile.
     constexpr int ROWB = BN_OUT * 2;        // bytes per staged row
     constexpr int CPR = BN_OUT / 8;         // 16-byte chunks per staged row
-    const bool odd = li & 1;
+#define GM_EPILOGUE_BAND(mi, e_row0, e_rows, e_nt, e_par)                                           \
+    {                                                                                               \
+        char *reg = reinterpret_cast<char *>(((mi) & 1) ? lds_b1 : lds_a1);                         \
+        _Pragma("unroll") for (int rp = 0; rp < 8; ++rp) {                                           \
+            const int r0 = 2 * rp;                                                                  \
+            const int rr0 = (r0 >> 2) * 8 + lh * 4 + (r0 & 3);   /* band row of acc[..][r0]; r0 + 1 is the next row */ \
+            const int row = odd ? rr0 + 1 : rr0;                                                    \
+            const int f = (row & 1) | (((row >> 2) & 1) << 1);                                      \
+            float sc0 = 1.0f, sc1 = 1.0f;                                                           \
+            if (MODE == 1) {                                                                        \
+                sc0 = lds_scale[e_par][(wm * TM + (mi)) * 32 + rr0];                                \
+                sc1 = lds_scale[e_par][(wm * TM + (mi)) * 32 + rr0 + 1];                            \
+            }                                                                                       \
+            _Pragma("unroll") for (int ni = 0; ni < ((MODE == 0) ? 1 : TN); ++ni) {                  \
+                float va, vb;                                                                       \
+                if (MODE == 0) {                                                                    \
+                    const float g0 = acc[mi][0][r0], u0 = acc[mi][1][r0];                           \
+                    const float g1 = acc[mi][0][r0 + 1], u1 = acc[mi][1][r0 + 1];                   \
+                    va = g0 / (1.0f + __expf(-g0)) * u0;                                            \
+                    vb = g1 / (1.0f + __expf(-g1)) * u1;                                            \
+                } else {                                                                            \
+                    va = acc[mi][ni][r0] * sc0;                                                     \
+                    vb = acc[mi][ni][r0 + 1] * sc1;                                                 \
+                }                                                                                   \
+                const float recv = swap_with_neighbour(odd ? va : vb);                              \
+                const uint32_t packed = odd ? pack_bf16x2(recv, vb) : pack_bf16x2(va, recv);        \
+                const int seg = (MODE == 0) ? wn : wn * TN + ni;                                    \
+                *reinterpret_cast<uint32_t *>(reg + (wm * 32 + row) * ROWB + ((seg ^ f) << 6) + ((li & ~1) << 1)) = packed; \
+            }                                                                                       \
+        }                                                                                           \
+        __syncthreads();                                                                            \
+        _Pragma("unroll") for (int j = 0; j < 64 * CPR / THREADS; ++j) {                             \
+            const int q2 = tid + THREADS * j;                                                       \
+            const int R = q2 / CPR, ch = q2 % CPR;     /* band row over both wm halves, chunk in the row */ \
+            const int row = R & 31;                                                                 \
+            const int f = (row & 1) | (((row >> 2) & 1) << 1);                                      \
+            const u32x4_t v = *reinterpret_cast<const u32x4_t *>(reg + R * ROWB + ((((ch >> 2) ^ f) << 6) + ((ch & 3) << 4))); \
+            const int m = ((R >> 5) * TM + (mi)) * 32 + row;                                        \
+            const int col = (e_nt) * BN_OUT + ch * 8;                                               \
+            if (m < (e_rows) && col < p.n_out)                                                      \
+                *reinterpret_cast<u32x4_t *>(p.c + (p.c_row_offset + (e_row0) + m) * p.ldc + col) = v; \
+        }                                                                                           \
+    }
+
+    GM_TILE_INFO(q, expert, row0, rows, nt)
+    GM_TILE_ROWS()
+    GM_TILE_OFFSETS()
+    GM_FILL_SCALE(0)
+    GM_COPY_SLICE(lds_a0, lds_b0, 0)
+
+    for (;;) {
+        // descriptor of this workgroup's next tile: scalar loads that complete under the main loop
+        const bool has_next = q + n_slots < q_end;
+        int nx_expert = 0, nx_row0 = 0, nx_rows = 1, nx_nt = 0;
+        if (has_next) GM_TILE_INFO(q + n_slots, nx_expert, nx_row0, nx_rows, nx_nt)
+
+        floatx16_t acc[TM][TN];
 #pragma unroll
-    for (int mi = 0; mi < TM; ++mi) {
-        char *reg = reinterpret_cast<char *>((mi & 1) ? lds_a1 : lds_a0);
+        for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
-        for (int rp = 0; rp < 8; ++rp) {
-            const int r0 = 2 * rp;
-            const int rr0 = (r0 >> 2) * 8 + lh * 4 + (r0 & 3);   // band row of acc[..][r0]; r0 + 1 is the next row
-            const int row = odd ? rr0 + 1 : rr0;
-            const int f = (row & 1) | (((row >> 2) & 1) << 1);
-            float sc0 = 1.0f, sc1 = 1.0f;
-            if (MODE == 1) {
-                sc0 = lds_scale[(wm * TM + mi) * 32 + rr0];
-                sc1 = lds_scale[(wm * TM + mi) * 32 + rr0 + 1];
-            }
+            for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-            for (int ni = 0; ni < ((MODE == 0) ? 1 : TN); ++ni) {
-                float va, vb;
-                if (MODE == 0) {
-                    const float g0 = acc[mi][0][r0], u0 = acc[mi][1][r0];
-                    const float g1 = acc[mi][0][r0 + 1], u1 = acc[mi][1][r0 + 1];
-                    va = g0 / (1.0f + __expf(-g0)) * u0;
-                    vb = g1 / (1.0f + __expf(-g1)) * u1;
-                } else {
-                    va = acc[mi][ni][r0] * sc0;
-                    vb = acc[mi][ni][r0 + 1] * sc1;
-                }
-                const float recv = swap_with_neighbour(odd ? va : vb);
-                const uint32_t packed = odd ? pack_bf16x2(recv, vb) : pack_bf16x2(va, recv);
-                const int seg = (MODE == 0) ? wn : wn * TN + ni;
-                *reinterpret_cast<uint32_t *>(reg + (wm * 32 + row) * ROWB + ((seg ^ f) << 6) + ((li & ~1) << 1)) = packed;
+                for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+        // Main loop.  Slice 0 is already on its way into stage 0.
+        int kt = 0;
+        if (nk & 1) {   // odd slice count: the first slice runs alone, without a copy behind it
+            __syncthreads();
+            GM_COMPUTE(lds_a0, lds_b0)
+            __syncthreads();
+            kt = 1;
+            if (kt < nk) { GM_COPY_SLICE(lds_a0, lds_b0, kt * GM_BK) }
+        }
+        if (kt < nk) {
+            __syncthreads();   // waits for this wavefront's copies (vmcnt) and then for everyone's
+            // pairs of slices: first in stage 0, second in stage 1; a stage is refilled right after
+            // the barrier that ends its last reads
+            for (; kt < nk; kt += 2) {
+                GM_COPY_SLICE(lds_a1, lds_b1, (kt + 1) * GM_BK)
+                GM_COMPUTE(lds_a0, lds_b0)
+                __syncthreads();
+                if (kt + 2 < nk) { GM_COPY_SLICE(lds_a0, lds_b0, (kt + 2) * GM_BK) }
+                GM_COMPUTE(lds_a1, lds_b1)
+                __syncthreads();
             }
         }
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < 64 * CPR / THREADS; ++j) {
-            const int q2 = tid + THREADS * j;
-            const int R = q2 / CPR, ch = q2 % CPR;     // band row over both wm halves, chunk in the row
-            const int row = R & 31;
-            const int f = (row & 1) | (((row >> 2) & 1) << 1);
-            const u32x4_t v = *reinterpret_cast<const u32x4_t *>(reg + R * ROWB + ((((ch >> 2) ^ f) << 6) + ((ch & 3) << 4)));
-            const int m = ((R >> 5) * TM + mi) * 32 + row;
-            const int col = nt * BN_OUT + ch * 8;
-            if (m < rows && col < p.n_out)
-                *reinterpret_cast<u32x4_t *>(p.c + (p.c_row_offset + row0 + m) * p.ldc + col) = v;
+
+        // Both stages are idle now.  The finished tile is written out band by band while the next
+        // tile's row indices, offsets and first slice are fetched in between.
+        // (Thread-index arithmetic of this phase is redone per tile from a value the optimiser
+        // cannot see through, so that none of it is hoisted and kept in registers across the main loop.)
+        int tid_again = threadIdx.x;
+        asm volatile("" : "+v"(tid_again));
+        const int tid = tid_again;
+        const int lane = tid & 63, wave = tid >> 6;
+        const int wm = wave / WN, wn = wave % WN;
+        const int li = lane & 31, lh = lane >> 5;
+        const int land_rs = lane >> 3, land_cp = lane & 7;
+        const bool odd = li & 1;
+        const int e_row0 = row0, e_rows = rows, e_nt = nt, e_par = par;
+        if (has_next) {
+            expert = nx_expert; row0 = nx_row0; rows = nx_rows; nt = nx_nt;
+            par ^= 1;
+            GM_TILE_ROWS()
         }
+        GM_EPILOGUE_BAND(0, e_row0, e_rows, e_nt, e_par)
+        if (has_next) {
+            GM_TILE_OFFSETS()
+            GM_FILL_SCALE(par)
+            GM_COPY_SLICE(lds_a0, lds_b0, 0)
+        }
+#pragma unroll
+        for (int mi = 1; mi < TM; ++mi) GM_EPILOGUE_BAND(mi, e_row0, e_rows, e_nt, e_par)
+        if (!has_next) break;
+        q += n_slots;
     }
 }
 
@@ -320,8 +386,16 @@ remoe_status launch_grouped_gemm_bf16(int mode, const GroupedGemmArgs &g, hipStr
     p.c = static_cast<bf16_t *>(g.c);
     p.ldc = g.ldc;
     p.c_row_offset = g.c_row_offset;
+    // persistent launch: one workgroup per compute unit (a multiple of 8, one share per XCD), fewer
+    // when the upper bound of tiles is smaller
+    int dev = 0, n_cu = 0;
+    REMOE_HIP_TRY(hipGetDevice(&dev));
+    REMOE_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
     const int64_t nblk = (int64_t)g.max_tiles * ceil_div(g.n_out, bn);
-    const dim3 grid((unsigned)(ceil_div(nblk, 8) * 8)), block(CFG_WM * CFG_WN * 64);
+    int64_t n_wg = ceil_div(nblk, 8) * 8;
+    const int64_t resident = n_cu >= 8 ? (int64_t)(n_cu / 8) * 8 : 8;
+    if (n_wg > resident) n_wg = resident;
+    const dim3 grid((unsigned)n_wg), block(CFG_WM * CFG_WN * 64);
     if (mode == 0)
         hipLaunchKernelGGL((grouped_gemm_bf16_kernel<0, CFG_WM, CFG_WN, CFG_TM, CFG_TN>), grid, block, 0, stream, p);
     else

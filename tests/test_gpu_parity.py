@@ -268,3 +268,13 @@ def test_workspace_too_small_is_reported():
     with pytest.raises(remoe.RemoeError, match="workspace"):
         remoe.moe_forward(desc, x, w["w_router"], w["w_gate"], w["w_up"], w["w_down"], None, None, None, None,
                           y, idx, gw, ws)
+
+
+def test_copy_probe_copies_exactly():
+    src = torch.arange(0, 3 * 1024 * 1024 + 16, dtype=torch.int32, device=DEV).view(torch.uint8)
+    dst = torch.zeros_like(src)
+    remoe.remoe_copy_probe(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    with pytest.raises(remoe.RemoeError):
+        remoe.remoe_copy_probe(dst[:32], src[:48])
