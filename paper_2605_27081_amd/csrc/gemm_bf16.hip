@@ -167,11 +167,12 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         if (brow_ >= p.n_out) brow_ = p.n_out - 1;   /* ragged last n-tile: loads stay in bounds, stores are masked */ \
         b_off[i] = (uint32_t)(((int64_t)brow_ * p.k_dim + c_ * 8) * 2);                             \
     }
+    // mode 1: the gate weight of tile row tid (threads below BM), fetched early and parked in LDS later
+    float scale_reg = 1.0f;
+#define GM_LOAD_SCALE()                                                                             \
+    if (MODE == 1) scale_reg = (p.row_scale && tid < rows) ? p.row_scale[row0 + tid] : 1.0f;
 #define GM_FILL_SCALE(buf)                                                                          \
-    if (MODE == 1) {                                                                                \
-        for (int r_ = tid; r_ < BM; r_ += THREADS)                                                  \
-            lds_scale[buf][r_] = (p.row_scale && r_ < rows) ? p.row_scale[row0 + r_] : 1.0f;        \
-    }
+    if (MODE == 1 && tid < BM) lds_scale[buf][tid] = scale_reg;
 
     // mode 0: row-slot groups below BN/2 rows hold gate rows, the others up rows (a group never straddles)
 #define GM_COPY_SLICE(la, lb, k0)                                                                   \
@@ -232,9 +233,14 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // free to receive the next tile's first slice meanwhile.
     constexpr int ROWB = BN_OUT * 2;        // bytes per staged row
     constexpr int CPR = BN_OUT / 8;         // 16-byte chunks per staged row
-#define GM_EPILOGUE_BAND(mi, e_row0, e_rows, e_nt, e_par)                                           \
+    static_assert(BM <= THREADS, "one thread per tile row fetches the row's gate weight");
+    // Workgroup barrier that orders LDS traffic only.  (__syncthreads would also wait for the
+    // direct-to-LDS copy of the next tile's first slice, which is in flight during the epilogue.)
+#define GM_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+    // accumulators of band mi -> staging array st (u32x4_t[], indexed in dwords)
+#define GM_EPI_STAGE(mi, st, e_par)                                                                 \
     {                                                                                               \
-        char *reg = reinterpret_cast<char *>(((mi) & 1) ? lds_b1 : lds_a1);                         \
+        uint32_t *reg = reinterpret_cast<uint32_t *>(st);                                           \
         _Pragma("unroll") for (int rp = 0; rp < 8; ++rp) {                                           \
             const int r0 = 2 * rp;                                                                  \
             const int rr0 = (r0 >> 2) * 8 + lh * 4 + (r0 & 3);   /* band row of acc[..][r0]; r0 + 1 is the next row */ \
@@ -259,25 +265,31 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
                 const float recv = swap_with_neighbour(odd ? va : vb);                              \
                 const uint32_t packed = odd ? pack_bf16x2(recv, vb) : pack_bf16x2(va, recv);        \
                 const int seg = (MODE == 0) ? wn : wn * TN + ni;                                    \
-                *reinterpret_cast<uint32_t *>(reg + (wm * 32 + row) * ROWB + ((seg ^ f) << 6) + ((li & ~1) << 1)) = packed; \
+                reg[((wm * 32 + row) * ROWB + ((seg ^ f) << 6) + ((li & ~1) << 1)) >> 2] = packed;  \
             }                                                                                       \
         }                                                                                           \
-        __syncthreads();                                                                            \
-        _Pragma("unroll") for (int j = 0; j < 64 * CPR / THREADS; ++j) {                             \
-            const int q2 = tid + THREADS * j;                                                       \
-            const int R = q2 / CPR, ch = q2 % CPR;     /* band row over both wm halves, chunk in the row */ \
-            const int row = R & 31;                                                                 \
-            const int f = (row & 1) | (((row >> 2) & 1) << 1);                                      \
-            const u32x4_t v = *reinterpret_cast<const u32x4_t *>(reg + R * ROWB + ((((ch >> 2) ^ f) << 6) + ((ch & 3) << 4))); \
-            const int m = ((R >> 5) * TM + (mi)) * 32 + row;                                        \
-            const int col = (e_nt) * BN_OUT + ch * 8;                                               \
-            if (m < (e_rows) && col < p.n_out)                                                      \
-                *reinterpret_cast<u32x4_t *>(p.c + (p.c_row_offset + (e_row0) + m) * p.ldc + col) = v; \
-        }                                                                                           \
     }
+    // staging array st -> global memory, 16 bytes per lane
+#define GM_EPI_STORE(mi, st, e_row0, e_rows, e_nt)                                                  \
+    _Pragma("unroll") for (int j = 0; j < 64 * CPR / THREADS; ++j) {                                 \
+        const int q2 = tid + THREADS * j;                                                           \
+        const int R = q2 / CPR, ch = q2 % CPR;     /* band row over both wm halves, chunk in the row */ \
+        const int row = R & 31;                                                                     \
+        const int f = (row & 1) | (((row >> 2) & 1) << 1);                                          \
+        const u32x4_t v = st[(R * ROWB + ((((ch >> 2) ^ f) << 6) + ((ch & 3) << 4))) >> 4];         \
+        const int m = ((R >> 5) * TM + (mi)) * 32 + row;                                            \
+        const int col = (e_nt) * BN_OUT + ch * 8;                                                   \
+        if (m < (e_rows) && col < p.n_out)                                                          \
+            *reinterpret_cast<u32x4_t *>(p.c + (p.c_row_offset + (e_row0) + m) * p.ldc + col) = v;  \
+    }
+#define GM_EPI_BAND(mi, st, e_row0, e_rows, e_nt, e_par)                                            \
+    GM_EPI_STAGE(mi, st, e_par)                                                                     \
+    GM_LDS_BARRIER();                                                                               \
+    GM_EPI_STORE(mi, st, e_row0, e_rows, e_nt)
 
     GM_TILE_INFO(q, expert, row0, rows, nt)
     GM_TILE_ROWS()
+    GM_LOAD_SCALE()
     GM_TILE_OFFSETS()
     GM_FILL_SCALE(0)
     GM_COPY_SLICE(lds_a0, lds_b0, 0)
@@ -336,15 +348,20 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             expert = nx_expert; row0 = nx_row0; rows = nx_rows; nt = nx_nt;
             par ^= 1;
             GM_TILE_ROWS()
+            GM_LOAD_SCALE()
         }
-        GM_EPILOGUE_BAND(0, e_row0, e_rows, e_nt, e_par)
-        if (has_next) {
+        GM_EPI_STAGE(0, lds_a1, e_par)
+        if (has_next) {   // before any store of this epilogue is in flight: the loads above are all that is waited for
             GM_TILE_OFFSETS()
             GM_FILL_SCALE(par)
             GM_COPY_SLICE(lds_a0, lds_b0, 0)
         }
-#pragma unroll
-        for (int mi = 1; mi < TM; ++mi) GM_EPILOGUE_BAND(mi, e_row0, e_rows, e_nt, e_par)
+        GM_LDS_BARRIER();
+        GM_EPI_STORE(0, lds_a1, e_row0, e_rows, e_nt)
+        if (TM > 1) { GM_EPI_BAND(1, lds_b1, e_row0, e_rows, e_nt, e_par) }
+        if (TM > 2) { GM_EPI_BAND(2, lds_a1, e_row0, e_rows, e_nt, e_par) }
+        if (TM > 3) { GM_EPI_BAND(3, lds_b1, e_row0, e_rows, e_nt, e_par) }
+        static_assert(TM <= 4, "the epilogue is written out for up to four bands");
         if (!has_next) break;
         q += n_slots;
     }

@@ -1,83 +1,233 @@
-// Router kernel: fp32 logits on the fp32 matrix cores, then a wavefront-shuffle top-k and softmax.
+// Router kernel: fp32-accurate logits on the matrix cores, then a lane-per-token top-k and softmax.
 //
 // Computes the paper's routing step (Sec. 3.1): P_t = Softmax(h_t^T theta_gate), E_t = Top-K(P_t).
 // One workgroup (4 wavefronts) owns 128 tokens and all N_r <= 128 experts, so every token's full
-// logit row ends in one wavefront: 32 tokens x (NT*32) experts per wavefront as NT accumulators of
-// v_mfma_f32_32x32x2_f32.  The logits are parked in LDS and each token is then ranked by its
-// wavefront: every lane owns experts {lane, lane+64}, and K+1 rounds of a 6-step butterfly argmax
-// over (logit, -id) produce the ids in descending-logit order with ties to the lower id.
+// logit row ends in one workgroup: 32 tokens x (NT*32) experts per wavefront as NT accumulators.
+//
+// Logits.  The gate weights are fp32 and the logits must carry fp32 accuracy (near ties decide
+// which experts run).  For fp32 hidden states the products run on v_mfma_f32_32x32x2_f32.  For bf16
+// hidden states every x is already exact in bf16, and each fp32 weight is split on the fly into three
+// bf16 pieces w = hi + mid + lo (each the round-to-nearest of what the previous ones left, 24+
+// significand bits in all), so x*hi, x*mid and x*lo are exact fp32 products and three
+// v_mfma_f32_32x32x16_bf16 with fp32 accumulation replace sixteen fp32 MFMA steps.
+//
+// Top-k.  The logits are parked in LDS, one padded row per token.  Two neighbouring lanes share a
+// token, each scanning half of its experts in ascending id and keeping the 9 largest (K <= 8, plus
+// the runner-up for the margin) by insertion into a sorted register list; strict comparisons keep
+// the lower id first among equal logits.  The halves are merged through a lane swap, the softmax
+// denominator is summed the same way, and the pair writes ids and weights of its token.
 #include "common.h"
-#include "topk.h"
 
 namespace remoe {
 
 namespace {
 
-constexpr int RT_BM = 128;  // tokens per workgroup
-constexpr int RT_BK = 32;   // reduction slice per LDS stage (fp32 elements)
+constexpr int RT_BM = 128;   // tokens per workgroup
+constexpr int RT_BK = 32;    // reduction slice per LDS stage (elements)
+constexpr int RT_LIST = 9;   // sorted candidates kept per lane: MAX top_k + 1
 
-// LDS tiles hold rows of 32 floats = 8 chunks of 16 bytes; chunk c of row r lives in row slot
-// r ^ ((r >> 3) & 1) at chunk position c ^ (r & 7), so that the rows a wavefront reads at once
-// spread over all banks whether 8 or 16 lanes are served per cycle.
-__device__ __forceinline__ int swz(int r, int c)
+// ---- fp32 path: LDS tiles hold rows of 32 floats = 8 chunks of 16 bytes; chunk c of row r lives in
+// row slot r ^ ((r >> 3) & 1) at chunk position c ^ (r & 7), so that the rows a wavefront reads at
+// once spread over all banks whether 8 or 16 lanes are served per cycle.
+__device__ __forceinline__ int swz_f32(int r, int c)
 {
     return (r ^ ((r >> 3) & 1)) * RT_BK + ((c ^ (r & 7)) << 2);
 }
 
-template <typename XT> struct XLoad;
+// ---- bf16 path: rows of 32 bf16 = 4 chunks of 16 bytes; chunk c of row r sits at chunk position
+// c ^ ((r >> 2) & 3), which makes 16 consecutive rows of one logical chunk cover all 16 slots of a
+// 256-byte period.  Returns the offset in 16-byte units.
+__device__ __forceinline__ int swz_bf16(int r, int c) { return r * 4 + (c ^ ((r >> 2) & 3)); }
 
-template <> struct XLoad<float> {
-    // 128 rows x 8 chunks(4 floats): 4 chunks per thread
-    floatx4_t v[4];
-    __device__ __forceinline__ void load(const float *x, int64_t t0, int64_t T, int H, int k0, int tid)
-    {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int q = tid + 256 * i, r = q >> 3, c = q & 7;
-            int64_t t = t0 + r;
-            if (t >= T) t = T - 1;
-            v[i] = *reinterpret_cast<const floatx4_t *>(x + t * H + k0 + c * 4);
-        }
-    }
-    __device__ __forceinline__ void store(float *as, int tid) const
-    {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int q = tid + 256 * i, r = q >> 3, c = q & 7;
-            *reinterpret_cast<floatx4_t *>(as + swz(r, c)) = v[i];
-        }
-    }
+// round-to-nearest-even bf16 pieces of an fp32 value: w = hi + mid + lo up to 2^-24 relative
+__device__ __forceinline__ void split3(float w, uint32_t &hi, uint32_t &mid, uint32_t &lo)
+{
+    hi = f32_to_bf16(w);
+    const float r1 = w - bf16_to_f32((bf16_t)hi);
+    mid = f32_to_bf16(r1);
+    const float r2 = r1 - bf16_to_f32((bf16_t)mid);
+    lo = f32_to_bf16(r2);
+}
+
+// Logit rows in LDS: experts [0, NE/2) then 4 floats of padding, experts [NE/2, NE), 4 more.  With a
+// row stride of NE + 8 floats the 16-byte reads of 8 tokens x 2 halves fall into 16 different slots.
+template <int NE> struct LogitLayout {
+    static constexpr int HALF = NE / 2;
+    static constexpr int STRIDE = NE + 8;
+    __device__ static __forceinline__ int at(int row, int col) { return row * STRIDE + col + (col >= HALF ? 4 : 0); }
 };
 
-template <> struct XLoad<bf16_t> {
-    // 128 rows x 4 chunks(8 bf16): 2 chunks per thread, each widened to two fp32 chunks
-    u32x4_t v[2];
-    __device__ __forceinline__ void load(const bf16_t *x, int64_t t0, int64_t T, int H, int k0, int tid)
-    {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            int q = tid + 256 * i, r = q >> 2, c = q & 3;
-            int64_t t = t0 + r;
-            if (t >= T) t = T - 1;
-            v[i] = *reinterpret_cast<const u32x4_t *>(x + t * H + k0 + c * 8);
-        }
+// ---- logits of fp32 hidden states: 2-stage LDS pipeline, v_mfma_f32_32x32x2_f32
+template <int NT>
+__device__ __forceinline__ void logits_f32(const float *__restrict__ x, int64_t t0, int64_t T, int H,
+                                           const float *__restrict__ wr, int N, float *smem,
+                                           floatx16_t (&acc)[NT], int tid)
+{
+    constexpr int NE = NT * 32;
+    constexpr int A_FLOATS = RT_BM * RT_BK;
+    constexpr int B_FLOATS = NE * RT_BK;
+    float *As = smem;
+    float *Bs = smem + 2 * A_FLOATS;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+
+    floatx4_t av[4], bv[NT];
+#define RT_LOAD_F32(k0)                                                                        \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
+        const int q_ = tid + 256 * i, r_ = q_ >> 3, c_ = q_ & 7;                               \
+        int64_t t_ = t0 + r_;                                                                  \
+        if (t_ >= T) t_ = T - 1;                                                               \
+        av[i] = *reinterpret_cast<const floatx4_t *>(x + t_ * H + (k0) + c_ * 4);              \
+    }                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < NT; ++i) {                                            \
+        const int q_ = tid + 256 * i, r_ = q_ >> 3, c_ = q_ & 7;                               \
+        const floatx4_t zero_ = {0.f, 0.f, 0.f, 0.f};                                           \
+        bv[i] = (r_ < N) ? *reinterpret_cast<const floatx4_t *>(wr + (int64_t)r_ * H + (k0) + c_ * 4) \
+                         : zero_;                                                              \
     }
-    __device__ __forceinline__ void store(float *as, int tid) const
-    {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            int q = tid + 256 * i, r = q >> 2, c = q & 3;
-            const u32x4_t w = v[i];
-            floatx4_t lo, hi;
-            lo.x = __uint_as_float(w.x << 16); lo.y = __uint_as_float(w.x & 0xFFFF0000u);
-            lo.z = __uint_as_float(w.y << 16); lo.w = __uint_as_float(w.y & 0xFFFF0000u);
-            hi.x = __uint_as_float(w.z << 16); hi.y = __uint_as_float(w.z & 0xFFFF0000u);
-            hi.z = __uint_as_float(w.w << 16); hi.w = __uint_as_float(w.w & 0xFFFF0000u);
-            *reinterpret_cast<floatx4_t *>(as + swz(r, 2 * c)) = lo;
-            *reinterpret_cast<floatx4_t *>(as + swz(r, 2 * c + 1)) = hi;
-        }
+#define RT_STORE_F32(as, bs)                                                                   \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
+        const int q_ = tid + 256 * i, r_ = q_ >> 3, c_ = q_ & 7;                               \
+        *reinterpret_cast<floatx4_t *>((as) + swz_f32(r_, c_)) = av[i];                         \
+    }                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < NT; ++i) {                                            \
+        const int q_ = tid + 256 * i, r_ = q_ >> 3, c_ = q_ & 7;                               \
+        *reinterpret_cast<floatx4_t *>((bs) + swz_f32(r_, c_)) = bv[i];                         \
     }
+
+    const int nk = H / RT_BK;
+    RT_LOAD_F32(0)
+    RT_STORE_F32(As, Bs)
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) { RT_LOAD_F32((kt + 1) * RT_BK) }
+        const float *as = As + cur * A_FLOATS;
+        const float *bs = Bs + cur * B_FLOATS;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            // this lane's four k values of the group: 8q + 4*lh + {0..3}
+            const floatx4_t a4 = *reinterpret_cast<const floatx4_t *>(as + swz_f32(wave * 32 + li, 2 * q + lh));
+            floatx4_t b4[NT];
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
+                b4[n] = *reinterpret_cast<const floatx4_t *>(bs + swz_f32(n * 32 + li, 2 * q + lh));
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+#pragma unroll
+                for (int n = 0; n < NT; ++n)
+                    acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[s], b4[n][s], acc[n], 0, 0, 0);
+            }
+        }
+        if (kt + 1 < nk) { RT_STORE_F32(As + (cur ^ 1) * A_FLOATS, Bs + (cur ^ 1) * B_FLOATS) }
+        __syncthreads();
+    }
+#undef RT_LOAD_F32
+#undef RT_STORE_F32
+}
+
+// ---- logits of bf16 hidden states: x as stored, weights as three bf16 pieces, v_mfma_f32_32x32x16_bf16
+template <int NT>
+__device__ __forceinline__ void logits_bf16(const bf16_t *__restrict__ x, int64_t t0, int64_t T, int H,
+                                            const float *__restrict__ wr, int N, float *smem,
+                                            floatx16_t (&acc)[NT], int tid)
+{
+    constexpr int NE = NT * 32;
+    constexpr int A_U4 = RT_BM * 4;          // 16-byte units of one x stage
+    constexpr int P_U4 = NE * 4;             // ... of one weight piece
+    constexpr int STAGE_U4 = A_U4 + 3 * P_U4;
+    u32x4_t *base = reinterpret_cast<u32x4_t *>(smem);
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+
+    u32x4_t xv[2];
+    floatx4_t wv[NT];
+#define RT_LOAD_BF16(k0)                                                                       \
+    _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                             \
+        const int q_ = tid + 256 * i, r_ = q_ >> 2, c_ = q_ & 3;                               \
+        int64_t t_ = t0 + r_;                                                                  \
+        if (t_ >= T) t_ = T - 1;                                                               \
+        xv[i] = *reinterpret_cast<const u32x4_t *>(x + t_ * H + (k0) + c_ * 8);                \
+    }                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < NT; ++i) {                                            \
+        const int q_ = tid + 256 * i, r_ = q_ >> 3, c_ = q_ & 7;                               \
+        const floatx4_t zero_ = {0.f, 0.f, 0.f, 0.f};                                           \
+        wv[i] = (r_ < N) ? *reinterpret_cast<const floatx4_t *>(wr + (int64_t)r_ * H + (k0) + c_ * 4) \
+                         : zero_;                                                              \
+    }
+    // a thread holds 4 consecutive k of one weight row: half a 16-byte chunk of each piece
+#define RT_STORE_BF16(st)                                                                      \
+    _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                             \
+        const int q_ = tid + 256 * i, r_ = q_ >> 2, c_ = q_ & 3;                               \
+        (st)[swz_bf16(r_, c_)] = xv[i];                                                        \
+    }                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < NT; ++i) {                                            \
+        const int q_ = tid + 256 * i, r_ = q_ >> 3, c_ = q_ & 7;                               \
+        uint32_t h_[4], m_[4], l_[4];                                                          \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) split3(wv[i][e], h_[e], m_[e], l_[e]);     \
+        uint2 *dst_ = reinterpret_cast<uint2 *>((st) + A_U4 + swz_bf16(r_, c_ >> 1)) + (c_ & 1); \
+        dst_[0] = make_uint2(h_[0] | (h_[1] << 16), h_[2] | (h_[3] << 16));                     \
+        dst_[2 * P_U4] = make_uint2(m_[0] | (m_[1] << 16), m_[2] | (m_[3] << 16));              \
+        dst_[4 * P_U4] = make_uint2(l_[0] | (l_[1] << 16), l_[2] | (l_[3] << 16));              \
+    }
+
+    const int nk = H / RT_BK;
+    RT_LOAD_BF16(0)
+    RT_STORE_BF16(base)
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) { RT_LOAD_BF16((kt + 1) * RT_BK) }
+        const u32x4_t *st = base + cur * STAGE_U4;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            // this lane's eight k values of the step: 16 ks + 8 lh + {0..7} = chunk 2 ks + lh
+            const bf16x8_t a8 = *reinterpret_cast<const bf16x8_t *>(&st[swz_bf16(wave * 32 + li, 2 * ks + lh)]);
+            bf16x8_t b8[NT][3];
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
+#pragma unroll
+                for (int pc = 0; pc < 3; ++pc)
+                    b8[n][pc] = *reinterpret_cast<const bf16x8_t *>(
+                        &st[A_U4 + pc * P_U4 + swz_bf16(n * 32 + li, 2 * ks + lh)]);
+#pragma unroll
+            for (int pc = 0; pc < 3; ++pc)
+#pragma unroll
+                for (int n = 0; n < NT; ++n)
+                    acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a8, b8[n][pc], acc[n], 0, 0, 0);
+        }
+        if (kt + 1 < nk) { RT_STORE_BF16(base + (cur ^ 1) * STAGE_U4) }
+        __syncthreads();
+    }
+#undef RT_LOAD_BF16
+#undef RT_STORE_BF16
+}
+
+template <int NT, typename XT> struct SmemFloats {
+    static constexpr int NE = NT * 32;
+    static constexpr int TILES = sizeof(XT) == 4 ? 2 * (RT_BM * RT_BK + NE * RT_BK)            // fp32 tiles
+                                                 : 2 * (RT_BM * 4 + 3 * NE * 4) * 4;           // bf16 tiles
+    static constexpr int LOGITS = RT_BM * LogitLayout<NE>::STRIDE;
+    static constexpr int VALUE = TILES > LOGITS ? TILES : LOGITS;
 };
+
+// (v, id) goes into the descending list if it beats an entry; what falls off the end is dropped
+#define RT_INSERT(v_in, id_in, BEATS)                                                          \
+    {                                                                                          \
+        float v_ = (v_in);                                                                     \
+        int id_ = (id_in);                                                                     \
+        _Pragma("unroll") for (int s = 0; s < RT_LIST; ++s) {                                   \
+            const bool gt_ = BEATS(v_, id_, val[s], idx[s]);                                   \
+            const float tv_ = gt_ ? val[s] : v_;                                               \
+            const int ti_ = gt_ ? idx[s] : id_;                                                \
+            val[s] = gt_ ? v_ : val[s];                                                        \
+            idx[s] = gt_ ? id_ : idx[s];                                                       \
+            v_ = tv_;                                                                          \
+            id_ = ti_;                                                                         \
+        }                                                                                      \
+    }
+#define RT_BEATS_SCAN(v, i, lv, li_) ((v) > (lv))                                  /* ids arrive ascending */
+#define RT_BEATS_ANY(v, i, lv, li_) ((v) > (lv) || ((v) == (lv) && (i) < (li_)))   /* any order */
 
 template <int NT, typename XT>
 __global__ __launch_bounds__(256) void route_kernel(const XT *__restrict__ x, int64_t T, int H,
@@ -88,20 +238,14 @@ __global__ __launch_bounds__(256) void route_kernel(const XT *__restrict__ x, in
                                                     float *__restrict__ out_probs)
 {
     constexpr int NE = NT * 32;
-    constexpr int A_FLOATS = RT_BM * RT_BK;
-    constexpr int B_FLOATS = NE * RT_BK;
-    constexpr int TILE_FLOATS = 2 * A_FLOATS + 2 * B_FLOATS;
-    constexpr int LOGIT_FLOATS = RT_BM * NE;
-    constexpr int SMEM_FLOATS = TILE_FLOATS > LOGIT_FLOATS ? TILE_FLOATS : LOGIT_FLOATS;
-    __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS];
-    float *As = smem;
-    float *Bs = smem + 2 * A_FLOATS;
+    typedef LogitLayout<NE> LL;
+    __shared__ __attribute__((aligned(16))) float smem[SmemFloats<NT, XT>::VALUE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int li = lane & 31;   // row / column inside a 32x32 MFMA tile
-    const int lh = lane >> 5;   // which k of the pair this lane feeds
+    const int lh = lane >> 5;
     const int64_t t0 = (int64_t)blockIdx.x * RT_BM;
 
     floatx16_t acc[NT];
@@ -110,87 +254,91 @@ __global__ __launch_bounds__(256) void route_kernel(const XT *__restrict__ x, in
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
 
-    XLoad<XT> xa;
-    floatx4_t bv[NT];
-#define RT_LOAD_B(k0)                                                                         \
-    _Pragma("unroll") for (int i = 0; i < NT; ++i) {                                           \
-        const int q_ = tid + 256 * i, r_ = q_ >> 3, c_ = q_ & 7;                              \
-        const floatx4_t zero_ = {0.f, 0.f, 0.f, 0.f};                                          \
-        bv[i] = (r_ < N) ? *reinterpret_cast<const floatx4_t *>(wr + (int64_t)r_ * H + (k0) + c_ * 4) \
-                         : zero_;                                                             \
-    }
-#define RT_STORE_B(bs)                                                                        \
-    _Pragma("unroll") for (int i = 0; i < NT; ++i) {                                           \
-        const int q_ = tid + 256 * i, r_ = q_ >> 3, c_ = q_ & 7;                              \
-        *reinterpret_cast<floatx4_t *>((bs) + swz(r_, c_)) = bv[i];                            \
-    }
+    if (sizeof(XT) == 4)
+        logits_f32<NT>(reinterpret_cast<const float *>(x), t0, T, H, wr, N, smem, acc, tid);
+    else
+        logits_bf16<NT>(reinterpret_cast<const bf16_t *>(x), t0, T, H, wr, N, smem, acc, tid);
 
-    const int nk = H / RT_BK;
-    xa.load(x, t0, T, H, 0, tid);
-    RT_LOAD_B(0)
-    xa.store(As, tid);
-    RT_STORE_B(Bs)
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            xa.load(x, t0, T, H, (kt + 1) * RT_BK, tid);
-            RT_LOAD_B((kt + 1) * RT_BK)
-        }
-        const float *as = As + cur * A_FLOATS;
-        const float *bs = Bs + cur * B_FLOATS;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            // this lane's four k values of the group: 8q + 4*lh + {0..3}
-            const floatx4_t a4 = *reinterpret_cast<const floatx4_t *>(as + swz(wave * 32 + li, 2 * q + lh));
-            floatx4_t b4[NT];
-#pragma unroll
-            for (int n = 0; n < NT; ++n)
-                b4[n] = *reinterpret_cast<const floatx4_t *>(bs + swz(n * 32 + li, 2 * q + lh));
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-#pragma unroll
-                for (int n = 0; n < NT; ++n)
-                    acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[s], b4[n][s], acc[n], 0, 0, 0);
-            }
-        }
-        if (kt + 1 < nk) {
-            xa.store(As + (cur ^ 1) * A_FLOATS, tid);
-            RT_STORE_B(Bs + (cur ^ 1) * B_FLOATS)
-        }
-        __syncthreads();
-    }
-
-    // park the logits: row = token inside the workgroup, column = expert
+    // park the logits (the tile stages are idle after the last barrier of the loop)
     float *Ls = smem;
 #pragma unroll
     for (int n = 0; n < NT; ++n)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int row = wave * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-            Ls[row * NE + n * 32 + li] = acc[n][r];
+            Ls[LL::at(row, n * 32 + li)] = acc[n][r];
         }
     __syncthreads();
 
+    // ---- top-k: lanes 2j and 2j+1 take token j of the workgroup, one half of the experts each
     const float NEG_INF = -__builtin_inff();
-#pragma unroll 1
-    for (int tl = 0; tl < 32; ++tl) {
-        const int64_t t = t0 + wave * 32 + tl;
-        if (t >= T) break;
-        const float *L = Ls + (wave * 32 + tl) * NE;
-        const float v0 = (lane < N) ? L[lane] : NEG_INF;
-        float v1 = NEG_INF;
-        if (NE > 64) v1 = (lane + 64 < N) ? L[lane + 64] : NEG_INF;
-        const TopKResult r = wave_topk_softmax(v0, v1, N, K, renorm, lane);
-        if (lane < K) {
-            out_idx[t * K + lane] = r.expert;
-            out_w[t * K + lane] = r.weight;
+    const int tl = tid >> 1, half = tid & 1;
+    const int64_t t = t0 + tl;
+    const int e_base = half * LL::HALF;
+    const float *row = Ls + tl * LL::STRIDE + half * (LL::HALF + 4);
+    float val[RT_LIST];
+    int idx[RT_LIST];
+#pragma unroll
+    for (int s = 0; s < RT_LIST; ++s) { val[s] = NEG_INF; idx[s] = 0x7FFFFFFF; }
+#pragma unroll 2
+    for (int e4 = 0; e4 < LL::HALF; e4 += 4) {
+        const floatx4_t v4 = *reinterpret_cast<const floatx4_t *>(row + e4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = e_base + e4 + j;
+            RT_INSERT((e < N) ? v4[j] : NEG_INF, e, RT_BEATS_SCAN)
         }
-        if (out_margin && lane == 0) out_margin[t] = r.margin;
+    }
+    // merge with the neighbour's list (both lanes end with the same merged list)
+    {
+        float pv[RT_LIST];
+        int pi[RT_LIST];
+#pragma unroll
+        for (int s = 0; s < RT_LIST; ++s) {
+            pv[s] = swap_with_neighbour(val[s]);
+            pi[s] = __float_as_int(swap_with_neighbour(__int_as_float(idx[s])));
+        }
+#pragma unroll
+        for (int s = 0; s < RT_LIST; ++s) RT_INSERT(pv[s], pi[s], RT_BEATS_ANY)
+    }
+    // softmax denominator over all N experts, maximum subtracted
+    const float zmax = val[0];
+    float part = 0.f;
+    for (int e4 = 0; e4 < LL::HALF; e4 += 4) {
+        const floatx4_t v4 = *reinterpret_cast<const floatx4_t *>(row + e4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) part += (e_base + e4 + j < N) ? __expf(v4[j] - zmax) : 0.f;
+    }
+    const float den = part + swap_with_neighbour(part);
+
+    if (t < T) {
+        float pk[RT_LIST - 1];
+        float sel = 0.f;
+#pragma unroll
+        for (int j = 0; j < RT_LIST - 1; ++j) {
+            pk[j] = (j < K) ? __expf(val[j] - zmax) : 0.f;
+            sel += pk[j];
+        }
+        const float inv = 1.0f / (renorm ? sel : den);
+        // the even lane writes the ids, the odd lane the weights
+#pragma unroll
+        for (int j = 0; j < RT_LIST - 1; ++j) {
+            if (j < K) {
+                if (half == 0) out_idx[t * K + j] = idx[j];
+                else out_w[t * K + j] = pk[j] * inv;
+            }
+        }
+        if (out_margin && half == 0) {
+            float zk = val[0], zk1 = val[1];
+#pragma unroll
+            for (int j = 1; j < RT_LIST - 1; ++j)
+                if (j < K) { zk = val[j]; zk1 = val[j + 1]; }
+            out_margin[t] = (K < N) ? zk - zk1 : __builtin_inff();
+        }
         if (out_probs) {
-            if (lane < N) out_probs[t * N + lane] = r.e0 / r.den;
-            if (lane + 64 < N) out_probs[t * N + lane + 64] = r.e1 / r.den;
+            const float rden = 1.0f / den;
+            for (int e = 0; e < LL::HALF; ++e)
+                if (e_base + e < N) out_probs[t * N + e_base + e] = __expf(row[e] - zmax) * rden;
         }
     }
 }
