@@ -174,7 +174,8 @@ remoe_status trace_reuse(const int32_t *idx, int64_t n_seq, int64_t n_steps,
  *   state [S, N_r] uint32, or NULL.  Entry e holds (global step of e's last use) + 1, 0 = never
  *         used.  NULL: every trace starts cold and the final state is discarded.  Non-NULL: the
  *         state is read, updated and written back, so a trace can be fed in pieces (online decode:
- *         n_steps = 1 per call); a zero-filled state is a cold cache.
+ *         n_steps = 1 per call); a zero-filled state is a cold cache.  Pieces are fed in order: step0 is
+ *         larger than every step the state already records.
  *   step0 global index of the first step of this call (>= 0; step0 + n_steps must stay below
  *         2^24 so that recency keys fit 32 bits).
  *
