@@ -40,14 +40,20 @@ constexpr int GM_BK = 64;
 // lanes also cover a full 256-byte period.  The 8-lanes-per-row copies into LDS stay conflict-free.
 __device__ __forceinline__ int lds_slot(int r, int c) { return ((r ^ ((r >> 3) & 1)) << 3) + (c ^ (r & 7)); }
 
-// 64 lanes x 16 bytes, global -> LDS without passing through registers: lane l's 16 bytes land at
-// lds_base + 16 l (lds_base must be wave-uniform).  The builtin exists only in the device pass.
-__device__ __forceinline__ void copy16_to_lds(const void *gsrc, void *lds_base)
+// 64 lanes x 16 bytes, global -> LDS without passing through registers: lane l's 16 bytes, read from
+// base + off (wave-uniform 64-bit base, per-lane 32-bit byte offset), land at lds_base + 16 l
+// (lds_base wave-uniform, handed over in M0).  Written as assembly so that the compiler keeps no
+// books on these copies: its own bookkeeping makes every later LDS read wait for all of them,
+// which would undo the overlap.  Every wait for a copy in this file is therefore explicit.  Nothing
+// else in the kernel uses M0.
+__device__ __forceinline__ void copy16_to_lds(const char *base, uint32_t off, const void *lds_base)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_global_load_lds(gsrc, lds_base, 16, 0, 0);
+    const uint32_t dst = (uint32_t)(uintptr_t)lds_base;   // the low 32 bits of a generic LDS pointer are the LDS offset
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(off), "s"(base) : "memory");
 #else
-    (void)gsrc;
+    (void)base;
+    (void)off;
     (void)lds_base;
 #endif
 }
@@ -105,6 +111,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lh = lane >> 5;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // the same value, known to be wave-uniform
 
     // Direct-to-LDS copies: one instruction moves 64 lanes x 16 bytes into 1 KB of contiguous LDS
     // (lane l lands at base + 16 l), i.e. into 8 row slots x 8 chunk positions.  Each lane therefore
@@ -114,6 +121,8 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // spans less than 4 GiB), contiguous rows are relative to the tile's first row, and B offsets
     // stay inside one expert matrix.
     constexpr int NWAVES = WM * WN;
+    constexpr int COPIES = A_CH + B_CH;   // copy instructions per wavefront and slice
+    static_assert((BN / 2) % (NWAVES * 8) == 0, "a copy instruction never straddles the gate and up halves of the B tile");
     const int land_rs = lane >> 3, land_cp = lane & 7;   // landing row slot (within the group), chunk position
     const int nk = p.k_dim / GM_BK;   // >= 1
 
@@ -176,13 +185,17 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 
     // mode 0: row-slot groups below BN/2 rows hold gate rows, the others up rows (a group never straddles)
 #define GM_COPY_SLICE(la, lb, k0)                                                                   \
-    _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                                                 \
-        copy16_to_lds(a_base + a_off[i] + (k0) * 2, &la[(wave + NWAVES * i) * 64]);                 \
-    _Pragma("unroll") for (int i = 0; i < B_CH; ++i) {                                               \
-        const char *bb_ = (MODE == 0 && (wave + NWAVES * i) * 8 >= BN / 2) ? b_base1 : b_base0;     \
-        copy16_to_lds(bb_ + b_off[i] + (k0) * 2, &lb[(wave + NWAVES * i) * 64]);                    \
+    {                                                                                               \
+        const char *ab_ = a_base + (k0) * 2;                                                        \
+        const char *bb0_ = b_base0 + (k0) * 2;                                                      \
+        const char *bb1_ = b_base1 + (k0) * 2;                                                      \
+        _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                                             \
+            copy16_to_lds(ab_, a_off[i], &la[(wave_u + NWAVES * i) * 64]);                          \
+        _Pragma("unroll") for (int i = 0; i < B_CH; ++i)                                             \
+            copy16_to_lds((MODE == 0 && NWAVES * i * 8 >= BN / 2) ? bb1_ : bb0_, b_off[i],          \
+                          &lb[(wave_u + NWAVES * i) * 64]);   /* whole groups: gate rows first, then up rows */ \
     }                                                                                               \
-    __builtin_amdgcn_sched_barrier(0);   /* keep the copies ahead of the MFMA phase */
+    __builtin_amdgcn_sched_barrier(0);   /* keep the copies where they are written */
 
     // fragment of k-step ks: row (tile base) + li, logical chunk 2 * ks + lh
     int fr_idx[4];
@@ -201,8 +214,28 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
         _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                            \
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
-    // k-steps of one slice: fragments of step ks+1 are read while the MFMAs of step ks run
-#define GM_COMPUTE(la, lb)                                                                          \
+    // copy instruction c of a slice (0 .. A_CH-1: A rows, then B rows)
+#define GM_COPY_ONE(la, lb, k0, c)                                                                  \
+    if ((c) < A_CH)                                                                                 \
+        copy16_to_lds(a_base + (k0) * 2, a_off[(c) < A_CH ? (c) : 0], &la[(wave_u + NWAVES * (c)) * 64]); \
+    else                                                                                            \
+        copy16_to_lds(((MODE == 0 && NWAVES * ((c) - A_CH) * 8 >= BN / 2) ? b_base1 : b_base0) + (k0) * 2, \
+                      b_off[(c) >= A_CH ? (c) - A_CH : 0], &lb[(wave_u + NWAVES * ((c) - A_CH)) * 64]);
+    // the MFMAs of one k-step with the copy instructions of a slice dealt out between them, so that
+    // the wavefront never queues several copies at once (a full address queue stalls the wavefront,
+    // MFMAs included)
+#define GM_MFMA_COPIES(fa, fb, la, lb, k0, on)                                                      \
+    _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
+        _Pragma("unroll") for (int ni = 0; ni < TN; ++ni) {                                          \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0); \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+            if (mi * TN + ni < COPIES && (on)) { GM_COPY_ONE(la, lb, k0, mi * TN + ni) }            \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+        }
+    // k-steps of one slice: fragments of step ks+1 are read while the MFMAs of step ks run.  MID runs
+    // after the MFMAs of step 2, when every fragment of the stage has been requested: it waits for
+    // them, passes a barrier and may then refill the stage, a k-step before the slice ends.
+#define GM_COMPUTE(la, lb, MID, LAST)                                                                   \
     {                                                                                               \
         bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];                                                \
         GM_READ_FRAGS(la, lb, 0, fa0, fb0)                                                           \
@@ -218,8 +251,20 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         __builtin_amdgcn_sched_barrier(0);                                                          \
         GM_MFMA(fa0, fb0)                                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
-        GM_MFMA(fa1, fb1)                                                                           \
+        MID                                                                                         \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        LAST(fa1, fb1)                                                                              \
     }
+    // Workgroup barrier that orders LDS traffic only.  (__syncthreads would also wait for every
+    // direct-to-LDS copy in flight.)
+#define GM_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+    // this wavefront's copies of one slice have landed once at most `later` younger vector memory
+    // operations are outstanding (they complete in order); then everyone's have
+    static_assert(COPIES == 8, "the wait immediates below are written for 8 copies per slice");
+#define GM_WAIT_SLICE(more_in_flight)                                                               \
+    if (more_in_flight) __builtin_amdgcn_s_waitcnt(0x0F78); /* vmcnt(8) */                          \
+    else __builtin_amdgcn_s_waitcnt(0x0F70);                /* vmcnt(0) */                          \
+    GM_LDS_BARRIER();
 
     // Epilogue of one 32-row band per wavefront row (mi).  A lane holds column li of 16 rows per
     // accumulator, which would make 2-byte stores.  Instead each band of the workgroup tile (both wm
@@ -234,9 +279,6 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     constexpr int ROWB = BN_OUT * 2;        // bytes per staged row
     constexpr int CPR = BN_OUT / 8;         // 16-byte chunks per staged row
     static_assert(BM <= THREADS, "one thread per tile row fetches the row's gate weight");
-    // Workgroup barrier that orders LDS traffic only.  (__syncthreads would also wait for the
-    // direct-to-LDS copy of the next tile's first slice, which is in flight during the epilogue.)
-#define GM_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
     // accumulators of band mi -> staging array st (u32x4_t[], indexed in dwords)
 #define GM_EPI_STAGE(mi, st, e_par)                                                                 \
     {                                                                                               \
@@ -308,26 +350,21 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-        // Main loop.  Slice 0 is already on its way into stage 0.
-        int kt = 0;
-        if (nk & 1) {   // odd slice count: the first slice runs alone, without a copy behind it
-            __syncthreads();
-            GM_COMPUTE(lds_a0, lds_b0)
-            __syncthreads();
-            kt = 1;
-            if (kt < nk) { GM_COPY_SLICE(lds_a0, lds_b0, kt * GM_BK) }
-        }
-        if (kt < nk) {
-            __syncthreads();   // waits for this wavefront's copies (vmcnt) and then for everyone's
-            // pairs of slices: first in stage 0, second in stage 1; a stage is refilled right after
-            // the barrier that ends its last reads
-            for (; kt < nk; kt += 2) {
-                GM_COPY_SLICE(lds_a1, lds_b1, (kt + 1) * GM_BK)
-                GM_COMPUTE(lds_a0, lds_b0)
-                __syncthreads();
-                if (kt + 2 < nk) { GM_COPY_SLICE(lds_a0, lds_b0, (kt + 2) * GM_BK) }
-                GM_COMPUTE(lds_a1, lds_b1)
-                __syncthreads();
+        // Main loop.  Slice 0 is already on its way into stage 0; even slices use stage 0, odd ones
+        // stage 1.  A stage is refilled with the slice after next as soon as all its fragments have
+        // been read (inside GM_COMPUTE), so a copy has about one and a half slices of MFMA time to land.
+        if (nk > 1) { GM_COPY_SLICE(lds_a1, lds_b1, GM_BK) }
+        GM_WAIT_SLICE(nk > 1)
+#define GM_LAST_REFILL0(fa, fb) GM_MFMA_COPIES(fa, fb, lds_a0, lds_b0, (kt + 2) * GM_BK, refill0)
+#define GM_LAST_REFILL1(fa, fb) GM_MFMA_COPIES(fa, fb, lds_a1, lds_b1, (kt + 3) * GM_BK, refill1)
+        for (int kt = 0; kt < nk; kt += 2) {
+            const bool refill0 = kt + 2 < nk;
+            GM_COMPUTE(lds_a0, lds_b0, GM_LDS_BARRIER();, GM_LAST_REFILL0)
+            if (kt + 1 < nk) {
+                const bool refill1 = kt + 3 < nk;
+                GM_WAIT_SLICE(refill0)
+                GM_COMPUTE(lds_a1, lds_b1, GM_LDS_BARRIER();, GM_LAST_REFILL1)
+                if (refill0) { GM_WAIT_SLICE(refill1) }
             }
         }
 
@@ -342,6 +379,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         const int wm = wave / WN, wn = wave % WN;
         const int li = lane & 31, lh = lane >> 5;
         const int land_rs = lane >> 3, land_cp = lane & 7;
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
         const bool odd = li & 1;
         const int e_row0 = row0, e_rows = rows, e_nt = nt, e_par = par;
         if (has_next) {
