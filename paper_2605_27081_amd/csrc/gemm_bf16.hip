@@ -149,13 +149,14 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         }                                                                                           \
         if (RS > BM) RS = BM;                                                                       \
     }
-    // rows of A this thread copies (through slot -> token when gathered); issued early, used by GM_TILE_OFFSETS
-#define GM_TILE_ROWS()                                                                              \
+    // rows of A this thread copies (through slot -> token when gathered) for the tile at first slot R0
+    // with RS valid rows; fetched a tile ahead, used by GM_TILE_OFFSETS
+#define GM_TILE_ROWS(R0, RS, OUT)                                                                   \
     _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                               \
         const int rs_ = (wave + NWAVES * i) * 8 + land_rs;                                          \
         const int r_ = rs_ ^ ((rs_ >> 3) & 1);                                                      \
-        const int rr_ = r_ < rows ? r_ : rows - 1;                                                  \
-        a_row[i] = p.row_gather ? p.row_gather[row0 + rr_] : rr_;                 \
+        const int rr_ = r_ < (RS) ? r_ : (RS) - 1;                                                  \
+        OUT[i] = p.row_gather ? p.row_gather[(R0) + rr_] : rr_;                                     \
     }
 #define GM_TILE_OFFSETS()                                                                           \
     a_base = reinterpret_cast<const char *>(p.row_gather ? p.a : p.a + (int64_t)row0 * p.lda);      \
@@ -178,8 +179,8 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     }
     // mode 1: the gate weight of tile row tid (threads below BM), fetched early and parked in LDS later
     float scale_reg = 1.0f;
-#define GM_LOAD_SCALE()                                                                             \
-    if (MODE == 1) scale_reg = (p.row_scale && tid < rows) ? p.row_scale[row0 + tid] : 1.0f;
+#define GM_LOAD_SCALE(R0, RS, OUT)                                                                  \
+    if (MODE == 1) OUT = (p.row_scale && tid < (RS)) ? p.row_scale[(R0) + tid] : 1.0f;
 #define GM_FILL_SCALE(buf)                                                                          \
     if (MODE == 1 && tid < BM) lds_scale[buf][tid] = scale_reg;
 
@@ -298,8 +299,8 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
                 if (MODE == 0) {                                                                    \
                     const float g0 = acc[mi][0][r0], u0 = acc[mi][1][r0];                           \
                     const float g1 = acc[mi][0][r0 + 1], u1 = acc[mi][1][r0 + 1];                   \
-                    va = g0 / (1.0f + __expf(-g0)) * u0;                                            \
-                    vb = g1 / (1.0f + __expf(-g1)) * u1;                                            \
+                    va = g0 * u0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0));   /* silu(g) * u; the 1-ulp reciprocal is far inside bf16 rounding */ \
+                    vb = g1 * u1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1));                       \
                 } else {                                                                            \
                     va = acc[mi][ni][r0] * sc0;                                                     \
                     vb = acc[mi][ni][r0 + 1] * sc1;                                                 \
@@ -330,17 +331,38 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     GM_EPI_STORE(mi, st, e_row0, e_rows, e_nt)
 
     GM_TILE_INFO(q, expert, row0, rows, nt)
-    GM_TILE_ROWS()
-    GM_LOAD_SCALE()
+    GM_TILE_ROWS(row0, rows, a_row)
+    GM_LOAD_SCALE(row0, rows, scale_reg)
     GM_TILE_OFFSETS()
     GM_FILL_SCALE(0)
     GM_COPY_SLICE(lds_a0, lds_b0, 0)
+    // descriptor of this workgroup's next tile
+    bool has_next = q + n_slots < q_end;
+    int nx_expert = 0, nx_row0 = 0, nx_rows = 1, nx_nt = 0;
+    if (has_next) GM_TILE_INFO(q + n_slots, nx_expert, nx_row0, nx_rows, nx_nt)
 
     for (;;) {
-        // descriptor of this workgroup's next tile: scalar loads that complete under the main loop
-        const bool has_next = q + n_slots < q_end;
-        int nx_expert = 0, nx_row0 = 0, nx_rows = 1, nx_nt = 0;
-        if (has_next) GM_TILE_INFO(q + n_slots, nx_expert, nx_row0, nx_rows, nx_nt)
+        // Fetched under the main loop: the next tile's row indices and gate weights (its descriptor
+        // arrived a tile ago) and the descriptor of the tile after it.
+        int a_row_nx[A_CH];
+        float scale_nx = 1.0f;
+        const bool has_nn = q + 2 * n_slots < q_end;
+        int nn_expert = 0, nn_row0 = 0, nn_rows = 1, nn_nt = 0;
+        {
+            int tid_early = threadIdx.x;
+            asm volatile("" : "+v"(tid_early));   // (index arithmetic redone here rather than kept in registers)
+            const int tid = tid_early;
+            const int lane = tid & 63, wave = tid >> 6;
+            const int land_rs = lane >> 3;
+            if (has_next) {
+                GM_TILE_ROWS(nx_row0, nx_rows, a_row_nx)
+                GM_LOAD_SCALE(nx_row0, nx_rows, scale_nx)
+            } else {
+#pragma unroll
+                for (int i = 0; i < A_CH; ++i) a_row_nx[i] = 0;
+            }
+            if (has_nn) GM_TILE_INFO(q + 2 * n_slots, nn_expert, nn_row0, nn_rows, nn_nt)
+        }
 
         floatx16_t acc[TM][TN];
 #pragma unroll
@@ -385,11 +407,12 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         if (has_next) {
             expert = nx_expert; row0 = nx_row0; rows = nx_rows; nt = nx_nt;
             par ^= 1;
-            GM_TILE_ROWS()
-            GM_LOAD_SCALE()
+#pragma unroll
+            for (int i = 0; i < A_CH; ++i) a_row[i] = a_row_nx[i];
+            scale_reg = scale_nx;
         }
         GM_EPI_STAGE(0, lds_a1, e_par)
-        if (has_next) {   // before any store of this epilogue is in flight: the loads above are all that is waited for
+        if (has_next) {
             GM_TILE_OFFSETS()
             GM_FILL_SCALE(par)
             GM_COPY_SLICE(lds_a0, lds_b0, 0)
@@ -402,6 +425,8 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         static_assert(TM <= 4, "the epilogue is written out for up to four bands");
         if (!has_next) break;
         q += n_slots;
+        has_next = has_nn;
+        nx_expert = nn_expert; nx_row0 = nn_row0; nx_rows = nn_rows; nx_nt = nn_nt;
     }
 }
 
