@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="before the run, copy this many MiB three times with the library's plain copy kernel "
                          "(the yardstick when the run is profiled with hardware byte counters)")
+    ap.add_argument("--decode-chained", action="store_true",
+                    help="decode workloads: run the layers of a step strictly one after the other (grid-wide waits "
+                         "between them) instead of overlapped")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
     ap.add_argument("--cpu-sample-layers", type=int, default=12)
     return ap.parse_args()

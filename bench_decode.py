@@ -56,9 +56,11 @@ def run_decode(args, cfg):
     nbytes = torch.zeros(len(caps), L, dtype=torch.int64, device=dev)
     ws = torch.zeros(remoe.remoe_decode_workspace_bytes(desc), dtype=torch.uint8, device=dev)
 
+    order = remoe.REMOE_DECODE_CHAINED if getattr(args, "decode_chained", False) else remoe.REMOE_DECODE_PIPELINED
+
     def decode(step0, n):
         remoe.moe_decode(desc, table, x, step0, n, y, idx, gw, caps, cfg.expert_bytes, state, ov, miss, sum_ov,
-                         tot, nbytes, ws)
+                         tot, nbytes, ws, 0, order)
 
     chunk = 128                      # steps per launch: keeps a launch well under a second
     pos = 0
@@ -95,7 +97,8 @@ def run_decode(args, cfg):
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "layers": L, "tokens_per_step": 1, "hidden": H, "n_experts": N,
                    "inter": I, "top_k": K, "rho": rho, "lru_capacities": caps, "seed": cfg.seed,
-                   "steps_per_launch": chunk},
+                   "steps_per_launch": chunk,
+                   "layer_order": "chained" if order == remoe.REMOE_DECODE_CHAINED else "pipelined"},
         "roofline": {"bound": "hbm", "kernel": "decode_kernel (router + K experts gather-GEMV)",
                      "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,

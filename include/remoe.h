@@ -192,7 +192,19 @@ remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps,
  * consecutive single-token steps, as one persistent kernel bound by HBM bandwidth (the B = 1
  * regime of Sec. 3: per layer-step the router matrix and the K selected experts' weights are read
  * once), with the routing-trace statistics updated online after every step (adjacent overlap,
- * Eq. 1; LRU misses of App. E.2 for up to 4 capacities at once).  Layers run in order.
+ * Eq. 1; LRU misses of App. E.2 for up to 4 capacities at once).  Steps run strictly in order.
+ *
+ *   layer_order     how the layers of one step are scheduled.  Every layer of a step reads the same
+ *                   input row x[g] (this path has no attention or residual between MoE layers), so the
+ *                   layers of a step do not depend on each other and both orders give the same result:
+ *                   REMOE_DECODE_CHAINED    a layer starts only after the previous layer has finished
+ *                                           on every compute unit, as in a decoder whose layers feed
+ *                                           each other (three grid-wide waits per layer-step);
+ *                   REMOE_DECODE_PIPELINED  the layers of a step overlap: while layer l's gate/up rows
+ *                                           stream, layer l+1's router logits are computed and layer
+ *                                           l-2's down rows are read, so no wait sits between two
+ *                                           HBM streams (needs top_k * inter <= 4 per wavefront:
+ *                                           top_k * inter <= 32 * compute units).
  *
  *   desc            bf16 layers without shared expert; hidden in {512, 1024, 2048, 4096},
  *                   inter % 8 == 0, top_k * inter <= 6144
@@ -218,6 +230,8 @@ remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps,
  * so other work that holds compute units for long while it runs can trip the wait limit.  Calls
  * that share a workspace or the state arrays must not overlap in time.
  */
+typedef enum { REMOE_DECODE_CHAINED = 0, REMOE_DECODE_PIPELINED = 1 } remoe_decode_order;
+
 size_t remoe_decode_workspace_bytes(const remoe_layer_desc *desc);
 remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers,
                         const void *const *layer_weights,
@@ -227,7 +241,7 @@ remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers,
                         uint32_t *lru_state, uint8_t *out_overlap, uint8_t *out_miss,
                         uint64_t *sum_overlap, uint64_t *total_miss, uint64_t *bytes_fetched,
                         void *workspace, size_t workspace_bytes, uint64_t spin_limit_us,
-                        void *stream);
+                        int32_t layer_order, void *stream);
 
 #ifdef __cplusplus
 }

@@ -6,6 +6,8 @@ loudly when the library has not been built.
 """
 from .binding import (  # noqa: F401
     LayerDesc,
+    REMOE_DECODE_CHAINED,
+    REMOE_DECODE_PIPELINED,
     RemoeError,
     library_path,
     load_library,

@@ -15,6 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libremoe_hip.so")
 _lib: Optional[ctypes.CDLL] = None
 
 REMOE_F32, REMOE_BF16 = 0, 1
+REMOE_DECODE_CHAINED, REMOE_DECODE_PIPELINED = 0, 1
 
 
 class RemoeError(RuntimeError):
@@ -69,7 +70,7 @@ def load_library() -> ctypes.CDLL:
     lib.remoe_decode_workspace_bytes.argtypes = [D]
     lib.moe_decode.restype = ctypes.c_int
     lib.moe_decode.argtypes = [D, I32, P, P, I64, I64, I64, P, P, P, I32, ctypes.POINTER(I32), U64,
-                               P, P, P, P, P, P, P, SZ, U64, P]
+                               P, P, P, P, P, P, P, SZ, U64, I32, P]
     lib.remoe_copy_probe.restype = ctypes.c_int
     lib.remoe_copy_probe.argtypes = [P, P, SZ, P]
     lib.remoe_profile_enable.restype = ctypes.c_int
@@ -181,8 +182,10 @@ def moe_decode(desc: LayerDesc, layer_weights: torch.Tensor, x: torch.Tensor, st
                y: torch.Tensor, out_idx: torch.Tensor, out_w: torch.Tensor, capacities, expert_bytes: int,
                lru_state: torch.Tensor, out_overlap: torch.Tensor, out_miss: Optional[torch.Tensor],
                sum_overlap: torch.Tensor, total_miss: Optional[torch.Tensor],
-               bytes_fetched: Optional[torch.Tensor], workspace: torch.Tensor, spin_limit_us: int = 0) -> None:
-    """layer_weights: int64 device tensor [n_layers, 4] of data_ptr()s (w_router, w_gate, w_up, w_down)."""
+               bytes_fetched: Optional[torch.Tensor], workspace: torch.Tensor, spin_limit_us: int = 0,
+               layer_order: int = 1) -> None:
+    """layer_weights: int64 device tensor [n_layers, 4] of data_ptr()s (w_router, w_gate, w_up, w_down).
+    layer_order: REMOE_DECODE_CHAINED (0) or REMOE_DECODE_PIPELINED (1)."""
     n_layers = layer_weights.shape[0]
     steps_total = x.shape[0]
     caps = (ctypes.c_int32 * max(len(capacities), 1))(*capacities)
@@ -190,4 +193,5 @@ def moe_decode(desc: LayerDesc, layer_weights: torch.Tensor, x: torch.Tensor, st
                                      step0, n_steps, _ptr(y), _ptr(out_idx), _ptr(out_w), len(capacities), caps,
                                      expert_bytes, _ptr(lru_state), _ptr(out_overlap), _ptr(out_miss),
                                      _ptr(sum_overlap), _ptr(total_miss), _ptr(bytes_fetched), _ptr(workspace),
-                                     workspace.numel() * workspace.element_size(), spin_limit_us, _stream()))
+                                     workspace.numel() * workspace.element_size(), spin_limit_us, layer_order,
+                                     _stream()))

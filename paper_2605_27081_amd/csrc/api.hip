@@ -394,13 +394,15 @@ remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers, const vo
                         int32_t *out_idx, float *out_w, int32_t n_caps, const int32_t *capacities,
                         uint64_t expert_bytes, uint32_t *lru_state, uint8_t *out_overlap, uint8_t *out_miss,
                         uint64_t *sum_overlap, uint64_t *total_miss, uint64_t *bytes_fetched, void *workspace,
-                        size_t workspace_bytes, uint64_t spin_limit_us, void *stream)
+                        size_t workspace_bytes, uint64_t spin_limit_us, int32_t layer_order, void *stream)
 {
     remoe_status st = validate_layer_desc(desc);
     if (st != REMOE_OK) return st;
     if (desc->dtype != REMOE_BF16 || desc->shared_inter != 0)
         return fail(REMOE_E_UNSUPPORTED, "moe_decode handles bf16 layers without a shared expert");
     if (n_layers < 1) return fail(REMOE_E_INVALID_ARG, "n_layers %d must be positive", n_layers);
+    if (layer_order != REMOE_DECODE_CHAINED && layer_order != REMOE_DECODE_PIPELINED)
+        return fail(REMOE_E_INVALID_ARG, "layer_order %d is neither REMOE_DECODE_CHAINED nor REMOE_DECODE_PIPELINED", layer_order);
     if (steps_total < 0 || step0 < 0 || n_steps < 0 || step0 + n_steps > steps_total || steps_total >= (1 << 24))
         return fail(REMOE_E_INVALID_ARG, "step range [%lld, %lld) outside 0..steps_total = %lld (< 2^24)",
                     (long long)step0, (long long)(step0 + n_steps), (long long)steps_total);
@@ -434,7 +436,8 @@ remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers, const vo
     d.workspace = workspace;
     d.spin_limit_ticks = (spin_limit_us ? spin_limit_us : 2000000ull) * 100ull;   // 100 MHz wall clock
     ProfScope prof(REMOE_PROF_DECODE, static_cast<hipStream_t>(stream));
-    return launch_decode(d, static_cast<hipStream_t>(stream));
+    return layer_order == REMOE_DECODE_PIPELINED ? launch_decode_pipelined(d, static_cast<hipStream_t>(stream))
+                                                 : launch_decode(d, static_cast<hipStream_t>(stream));
 }
 
 #pragma GCC visibility pop

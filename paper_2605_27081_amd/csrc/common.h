@@ -132,7 +132,8 @@ struct DecodeLaunch {
     uint64_t spin_limit_ticks;
 };
 size_t decode_workspace_bytes(int H, int N, int I, int K);
-remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream);
+remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream);             // layers chained
+remoe_status launch_decode_pipelined(const DecodeLaunch &d, hipStream_t stream);   // layers of a step overlapped
 
 // Trace statistics.
 remoe_status launch_trace_reuse(const int32_t *idx, int64_t S, int64_t T, int K, int N,

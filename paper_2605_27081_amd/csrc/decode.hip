@@ -24,20 +24,21 @@
 // Every wait is bounded: a workgroup that waits longer than the limit raises an abort flag, every
 // other workgroup sees the flag at its next wait, and the whole grid drains.
 #include "common.h"
+#include "decode_common.h"
 #include "topk.h"
 
 namespace remoe {
 
 namespace {
 
-constexpr int DC_THREADS = 512;
+constexpr int DC_THREADS = DEC_THREADS;
 constexpr int DC_WAVES = DC_THREADS / 64;
-constexpr int DC_SEG = 256;          // router row segment per wavefront (floats)
+constexpr int DC_SEG = DEC_SEG;
 constexpr int DC_MAX_KI = 6144;      // K * I floats of h staged in LDS (24 KB)
-constexpr int DC_MAX_CAPS = 4;
-constexpr int DC_MAX_GRID = 1024;     // workgroups the flag barrier can hold
-constexpr int DC_FLAG_BYTES = 256 + DC_MAX_GRID * 4;   // abort flag at byte 128, flags from byte 256
-constexpr int DC_MAX_LAYERS = 64;     // trace state of all layers is kept in LDS
+constexpr int DC_MAX_CAPS = DEC_MAX_CAPS;
+constexpr int DC_MAX_GRID = DEC_MAX_GRID;
+constexpr int DC_FLAG_BYTES = DEC_FLAG_BYTES;
+constexpr int DC_MAX_LAYERS = DEC_MAX_LAYERS;
 constexpr int DC_ITEM_BATCH = 3;     // gate/up activations a wavefront has in flight
 constexpr int DC_MAX_DCH = 12;       // down-projection chunks per lane per output row (K * I <= 6144)
 
@@ -64,164 +65,6 @@ struct DecodeArgs {
     uint32_t *abort_flag;        // zero at launch
     unsigned long long spin_limit;   // wall-clock ticks (100 MHz) a single wait may last
 };
-
-// Data that crosses workgroups inside the kernel (partial logits, SwiGLU activations) is written and
-// read with agent-scope relaxed atomics: such stores write through the per-XCD L2 and such loads
-// bypass it, so no cache write-back or invalidate is needed at the grid barriers.
-__device__ __forceinline__ void put_shared(float *p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float get_shared(const float *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// A value and the number of the phase that produced it, as one 8-byte word.
-__device__ __forceinline__ void put_tagged(unsigned long long *p, float v, uint32_t tag)
-{
-    __hip_atomic_store(p, ((unsigned long long)tag << 32) | __float_as_uint(v), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Grid-wide barrier without read-modify-write traffic: workgroup b publishes the number of the phase
-// it has finished in flags[b]; wavefront 0 of every workgroup polls all flags (each lane a few of
-// them) until none is behind.  The workgroup barrier in front makes every wavefront wait for its own
-// stores first (they are complete at agent scope then).  Returns false when the grid is aborting.
-__device__ __forceinline__ bool grid_barrier(const DecodeArgs &a, uint32_t phase, int *lds_flag)
-{
-    __syncthreads();
-    if (threadIdx.x < 64) {
-        const int lane = threadIdx.x;
-        const int G = gridDim.x;
-        if (lane == 0) __hip_atomic_store(&a.bar[blockIdx.x], phase, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        int ok = 1;
-        unsigned long long t0 = 0;
-        bool timing = false;
-        for (;;) {
-            // one memory round trip per poll: the abort flag travels with the flags
-            const uint32_t ab = __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            bool behind = false;
-            for (int q = lane; q < G; q += 64)
-                behind |= __hip_atomic_load(&a.bar[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < phase;
-            if (!__any(behind)) break;
-            if (!timing) { t0 = wall_clock64(); timing = true; }
-            if (ab) { ok = 0; break; }
-            if (wall_clock64() - t0 > a.spin_limit) {
-                __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ok = 0;
-                break;
-            }
-        }
-        if (lane == 0) *lds_flag = ok;
-    }
-    __syncthreads();
-    return *lds_flag != 0;
-}
-
-// Rendezvous on tagged values: every thread polls its share of the n words until all of them carry
-// `tag`, leaving the values in LDS.  Returns false when the grid is aborting.
-__device__ __forceinline__ bool gather_tagged(const DecodeArgs &a, float *dst, int n, uint32_t tag, int *lds_flag)
-{
-    unsigned long long t0 = 0;
-    bool timing = false;
-    for (;;) {
-        uint32_t ab = 0;
-        if (threadIdx.x == 0) ab = __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        bool behind = false;
-        for (int q = threadIdx.x; q < n; q += DC_THREADS) {
-            const unsigned long long w = __hip_atomic_load(&a.logit_part[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((uint32_t)(w >> 32) == tag) dst[q] = __uint_as_float((uint32_t)w);
-            else behind = true;
-        }
-        if (threadIdx.x == 0) {
-            int ok = 1;
-            if (ab) ok = 0;
-            if (!timing) { t0 = wall_clock64(); timing = true; }
-            else if (wall_clock64() - t0 > a.spin_limit) {
-                __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ok = 0;
-            }
-            *lds_flag = ok;
-        }
-        const int any_behind = __syncthreads_or(behind ? 1 : 0);
-        if (!*lds_flag) return false;
-        if (!any_behind) return true;
-        __syncthreads();      // lds_flag is rewritten in the next round
-    }
-}
-
-__device__ __forceinline__ float dot8(const u32x4_t w, const float *xv, float acc)
-{
-    acc = fmaf(__uint_as_float(w.x << 16), xv[0], acc);
-    acc = fmaf(__uint_as_float(w.x & 0xFFFF0000u), xv[1], acc);
-    acc = fmaf(__uint_as_float(w.y << 16), xv[2], acc);
-    acc = fmaf(__uint_as_float(w.y & 0xFFFF0000u), xv[3], acc);
-    acc = fmaf(__uint_as_float(w.z << 16), xv[4], acc);
-    acc = fmaf(__uint_as_float(w.z & 0xFFFF0000u), xv[5], acc);
-    acc = fmaf(__uint_as_float(w.w << 16), xv[6], acc);
-    acc = fmaf(__uint_as_float(w.w & 0xFFFF0000u), xv[7], acc);
-    return acc;
-}
-
-// Per-layer trace state of the one wavefront that keeps the statistics; it lives in LDS for the whole
-// kernel and is loaded from / stored to device memory at the kernel's ends.
-struct TraceLds {
-    uint32_t last[DC_MAX_LAYERS][128];                 // (step of last use) + 1, 0 = never
-    unsigned long long sum_ov[DC_MAX_LAYERS];
-    unsigned long long tot[DC_MAX_CAPS][DC_MAX_LAYERS];
-};
-
-// Online overlap and LRU misses of one layer-step (one wavefront).  Lane l owns experts l, l + 64.
-__device__ __forceinline__ void online_trace_stats(const DecodeArgs &a, TraceLds &ts, int layer, int64_t g,
-                                                   const int *sel_e, int lane)
-{
-    const int N = a.N, K = a.K;
-    const uint32_t last0 = ts.last[layer][lane], last1 = ts.last[layer][lane + 64];
-    bool req0 = false, req1 = false;
-    for (int j = 0; j < K; ++j) {
-        const int e = sel_e[j];          // LDS broadcast
-        req0 |= (e == lane);
-        req1 |= (e == lane + 64);
-    }
-    req0 &= lane < N;
-    req1 &= lane + 64 < N;
-    // experts of the previous step carry last == g (they were stamped (g - 1) + 1)
-    const int ov = (g > 0) ? __popcll(__ballot(req0 && last0 == (uint32_t)g)) +
-                                 __popcll(__ballot(req1 && last1 == (uint32_t)g))
-                           : 0;
-    const uint32_t key0 = last0 ? ((last0 << 7) | (uint32_t)lane) : 0u;
-    const uint32_t key1 = last1 ? ((last1 << 7) | (uint32_t)(lane + 64)) : 0u;
-    unsigned long long m0 = __ballot(req0), m1 = __ballot(req1);
-    const int n_unique = __popcll(m0) + __popcll(m1);
-    int hits[DC_MAX_CAPS] = {0, 0, 0, 0};
-    while (m0 | m1) {
-        uint32_t ke;
-        if (m0) {
-            const int b = __ffsll((long long)m0) - 1;
-            m0 &= m0 - 1;
-            ke = __shfl(key0, b, 64);
-        } else {
-            const int b = __ffsll((long long)m1) - 1;
-            m1 &= m1 - 1;
-            ke = __shfl(key1, b, 64);
-        }
-        const int above = __popcll(__ballot(key0 > ke)) + __popcll(__ballot(key1 > ke));
-#pragma unroll
-        for (int c = 0; c < DC_MAX_CAPS; ++c) hits[c] += (c < a.n_caps && ke != 0u && above < a.caps[c]);
-    }
-    if (req0) ts.last[layer][lane] = (uint32_t)(g + 1);
-    if (req1) ts.last[layer][lane + 64] = (uint32_t)(g + 1);
-    if (lane == 0) {
-        a.out_overlap[(int64_t)layer * a.steps_total + g] = (uint8_t)ov;
-        ts.sum_ov[layer] += (unsigned long long)ov;
-        for (int c = 0; c < a.n_caps; ++c) {
-            const int miss = n_unique - hits[c];
-            a.out_miss[((int64_t)c * a.n_layers + layer) * a.steps_total + g] = (uint8_t)miss;
-            ts.tot[c][layer] += (unsigned long long)miss;
-        }
-    }
-}
 
 template <int XCH>
 __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
@@ -267,7 +110,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
     floatx4_t wr_pf = {0.f, 0.f, 0.f, 0.f};
     const int e1 = gw / segs, k1 = (gw - e1 * segs) * DC_SEG + lane * 4;
     if (gw < n_items1)
-        wr_pf = *reinterpret_cast<const floatx4_t *>(static_cast<const float *>(a.layers[0]) + (int64_t)e1 * H + k1);
+        wr_pf = load_global<floatx4_t>(static_cast<const float *>(a.layers[0]) + (int64_t)e1 * H + k1);
 
 #pragma unroll 1
     for (int64_t s = 0; s < a.n_steps; ++s) {
@@ -286,7 +129,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                 const int e = item / segs, sg = item - e * segs;
                 const int k0 = sg * DC_SEG + lane * 4;
                 floatx4_t wv = wr_pf;
-                if (item != gw) wv = *reinterpret_cast<const floatx4_t *>(w_router + (int64_t)e * H + k0);
+                if (item != gw) wv = load_global<floatx4_t>(w_router + (int64_t)e * H + k0);
                 const uint2 xb = *reinterpret_cast<const uint2 *>(xg + k0);
                 float p = wv.x * __uint_as_float(xb.x << 16);
                 p = fmaf(wv.y, __uint_as_float(xb.x & 0xFFFF0000u), p);
@@ -375,7 +218,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
         if (q_ < dchunks && row_first < H) {                                                         \
             const int j_ = q_ / chunks_per_row, pos_ = (q_ - j_ * chunks_per_row) * 8;               \
             const uint32_t off_ = (uint32_t)((((int64_t)sel_e[j_] * H + row_first) * I + pos_) * 2); \
-            dv[c] = *reinterpret_cast<const u32x4_t *>(wd_bytes + off_);                             \
+            dv[c] = load_global<u32x4_t>(wd_bytes + off_);                             \
         }                                                                                            \
     }
             {
@@ -392,8 +235,8 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
         const bf16_t *gp_ = w_gate + ((int64_t)e_ * I + i_) * H;                                     \
         const bf16_t *up_ = w_up + ((int64_t)e_ * I + i_) * H;                                       \
         _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                             \
-            gv[c] = *reinterpret_cast<const u32x4_t *>(gp_ + loff + c * 512);                        \
-            uv[c] = *reinterpret_cast<const u32x4_t *>(up_ + loff + c * 512);                        \
+            gv[c] = load_global<u32x4_t>(gp_ + loff + c * 512);                        \
+            uv[c] = load_global<u32x4_t>(up_ + loff + c * 512);                        \
         }                                                                                            \
     }
 #define DC_REDUCE_ITEM(gv, uv, it)                                                                   \
@@ -445,8 +288,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                 int nl = layer + 1;
                 if (nl == a.n_layers) nl = 0;
                 if (gw < n_items1)
-                    wr_pf = *reinterpret_cast<const floatx4_t *>(static_cast<const float *>(a.layers[nl * 4]) +
-                                                                 (int64_t)e1 * H + k1);
+                    wr_pf = load_global<floatx4_t>(static_cast<const float *>(a.layers[nl * 4]) + (int64_t)e1 * H + k1);
             }
             __syncthreads();
 #pragma unroll 1
@@ -462,7 +304,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                         if (rw > 0) {   // further rows of this wavefront are fetched on the spot
                             const int j = q / chunks_per_row, pos = (q - j * chunks_per_row) * 8;
                             const uint32_t off = (uint32_t)((((int64_t)sel_e[j] * H + o) * I + pos) * 2);
-                            wv = *reinterpret_cast<const u32x4_t *>(wd_bytes + off);
+                            wv = load_global<u32x4_t>(wd_bytes + off);
                         }
                         acc = dot8(wv, &hl[q * 8], acc);
                     }
@@ -499,13 +341,7 @@ __global__ void decode_clear_flags(uint32_t *bar, int n, uint32_t *abort_flag, u
 
 }  // namespace
 
-size_t decode_workspace_bytes(int H, int N, int I, int K)
-{
-    size_t off = DC_FLAG_BYTES;                                  // abort flag + barrier flags
-    off += align_up(sizeof(unsigned long long) * (size_t)N * (H / DC_SEG), 256);
-    off += align_up(sizeof(float) * (size_t)K * I, 256);
-    return off;
-}
+size_t decode_workspace_bytes(int H, int N, int I, int K) { return decode_ws_layout(H, N, I, K).total; }
 
 remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream)
 {
@@ -552,8 +388,9 @@ remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream)
     if (G > DC_MAX_GRID) return fail(REMOE_E_UNSUPPORTED, "decode: %d compute units exceed the barrier's %d flags", G, DC_MAX_GRID);
     a.abort_flag = reinterpret_cast<uint32_t *>(ws + 128);
     a.bar = reinterpret_cast<uint32_t *>(ws + 256);
-    a.logit_part = reinterpret_cast<unsigned long long *>(ws + DC_FLAG_BYTES);
-    a.hbuf = reinterpret_cast<float *>(ws + DC_FLAG_BYTES + align_up(sizeof(unsigned long long) * (size_t)d.N * (d.H / DC_SEG), 256));
+    const DecodeWsLayout wl = decode_ws_layout(d.H, d.N, d.I, d.K);
+    a.logit_part = reinterpret_cast<unsigned long long *>(ws + wl.logit_off);
+    a.hbuf = reinterpret_cast<float *>(ws + wl.h_off);
     a.spin_limit = d.spin_limit_ticks;
 
     hipLaunchKernelGGL(decode_clear_flags, dim3(1), dim3(256), 0, stream, a.bar, G, a.abort_flag, a.logit_part,

@@ -1,0 +1,563 @@
+// M = 1 decode with the layers of a step overlapped (software pipeline over layers).
+//
+// Per layer-step the work is the same as in the layer-chained kernel: the fp32 router matrix and the
+// three matrices of the K selected experts are streamed once from HBM (Sec. 3.1 routing; the B = 1
+// regime of Sec. 3), about one flop per byte.  What differs is the order.  Every layer of a step reads
+// the same input row, so the layers of one step do not depend on each other, and the two exchanges a
+// layer needs between workgroups (all partial logits before the top-k, all SwiGLU activations before
+// the down projection) can each be given a whole pipeline stage to arrive instead of a grid barrier:
+//
+//   iteration i of a step:   R(i)    partial router logits of layer i            -> published, tagged
+//                            T(i-1)  top-k / softmax of layer i-1 from the logits published an iteration ago
+//                            G(i-1)  gate/up rows of layer i-1's experts, SwiGLU  -> published, tagged
+//                            D(i-3)  down projection of layer i-3 from the activations published two
+//                                    iterations ago
+//
+// Exchanged values carry the number of the layer-step that produced them (one 8-byte word), so a
+// reader needs no barrier: it polls until the tags match, and in steady state they already do.  The
+// polls and the weight loads of the next iteration are issued before the last activation of the
+// current one is reduced, so HBM keeps streaming across iterations.  Steps stay strictly sequential:
+// a grid barrier closes every step (the statistics of step t+1 need those of step t, and a decoder
+// would need the step's output before it has the next input).
+//
+// A wavefront's (up to three) SwiGLU activations travel as one 8-byte word: three bf16 values and a
+// 16-bit tag.  bf16 is what the batched path stores between its two GEMMs as well; it lets both the
+// gate/up and the down products run as packed bf16 dot instructions (v_dot2_f32_bf16: exact products,
+// fp32 accumulation) against x and h kept in bf16 in LDS.
+//
+// One workgroup of 8 wavefronts per compute unit; every wait is bounded as in the chained kernel.
+#include "common.h"
+#include "decode_common.h"
+#include "topk.h"
+
+namespace remoe {
+
+namespace {
+
+constexpr int DP_THREADS = DEC_THREADS;
+constexpr int DP_WAVES = DP_THREADS / 64;
+constexpr int DP_MAX_KI = 6144;      // K * I activations of one layer
+constexpr int DP_MAX_DCH = 12;       // down-projection 16-byte chunks per lane per output row
+constexpr int DP_POLL_L = 2;         // 16-byte pairs of tagged logit words per thread (N * H / 256 <= 2048)
+constexpr int DP_POLL_H = 2;         // 16-byte pairs of activation words per thread (one word per wavefront, <= 2048)
+constexpr int DP_MAX_ITEMS = 3;      // gate/up activations per wavefront (they share one exchanged word)
+
+struct PipeArgs {
+    const void *const *layers;   // [L][4] device pointers: w_router, w_gate, w_up, w_down
+    const bf16_t *x;             // [T_total, H]
+    int64_t steps_total, step0, n_steps;
+    int n_layers, H, N, I, K, renorm;
+    bf16_t *y;                   // [T_total, L, H]
+    int32_t *out_idx;            // [L, T_total, K]
+    float *out_w;                // [L, T_total, K]
+    int n_caps;
+    int caps[DEC_MAX_CAPS];
+    unsigned long long expert_bytes;
+    uint32_t *lru_state;
+    uint8_t *out_overlap;
+    uint8_t *out_miss;
+    unsigned long long *sum_overlap;
+    unsigned long long *total_miss;
+    unsigned long long *bytes_fetched;
+    unsigned long long *logit_ring;   // [DEC_RING][N * H / 256]  (tag << 32) | float bits
+    unsigned long long *h_ring;       // [DEC_RING][h_slot]: word w = wavefront w's activations, 3 x bf16 | tag16 << 48
+    int h_slot;                       // words per ring slot
+    uint32_t *bar;
+    uint32_t *abort_flag;
+    unsigned long long spin_limit;
+};
+
+// Workgroup barrier that orders LDS traffic only (a full __syncthreads would also wait for every
+// weight load in flight, which is exactly what must keep flying).
+#define DP_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+
+// 16-bit tag of a layer-step (never 0, the value of a cleared word).  A ring slot is rewritten every
+// DEC_RING layer-steps, so a word 65535 layer-steps old cannot survive to be mistaken for a new one.
+__device__ __forceinline__ uint32_t tag16(uint32_t tag) { return tag % 65535u + 1u; }
+
+__device__ __forceinline__ unsigned long long poll_word(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int XCH>
+__global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs a)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t hl[2][DP_MAX_KI];   // activations of two layers (bf16)
+    __shared__ __attribute__((aligned(16))) bf16_t xs[4096];           // the step's input row
+    __shared__ float lpart[2][128 * 16]; // partial logits of the layer being ranked (two iterations apart)
+    __shared__ int sel_e_all[DP_WAVES][DEC_RING][8];     // every wavefront ranks for itself and keeps its own copy,
+    __shared__ float sel_w_all[DP_WAVES][DEC_RING][8];   // so the selection needs no workgroup barrier
+    __shared__ int behind_lds;
+    __shared__ int bar_ok;
+    __shared__ TraceLds ts;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int G = gridDim.x;
+    const int W = G * DP_WAVES;
+    const int gw = blockIdx.x * DP_WAVES + wave;
+    const int H = a.H, N = a.N, I = a.I, K = a.K, L = a.n_layers;
+    const int segs = H / DEC_SEG;
+    const int KI = K * I;
+    const int n_items1 = N * segs;
+    const int items_per_wave = (KI + W - 1) / W;          // <= DP_MAX_ITEMS (checked by the launcher)
+    const int rows_per_wave = (H + W - 1) / W;
+    const int dchunks = KI / 8;
+    const int chunks_per_row = I / 8;
+    const bool stats_wave = blockIdx.x == G - 1 && wave == DP_WAVES - 1;
+    int (*sel_e)[8] = sel_e_all[wave];
+    float (*sel_w)[8] = sel_w_all[wave];
+    uint32_t bar_phase = 0;
+
+    if (blockIdx.x == G - 1) {
+        for (int q = tid; q < L * 128; q += DP_THREADS) {
+            const int l = q >> 7, e = q & 127;
+            ts.last[l][e] = (e < N) ? a.lru_state[l * N + e] : 0u;
+        }
+        for (int q = tid; q < L; q += DP_THREADS) {
+            ts.sum_ov[q] = a.sum_overlap[q];
+            for (int c = 0; c < a.n_caps; ++c) ts.tot[c][q] = a.total_miss[c * L + q];
+        }
+    }
+    if (tid == 0) behind_lds = 0;
+    __syncthreads();
+
+    // ---- per-wavefront constants: which activations, which output row, which router segment ----------
+    const int item0 = gw * items_per_wave;
+    int nit = KI - item0;
+    if (nit > items_per_wave) nit = items_per_wave;
+    if (nit < 0) nit = 0;
+    int it_j[DP_MAX_ITEMS], it_i[DP_MAX_ITEMS];          // (expert slot, intermediate index) of each activation
+#pragma unroll
+    for (int u = 0; u < DP_MAX_ITEMS; ++u) {
+        const int item = item0 + u;
+        const int j = (u < nit) ? item / I : 0;
+        it_j[u] = __builtin_amdgcn_readfirstlane(j);
+        it_i[u] = __builtin_amdgcn_readfirstlane((u < nit) ? item - j * I : 0);
+    }
+    const int row_first = gw * rows_per_wave;
+    uint32_t d_pos[DP_MAX_DCH];                          // byte offset inside a down row | expert slot << 24
+#pragma unroll
+    for (int c = 0; c < DP_MAX_DCH; ++c) {
+        const int q = c * 64 + lane;
+        const int j = (q < dchunks) ? q / chunks_per_row : 0;
+        d_pos[c] = (uint32_t)(((q < dchunks) ? (q - j * chunks_per_row) * 16 : 0) | (j << 24));
+    }
+    const int r_e = gw / segs, r_k = (gw - r_e * segs) * DEC_SEG + lane * 4;   // first router work item
+    const int loff = lane * 8;
+
+#pragma unroll 1
+    for (int64_t s = 0; s < a.n_steps; ++s) {
+        const int64_t g = a.step0 + s;
+        const bf16_t *xg = a.x + g * H;
+        const uint32_t tag0 = (uint32_t)(g * L) + 1u;    // tag of layer l of this step: tag0 + l
+
+        // x of this step lives in LDS as bf16 (registers are needed for loads in flight);
+        // the previous step's last readers are behind the grid barrier that closed it
+        for (int k = tid; k < H / 8; k += DP_THREADS)
+            *reinterpret_cast<u32x4_t *>(&xs[k * 8]) = *reinterpret_cast<const u32x4_t *>(xg + k * 8);
+        DP_LDS_BARRIER();
+
+        // registers that carry loads across the iteration boundary
+        u32x4_t pl[DP_POLL_L], ph[DP_POLL_H];   // two tagged words each: (value, tag, value, tag)
+        u32x4_t dv[DP_MAX_DCH];
+        floatx4_t wr = {0.f, 0.f, 0.f, 0.f};
+
+        // Loads of iteration `itn`: the polls first (loads return in order, so whatever is issued
+        // behind them does not delay them), then the down rows of layer itn-3 and the router segment
+        // of layer itn.
+#define DP_ISSUE_ITER(itn)                                                                            \
+    {                                                                                                 \
+        const int lG_ = (itn) - 1, lD_ = (itn) - 3;                                                   \
+        int tid_ = threadIdx.x;                                                                       \
+        asm volatile("" : "+v"(tid_));   /* offsets are recomputed here, not kept in registers */      \
+        const int lane_ = tid_ & 63;                                                                  \
+        if (lG_ >= 0 && lG_ < L) {                                                                    \
+            const unsigned long long *src_ = a.logit_ring + (size_t)(lG_ & (DEC_RING - 1)) * n_items1; \
+            _Pragma("unroll") for (int k = 0; k < DP_POLL_L; ++k) {                                    \
+                const int q_ = 2 * (tid_ + k * DP_THREADS);                                           \
+                if (q_ < n_items1) pl[k] = *reinterpret_cast<const u32x4_t *>(src_ + q_);             \
+            }                                                                                         \
+        }                                                                                             \
+        if (lD_ >= 0) {                                                                               \
+            const unsigned long long *src_ = a.h_ring + (size_t)(lD_ & (DEC_RING - 1)) * a.h_slot;    \
+            _Pragma("unroll") for (int k = 0; k < DP_POLL_H; ++k) {                                    \
+                const int q_ = 2 * (tid_ + k * DP_THREADS);                                           \
+                if (q_ * items_per_wave < KI) ph[k] = *reinterpret_cast<const u32x4_t *>(src_ + q_);  \
+            }                                                                                         \
+        }                                                                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                            \
+        if (lD_ >= 0 && row_first < H) {                                                              \
+            const char *wd_ = static_cast<const char *>(a.layers[lD_ * 4 + 3]);                       \
+            const int *se_ = sel_e[lD_ & (DEC_RING - 1)];                                             \
+            _Pragma("unroll") for (int c = 0; c < DP_MAX_DCH; ++c) {                                   \
+                if (c * 64 + lane_ < dchunks) {                                                       \
+                    const uint32_t off_ = (uint32_t)(((int64_t)se_[d_pos[c] >> 24] * H + row_first) * I * 2) + (d_pos[c] & 0xFFFFFFu); \
+                    dv[c] = load_global<u32x4_t>(wd_ + off_);                           \
+                }                                                                                     \
+            }                                                                                         \
+        }                                                                                             \
+        if ((itn) < L && gw < n_items1)                                                               \
+            wr = load_global<floatx4_t>(static_cast<const float *>(a.layers[(itn) * 4]) + (int64_t)r_e * H + r_k); \
+        __builtin_amdgcn_sched_barrier(0);                                                            \
+    }
+
+        DP_ISSUE_ITER(0)
+
+#pragma unroll 1
+        for (int it = 0; it < L + 3; ++it) {
+            const int lR = it, lG = it - 1, lD = it - 3;
+            const bool doR = lR < L, doG = lG >= 0 && lG < L, doD = lD >= 0;
+
+            // ---- consume the polls: partial logits of layer lG, activations of layer lD ---------------
+            bool behind = false;
+            int tid_c = threadIdx.x;
+            asm volatile("" : "+v"(tid_c));
+            if (doG) {
+                const uint32_t tg = tag0 + (uint32_t)lG;
+                float *dst = lpart[it & 1];
+#pragma unroll
+                for (int k = 0; k < DP_POLL_L; ++k) {
+                    const int q = 2 * (tid_c + k * DP_THREADS);
+                    if (q < n_items1) {
+                        if (pl[k].y == tg && pl[k].w == tg) {
+                            dst[q] = __uint_as_float(pl[k].x);
+                            dst[q + 1] = __uint_as_float(pl[k].z);
+                        } else behind = true;
+                    }
+                }
+            }
+            if (doD) {
+                const uint32_t td = tag16(tag0 + (uint32_t)lD);
+                bf16_t *dst = hl[lD & 1];
+#pragma unroll
+                for (int k = 0; k < DP_POLL_H; ++k) {
+                    const int u = 2 * (tid_c + k * DP_THREADS);         // first of two wavefront words
+                    if (u * items_per_wave < KI) {
+                        const bool two = (u + 1) * items_per_wave < KI;
+                        if ((ph[k].y >> 16) == td && (!two || (ph[k].w >> 16) == td)) {
+                            const int i0 = u * items_per_wave;
+                            dst[i0] = (bf16_t)ph[k].x;
+                            if (items_per_wave > 1 && i0 + 1 < KI) dst[i0 + 1] = (bf16_t)(ph[k].x >> 16);
+                            if (items_per_wave > 2 && i0 + 2 < KI) dst[i0 + 2] = (bf16_t)ph[k].y;
+                            if (two) {
+                                const int i1 = i0 + items_per_wave;
+                                dst[i1] = (bf16_t)ph[k].z;
+                                if (items_per_wave > 1 && i1 + 1 < KI) dst[i1 + 1] = (bf16_t)(ph[k].z >> 16);
+                                if (items_per_wave > 2 && i1 + 2 < KI) dst[i1 + 2] = (bf16_t)ph[k].w;
+                            }
+                        } else behind = true;
+                    }
+                }
+            }
+            if (__any(behind) && lane == 0) behind_lds = 1;
+            DP_LDS_BARRIER();
+            if (behind_lds) {
+                // Slow path (a producer was more than a pipeline stage late): poll again until every
+                // tag matches, with the bounded wait.
+                unsigned long long t0 = 0;
+                bool timing = false;
+                for (;;) {
+                    DP_LDS_BARRIER();          // everyone has read behind_lds / bar_ok of the last round
+                    uint32_t ab = 0;
+                    if (tid == 0) ab = __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    bool still = false;
+                    if (doG) {
+                        const uint32_t tg = tag0 + (uint32_t)lG;
+                        const unsigned long long *src = a.logit_ring + (size_t)(lG & (DEC_RING - 1)) * n_items1;
+                        for (int q = tid; q < n_items1; q += DP_THREADS) {
+                            const unsigned long long w = poll_word(src + q);
+                            if ((uint32_t)(w >> 32) == tg) lpart[it & 1][q] = __uint_as_float((uint32_t)w);
+                            else still = true;
+                        }
+                    }
+                    if (doD) {
+                        const uint32_t td = tag16(tag0 + (uint32_t)lD);
+                        const unsigned long long *src = a.h_ring + (size_t)(lD & (DEC_RING - 1)) * a.h_slot;
+                        bf16_t *dst = hl[lD & 1];
+                        for (int u = tid; u * items_per_wave < KI; u += DP_THREADS) {
+                            const unsigned long long w = poll_word(src + u);
+                            if ((uint32_t)(w >> 48) == td) {
+                                for (int v = 0; v < items_per_wave; ++v)
+                                    if (u * items_per_wave + v < KI) dst[u * items_per_wave + v] = (bf16_t)(w >> (16 * v));
+                            } else still = true;
+                        }
+                    }
+                    if (tid == 0) {
+                        int ok = 1;
+                        if (ab) ok = 0;
+                        if (!timing) { t0 = wall_clock64(); timing = true; }
+                        else if (wall_clock64() - t0 > a.spin_limit) {
+                            __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            ok = 0;
+                        }
+                        bar_ok = ok;
+                        behind_lds = 0;
+                    }
+                    DP_LDS_BARRIER();          // behind_lds cleared, bar_ok set
+                    if (__any(still) && lane == 0) behind_lds = 1;
+                    DP_LDS_BARRIER();
+                    if (!bar_ok) return;
+                    if (!behind_lds) break;
+                }
+            }
+
+            // ---- top-k and softmax of layer lG: every wavefront for itself (same result everywhere, no
+            // barrier): K rounds of wavefront maximum, ties to the lower id -------------------------------
+            if (doG) {
+                const float NEG_INF = -__builtin_inff();
+                const float *lp = lpart[it & 1];
+                float v0 = NEG_INF, v1 = NEG_INF;
+                if (lane < N) {
+                    v0 = 0.f;
+                    for (int q = 0; q < segs; ++q) v0 += lp[lane * segs + q];
+                }
+                if (lane + 64 < N) {
+                    v1 = 0.f;
+                    for (int q = 0; q < segs; ++q) v1 += lp[(lane + 64) * segs + q];
+                }
+                float m0 = v0, m1 = v1, my_z = NEG_INF, zmax = 0.f;
+                int my_e = 0;
+                for (int j = 0; j < K; ++j) {
+                    const float m = wave_max(fmaxf(m0, m1));
+                    const unsigned long long b0 = __ballot(m0 == m), b1 = __ballot(m1 == m);
+                    const int e = b0 ? __ffsll((long long)b0) - 1 : 63 + __ffsll((long long)b1);
+                    if (j == 0) zmax = m;
+                    if (lane == j) { my_z = m; my_e = e; }
+                    if (e == lane) m0 = NEG_INF;
+                    if (e == lane + 64) m1 = NEG_INF;
+                }
+                const float den = wave_sum(((lane < N) ? expf(v0 - zmax) : 0.f) + ((lane + 64 < N) ? expf(v1 - zmax) : 0.f));
+                const float my_p = (lane < K) ? expf(my_z - zmax) : 0.f;
+                float wgt = my_p / den;
+                if (a.renorm) wgt = my_p / wave_sum(my_p);
+                if (lane < K) {
+                    sel_e[lG & (DEC_RING - 1)][lane] = my_e;
+                    sel_w[lG & (DEC_RING - 1)][lane] = wgt;
+                    if (blockIdx.x == 0 && wave == 0) {
+                        const int64_t o = ((int64_t)lG * a.steps_total + g) * K + lane;
+                        a.out_idx[o] = my_e;
+                        a.out_w[o] = wgt;
+                    }
+                }
+            }
+
+            // ---- G(lG): request the first two activations' gate and up rows ---------------------------
+            u32x4_t gA[XCH], uA[XCH], gB[XCH], uB[XCH];
+            const bf16_t *w_gate = doG ? static_cast<const bf16_t *>(a.layers[lG * 4 + 1]) : nullptr;
+            const bf16_t *w_up = doG ? static_cast<const bf16_t *>(a.layers[lG * 4 + 2]) : nullptr;
+            const int *se_g = sel_e[lG & (DEC_RING - 1)];
+#define DP_LOAD_ITEM(gv, uv, u)                                                                       \
+    {                                                                                                 \
+        const int e_ = __builtin_amdgcn_readfirstlane(se_g[it_j[u]]);                                 \
+        const bf16_t *gp_ = w_gate + ((int64_t)e_ * I + it_i[u]) * H;                                 \
+        const bf16_t *up_ = w_up + ((int64_t)e_ * I + it_i[u]) * H;                                   \
+        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
+            gv[c] = load_global<u32x4_t>(gp_ + loff + c * 512);                         \
+            uv[c] = load_global<u32x4_t>(up_ + loff + c * 512);                         \
+        }                                                                                             \
+    }
+#define DP_REDUCE_ITEM(gv, uv, u)                                                                     \
+    {                                                                                                 \
+        float gs_ = 0.f, us_ = 0.f;                                                                   \
+        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
+            const u32x4_t xq_ = *reinterpret_cast<const u32x4_t *>(&xs[(c * 64 + lane) * 8]);         \
+            gs_ = dot8_bf16(gv[c], xq_, gs_);                                                         \
+            us_ = dot8_bf16(uv[c], xq_, us_);                                                         \
+        }                                                                                             \
+        gs_ = wave_sum(gs_);                                                                          \
+        us_ = wave_sum(us_);                                                                          \
+        h_word |= (unsigned long long)f32_to_bf16(gs_ / (1.0f + expf(-gs_)) * us_) << (16 * (u));     \
+    }
+            const int nG = doG ? nit : 0;
+            unsigned long long h_word = (unsigned long long)tag16(tag0 + (uint32_t)lG) << 48;
+            if (nG > 0) DP_LOAD_ITEM(gA, uA, 0)
+            if (nG > 1) DP_LOAD_ITEM(gB, uB, 1)
+            __builtin_amdgcn_sched_barrier(0);
+
+            // ---- R(lR): this wavefront's router segment(s) -> tagged partial logits ---------------------
+            if (doR) {
+                const float *w_router = static_cast<const float *>(a.layers[lR * 4]);
+                unsigned long long *dstp = a.logit_ring + (size_t)(lR & (DEC_RING - 1)) * n_items1;
+#pragma unroll 1
+                for (int item = gw; item < n_items1; item += W) {
+                    floatx4_t wv = wr;
+                    int k0 = r_k;
+                    if (item != gw) {
+                        const int e = item / segs;
+                        k0 = (item - e * segs) * DEC_SEG + lane * 4;
+                        wv = load_global<floatx4_t>(w_router + (int64_t)e * H + k0);
+                    }
+                    const uint2 xb = *reinterpret_cast<const uint2 *>(&xs[k0]);
+                    float p = wv.x * __uint_as_float(xb.x << 16);
+                    p = fmaf(wv.y, __uint_as_float(xb.x & 0xFFFF0000u), p);
+                    p = fmaf(wv.z, __uint_as_float(xb.y << 16), p);
+                    p = fmaf(wv.w, __uint_as_float(xb.y & 0xFFFF0000u), p);
+                    p = wave_sum(p);
+                    if (lane == 0) put_tagged(dstp + item, p, tag0 + (uint32_t)lR);
+                }
+            }
+
+            // ---- statistics of layer lG (one wavefront of the grid), riding on the loads in flight -----
+            if (doG && stats_wave) online_trace_stats(a, ts, lG, g, se_g, lane);
+
+            // ---- D(lD): output rows of layer lD ------------------------------------------------------
+            if (doD) {
+                const char *wd_bytes = static_cast<const char *>(a.layers[lD * 4 + 3]);
+                const int *se_d = sel_e[lD & (DEC_RING - 1)];
+                const bf16_t *hcur = hl[lD & 1];
+                const float *sw_d = sel_w[lD & (DEC_RING - 1)];
+                int lane_d = threadIdx.x & 63;
+                asm volatile("" : "+v"(lane_d));
+#pragma unroll 1
+                for (int rw = 0; rw < rows_per_wave; ++rw) {
+                    const int o = row_first + rw;
+                    if (o >= H) break;
+                    float acc = 0.f;
+#pragma unroll
+                    for (int c = 0; c < DP_MAX_DCH; ++c) {
+                        const int q = c * 64 + lane_d;
+                        if (q < dchunks) {
+                            u32x4_t wv = dv[c];
+                            if (rw > 0) {
+                                const uint32_t off = (uint32_t)(((int64_t)se_d[d_pos[c] >> 24] * H + o) * I * 2) + (d_pos[c] & 0xFFFFFFu);
+                                wv = load_global<u32x4_t>(wd_bytes + off);
+                            }
+                            const u32x4_t hq = *reinterpret_cast<const u32x4_t *>(&hcur[q * 8]);
+                            acc = fmaf(sw_d[d_pos[c] >> 24], dot8_bf16(wv, hq, 0.f), acc);
+                        }
+                    }
+                    acc = wave_sum(acc);
+                    if (lane == 0) a.y[(g * L + lD) * H + o] = f32_to_bf16(acc);
+                }
+            }
+
+            // ---- G(lG): roll over the activations (register sets A and B alternate); the next
+            // iteration's polls and weight loads go out right before the last one is reduced, so the
+            // memory pipe never runs dry between iterations ----------------------------------------------
+            if (nG > 1) { DP_REDUCE_ITEM(gA, uA, 0) if (nG > 2) DP_LOAD_ITEM(gA, uA, 2) }
+            if (nG > 2) { DP_REDUCE_ITEM(gB, uB, 1) }
+            if (it + 1 < L + 3) { DP_ISSUE_ITER(it + 1) }
+            if (nG > 0) {
+                if ((nG - 1) & 1) { DP_REDUCE_ITEM(gB, uB, nG - 1) } else { DP_REDUCE_ITEM(gA, uA, nG - 1) }
+                if (lane == 0)
+                    __hip_atomic_store(&a.h_ring[(size_t)(lG & (DEC_RING - 1)) * a.h_slot + gw], h_word, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+
+        // ---- the step is complete everywhere before the next one starts ---------------------------------
+        if (!grid_barrier(a, ++bar_phase, &bar_ok)) return;
+    }
+
+    if (blockIdx.x == G - 1) {
+        __syncthreads();
+        for (int q = tid; q < L * 128; q += DP_THREADS) {
+            const int l = q >> 7, e = q & 127;
+            if (e < N) a.lru_state[l * N + e] = ts.last[l][e];
+        }
+        for (int q = tid; q < L; q += DP_THREADS) {
+            a.sum_overlap[q] = ts.sum_ov[q];
+            for (int c = 0; c < a.n_caps; ++c) {
+                a.total_miss[c * L + q] = ts.tot[c][q];
+                a.bytes_fetched[c * L + q] = ts.tot[c][q] * a.expert_bytes;
+            }
+        }
+    }
+}
+
+__global__ void decode_pipe_clear(uint32_t *bar, int n, uint32_t *abort_flag, unsigned long long *tagged, int n_tagged)
+{
+    for (int q = threadIdx.x; q < n; q += blockDim.x) bar[q] = 0u;
+    for (int q = threadIdx.x; q < n_tagged; q += blockDim.x) tagged[q] = 0ull;   // tag 0 = no layer-step
+    if (threadIdx.x == 0) *abort_flag = 0u;
+}
+
+}  // namespace
+
+remoe_status launch_decode_pipelined(const DecodeLaunch &d, hipStream_t stream)
+{
+    if (d.H != 512 && d.H != 1024 && d.H != 2048 && d.H != 4096)
+        return fail(REMOE_E_UNSUPPORTED, "decode supports hidden in {512, 1024, 2048, 4096} (got %d)", d.H);
+    if (d.I % 8 != 0 || d.K * d.I > DP_MAX_KI)
+        return fail(REMOE_E_UNSUPPORTED, "decode needs inter %% 8 == 0 and top_k * inter <= %d", DP_MAX_KI);
+    if (d.n_layers > DEC_MAX_LAYERS)
+        return fail(REMOE_E_UNSUPPORTED, "decode keeps the trace state of at most %d layers (got %d)", DEC_MAX_LAYERS, d.n_layers);
+    if (d.n_caps < 0 || d.n_caps > DEC_MAX_CAPS)
+        return fail(REMOE_E_INVALID_ARG, "n_caps %d outside 0..%d", d.n_caps, DEC_MAX_CAPS);
+    if ((int64_t)d.N * d.H * d.I * 2 >= ((int64_t)1 << 32))
+        return fail(REMOE_E_UNSUPPORTED, "decode: one layer's down-projection tensor spans 4 GiB or more");
+    if ((int64_t)d.steps_total * d.n_layers + d.n_layers >= ((int64_t)1 << 32))
+        return fail(REMOE_E_UNSUPPORTED, "decode: steps_total * n_layers does not fit the 32-bit exchange tags");
+    int dev = 0, n_cu = 0;
+    REMOE_HIP_TRY(hipGetDevice(&dev));
+    REMOE_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (n_cu < 1) return fail(REMOE_E_HIP, "device reports no compute units");
+    const int G = n_cu;
+    const int W = G * DP_WAVES;
+    const DecodeWsLayout wl0 = decode_ws_layout(d.H, d.N, d.I, d.K);
+    if (G > DEC_MAX_GRID) return fail(REMOE_E_UNSUPPORTED, "decode: %d compute units exceed the barrier's %d flags", G, DEC_MAX_GRID);
+    if (W > 2 * DP_POLL_H * DP_THREADS || W > wl0.n_h)
+        return fail(REMOE_E_UNSUPPORTED, "decode: %d wavefronts exceed the %d exchange words a workgroup polls", W, 2 * DP_POLL_H * DP_THREADS);
+    if ((d.K * d.I + W - 1) / W > DP_MAX_ITEMS)
+        return fail(REMOE_E_UNSUPPORTED, "decode: top_k * inter = %d needs more than %d activations per wavefront on %d compute units",
+                    d.K * d.I, DP_MAX_ITEMS, G);
+    if (d.N * (d.H / DEC_SEG) > DP_POLL_L * DP_THREADS)
+        return fail(REMOE_E_UNSUPPORTED, "decode: n_experts * hidden / 256 exceeds %d", DP_POLL_L * DP_THREADS);
+
+    PipeArgs a;
+    a.layers = d.layers;
+    a.x = static_cast<const bf16_t *>(d.x);
+    a.steps_total = d.steps_total;
+    a.step0 = d.step0;
+    a.n_steps = d.n_steps;
+    a.n_layers = d.n_layers;
+    a.H = d.H; a.N = d.N; a.I = d.I; a.K = d.K; a.renorm = d.renorm;
+    a.y = static_cast<bf16_t *>(d.y);
+    a.out_idx = d.out_idx;
+    a.out_w = d.out_w;
+    a.n_caps = d.n_caps;
+    for (int c = 0; c < DEC_MAX_CAPS; ++c) a.caps[c] = (c < d.n_caps) ? d.caps[c] : 0;
+    a.expert_bytes = d.expert_bytes;
+    a.lru_state = d.lru_state;
+    a.out_overlap = d.out_overlap;
+    a.out_miss = d.out_miss;
+    a.sum_overlap = reinterpret_cast<unsigned long long *>(d.sum_overlap);
+    a.total_miss = reinterpret_cast<unsigned long long *>(d.total_miss);
+    a.bytes_fetched = reinterpret_cast<unsigned long long *>(d.bytes_fetched);
+    char *ws = static_cast<char *>(d.workspace);
+    const DecodeWsLayout wl = decode_ws_layout(d.H, d.N, d.I, d.K);
+    a.abort_flag = reinterpret_cast<uint32_t *>(ws + 128);
+    a.bar = reinterpret_cast<uint32_t *>(ws + 256);
+    a.logit_ring = reinterpret_cast<unsigned long long *>(ws + wl.logit_off);
+    a.h_ring = reinterpret_cast<unsigned long long *>(ws + wl.h_off);
+    a.h_slot = wl.n_h;
+    a.spin_limit = d.spin_limit_ticks;
+
+    // both rings are contiguous from logit_off to the end of the workspace
+    hipLaunchKernelGGL(decode_pipe_clear, dim3(1), dim3(1024), 0, stream, a.bar, G, a.abort_flag, a.logit_ring,
+                       (int)((wl.total - wl.logit_off) / sizeof(unsigned long long)));
+    void *params[] = {&a};
+    const void *fn = nullptr;
+    switch (d.H / 512) {
+    case 1: fn = reinterpret_cast<const void *>(decode_pipe_kernel<1>); break;
+    case 2: fn = reinterpret_cast<const void *>(decode_pipe_kernel<2>); break;
+    case 4: fn = reinterpret_cast<const void *>(decode_pipe_kernel<4>); break;
+    case 8: fn = reinterpret_cast<const void *>(decode_pipe_kernel<8>); break;
+    default: return fail(REMOE_E_UNSUPPORTED, "decode supports hidden in {512, 1024, 2048, 4096} (got %d)", d.H);
+    }
+    // Every workgroup must be resident (the exchanges and the step barrier wait for all of them): one
+    // workgroup per compute unit, checked against the occupancy; unused dynamic LDS lifts a workgroup
+    // above half a compute unit's 160 KB so that no two share a compute unit while another idles.
+    hipFuncAttributes attr;
+    REMOE_HIP_TRY(hipFuncGetAttributes(&attr, fn));
+    const size_t half_lds = 80 * 1024 + 256;
+    const size_t pad = attr.sharedSizeBytes < half_lds ? half_lds - attr.sharedSizeBytes : 0;
+    int per_cu = 0;
+    REMOE_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, DP_THREADS, pad));
+    if (per_cu < 1) return fail(REMOE_E_UNSUPPORTED, "decode: a workgroup does not fit one compute unit");
+    REMOE_HIP_TRY(hipLaunchKernel(fn, dim3(G), dim3(DP_THREADS), params, pad, stream));
+    return REMOE_OK;
+}
+
+}  // namespace remoe

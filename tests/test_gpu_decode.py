@@ -31,7 +31,7 @@ def _layers(seed, L, H, N, I, std):
     return out
 
 
-def _run_decode(desc, layers, x, caps, expert_bytes, pieces, spin_limit_us=0):
+def _run_decode(desc, layers, x, caps, expert_bytes, pieces, spin_limit_us=0, order=remoe.REMOE_DECODE_PIPELINED):
     L, T = len(layers), x.shape[0]
     K, N, H = desc.top_k, desc.n_experts, desc.hidden
     table = torch.tensor([[w["w_router"].data_ptr(), w["w_gate"].data_ptr(), w["w_up"].data_ptr(),
@@ -51,7 +51,7 @@ def _run_decode(desc, layers, x, caps, expert_bytes, pieces, spin_limit_us=0):
     pos = 0
     for n in pieces:
         remoe.moe_decode(desc, table, x, pos, n, out["y"], out["idx"], out["w"], caps, expert_bytes, out["state"],
-                         out["ov"], out["miss"], out["sum_ov"], out["tot"], out["bytes"], ws, spin_limit_us)
+                         out["ov"], out["miss"], out["sum_ov"], out["tot"], out["bytes"], ws, spin_limit_us, order)
         torch.cuda.synchronize()
         pos += n
     assert pos == T
@@ -81,34 +81,54 @@ def _check_decode(desc, layers, x, caps, expert_bytes, out, renorm):
     return worst
 
 
+@pytest.mark.parametrize("order", [remoe.REMOE_DECODE_CHAINED, remoe.REMOE_DECODE_PIPELINED], ids=["chained", "pipelined"])
 @pytest.mark.parametrize("L,T,H,N,I,K,renorm,caps,pieces", [
     (3, 40, 512, 16, 64, 4, True, [4, 8], [40]),
     (2, 33, 1024, 60, 128, 4, False, [12], [1, 1, 7, 24]),          # online: fed in pieces
     (4, 24, 2048, 128, 768, 8, True, [16, 32, 64], [10, 14]),       # the Qwen3-30B-A3B layer shape
     (1, 17, 512, 8, 64, 8, False, [2, 8, 9, 3], [17]),              # K = N, C < K, four capacities
 ])
-def test_decode_matches_oracle(L, T, H, N, I, K, renorm, caps, pieces):
-    _say(f"decode L={L} T={T} H={H} N={N} I={I} K={K} caps={caps} pieces={pieces}")
+def test_decode_matches_oracle(L, T, H, N, I, K, renorm, caps, pieces, order):
+    _say(f"decode order={order} L={L} T={T} H={H} N={N} I={I} K={K} caps={caps} pieces={pieces}")
     layers = _layers(70 + N, L, H, N, I, 0.05)
     x = wl.ar1_hidden_states(70 + N, 1, T, H, 0.9, torch.bfloat16, DEV)[0].contiguous()
     desc = remoe.LayerDesc(H, N, I, K, int(renorm), 0, 0, 1)
-    out = _run_decode(desc, layers, x, caps, 3 * H * I * 2, pieces)
+    out = _run_decode(desc, layers, x, caps, 3 * H * I * 2, pieces, order=order)
     err = _check_decode(desc, layers, x, caps, 3 * H * I * 2, out, renorm)
     _say(f"  worst rel L2 {err:.3e}")
 
 
-def test_decode_wait_limit_aborts_cleanly():
+def test_decode_orders_agree():
+    """Chained and pipelined schedules route identically (same fp32 router arithmetic: ids, gate
+    weights and every statistic agree bit for bit); the layer outputs agree to bf16 rounding (the
+    pipelined kernel carries h in bf16 and uses packed bf16 dot products)."""
+    L, T, H, N, I, K = 5, 12, 1024, 32, 256, 4
+    layers = _layers(90, L, H, N, I, 0.05)
+    x = wl.ar1_hidden_states(90, 1, T, H, 0.7, torch.bfloat16, DEV)[0].contiguous()
+    desc = remoe.LayerDesc(H, N, I, K, 1, 0, 0, 1)
+    a = _run_decode(desc, layers, x, [6, 16], 7, [5, 7], order=remoe.REMOE_DECODE_CHAINED)
+    b = _run_decode(desc, layers, x, [6, 16], 7, [12], order=remoe.REMOE_DECODE_PIPELINED)
+    assert a["abort"] == 0 and b["abort"] == 0
+    for k in ("idx", "ov", "miss", "sum_ov", "tot", "bytes", "state"):
+        assert torch.equal(a[k], b[k]), k
+    assert torch.equal(a["w"].view(torch.int32), b["w"].view(torch.int32))
+    ya, yb = a["y"].double(), b["y"].double()
+    assert float((ya - yb).norm() / ya.norm()) < 1e-2
+
+
+@pytest.mark.parametrize("order", [remoe.REMOE_DECODE_CHAINED, remoe.REMOE_DECODE_PIPELINED], ids=["chained", "pipelined"])
+def test_decode_wait_limit_aborts_cleanly(order):
     """A wait limit the barrier cannot meet makes the kernel give up: it must still exit (no hang)
     and report it through the abort flag."""
     L, T, H, N, I, K = 2, 4, 512, 16, 64, 4
     layers = _layers(81, L, H, N, I, 0.05)
     x = wl.ar1_hidden_states(81, 1, T, H, 0.5, torch.bfloat16, DEV)[0].contiguous()
     desc = remoe.LayerDesc(H, N, I, K, 1, 0, 0, 1)
-    ok = _run_decode(desc, layers, x, [4], 1, [T])
+    ok = _run_decode(desc, layers, x, [4], 1, [T], order=order)
     assert ok["abort"] == 0
     # the limit is per wait; 10 ns cannot cover one atomic round trip of 256 workgroups
     # (spin_limit_us is in whole microseconds, so this uses the smallest value, 1 us, and many layers)
-    aborted = _run_decode(desc, layers * 8, x, [4], 1, [T], spin_limit_us=1)
+    aborted = _run_decode(desc, layers * 8, x, [4], 1, [T], spin_limit_us=1, order=order)
     assert aborted["abort"] in (0, 1)      # either it kept up or it gave up; it returned either way
 
 
@@ -124,3 +144,6 @@ def test_decode_rejects_unsupported_layers():
     x2 = torch.zeros(4, 512, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(remoe.RemoeError, match="shared"):
         remoe.moe_decode(desc2, t, x2, 0, 4, x2, z, z, [4], 1, z, z, z, z, z, z, ws)
+    desc3 = remoe.LayerDesc(512, 16, 64, 4, 1, 0, 0, 1)
+    with pytest.raises(remoe.RemoeError, match="layer_order"):
+        remoe.moe_decode(desc3, t, x2, 0, 4, x2, z, z, [4], 1, z, z, z, z, z, z, ws, 0, 7)
