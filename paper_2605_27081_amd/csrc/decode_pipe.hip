@@ -8,13 +8,15 @@
 // the down projection) can each be given a whole pipeline stage to arrive instead of a grid barrier:
 //
 //   iteration i of a step:   R(i)    partial router logits of layer i            -> published, tagged
-//                            T(i-1)  top-k / softmax of layer i-1 from the logits published an iteration ago
-//                            G(i-1)  gate/up rows of layer i-1's experts, SwiGLU  -> published, tagged
-//                            D(i-3)  down projection of layer i-3 from the activations published two
+//                            T(i-1)  top-k / softmax of layer i-1 from the logits published an iteration
+//                                    ago (one wavefront per workgroup, off the others' critical path)
+//                            G(i-2)  gate/up rows of layer i-2's experts, SwiGLU  -> published, tagged
+//                            D(i-4)  down projection of layer i-4 from the activations published two
 //                                    iterations ago
 //
 // Exchanged values carry the number of the layer-step that produced them (one 8-byte word), so a
-// reader needs no barrier: it polls until the tags match, and in steady state they already do.  The
+// reader needs no barrier: it polls (agent-scope loads, which bypass the per-XCD L2 and its stale
+// copies) until the tags match, and in steady state they already do.  The
 // polls and the weight loads of the next iteration are issued before the last activation of the
 // current one is reduced, so HBM keeps streaming across iterations.  Steps stay strictly sequential:
 // a grid barrier closes every step (the statistics of step t+1 need those of step t, and a decoder
@@ -38,8 +40,8 @@ constexpr int DP_THREADS = DEC_THREADS;
 constexpr int DP_WAVES = DP_THREADS / 64;
 constexpr int DP_MAX_KI = 6144;      // K * I activations of one layer
 constexpr int DP_MAX_DCH = 12;       // down-projection 16-byte chunks per lane per output row
-constexpr int DP_POLL_L = 2;         // 16-byte pairs of tagged logit words per thread (N * H / 256 <= 2048)
-constexpr int DP_POLL_H = 2;         // 16-byte pairs of activation words per thread (one word per wavefront, <= 2048)
+constexpr int DP_POLL_L = 4;         // tagged logit words per thread (N * H / 256 <= 2048)
+constexpr int DP_POLL_H = 4;         // activation words per thread (one word per wavefront, <= 2048)
 constexpr int DP_MAX_ITEMS = 3;      // gate/up activations per wavefront (they share one exchanged word)
 
 struct PipeArgs {
@@ -86,9 +88,9 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
     __shared__ __attribute__((aligned(16))) bf16_t hl[2][DP_MAX_KI];   // activations of two layers (bf16)
     __shared__ __attribute__((aligned(16))) bf16_t xs[4096];           // the step's input row
     __shared__ float lpart[2][128 * 16]; // partial logits of the layer being ranked (two iterations apart)
-    __shared__ int sel_e_all[DP_WAVES][DEC_RING][8];     // every wavefront ranks for itself and keeps its own copy,
-    __shared__ float sel_w_all[DP_WAVES][DEC_RING][8];   // so the selection needs no workgroup barrier
-    __shared__ int behind_lds;
+    __shared__ int sel_e[DEC_RING][8];     // selections of the last DEC_RING layers: written by the wavefront on
+    __shared__ float sel_w[DEC_RING][8];   // top-k duty, read by everyone from the next iteration on
+    __shared__ int behind_lds;           // set when a wait ran out: the workgroup returns
     __shared__ int bar_ok;
     __shared__ TraceLds ts;
 
@@ -105,8 +107,6 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
     const int dchunks = KI / 8;
     const int chunks_per_row = I / 8;
     const bool stats_wave = blockIdx.x == G - 1 && wave == DP_WAVES - 1;
-    int (*sel_e)[8] = sel_e_all[wave];
-    float (*sel_w)[8] = sel_w_all[wave];
     uint32_t bar_phase = 0;
 
     if (blockIdx.x == G - 1) {
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         DP_LDS_BARRIER();
 
         // registers that carry loads across the iteration boundary
-        u32x4_t pl[DP_POLL_L], ph[DP_POLL_H];   // two tagged words each: (value, tag, value, tag)
+        unsigned long long pl[DP_POLL_L], ph[DP_POLL_H];
         u32x4_t dv[DP_MAX_DCH];
         floatx4_t wr = {0.f, 0.f, 0.f, 0.f};
 
@@ -168,22 +168,22 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         // of layer itn.
 #define DP_ISSUE_ITER(itn)                                                                            \
     {                                                                                                 \
-        const int lG_ = (itn) - 1, lD_ = (itn) - 3;                                                   \
+        const int lT_ = (itn) - 1, lD_ = (itn) - 4;                                                   \
         int tid_ = threadIdx.x;                                                                       \
         asm volatile("" : "+v"(tid_));   /* offsets are recomputed here, not kept in registers */      \
         const int lane_ = tid_ & 63;                                                                  \
-        if (lG_ >= 0 && lG_ < L) {                                                                    \
-            const unsigned long long *src_ = a.logit_ring + (size_t)(lG_ & (DEC_RING - 1)) * n_items1; \
+        if (lT_ >= 0 && lT_ < L) {                                                                    \
+            const unsigned long long *src_ = a.logit_ring + (size_t)(lT_ & (DEC_RING - 1)) * n_items1; \
             _Pragma("unroll") for (int k = 0; k < DP_POLL_L; ++k) {                                    \
-                const int q_ = 2 * (tid_ + k * DP_THREADS);                                           \
-                if (q_ < n_items1) pl[k] = *reinterpret_cast<const u32x4_t *>(src_ + q_);             \
+                const int q_ = tid_ + k * DP_THREADS;                                                 \
+                if (q_ < n_items1) pl[k] = poll_word(src_ + q_);                                      \
             }                                                                                         \
         }                                                                                             \
         if (lD_ >= 0) {                                                                               \
             const unsigned long long *src_ = a.h_ring + (size_t)(lD_ & (DEC_RING - 1)) * a.h_slot;    \
             _Pragma("unroll") for (int k = 0; k < DP_POLL_H; ++k) {                                    \
-                const int q_ = 2 * (tid_ + k * DP_THREADS);                                           \
-                if (q_ * items_per_wave < KI) ph[k] = *reinterpret_cast<const u32x4_t *>(src_ + q_);  \
+                const int q_ = tid_ + k * DP_THREADS;                                                 \
+                if (q_ * items_per_wave < KI) ph[k] = poll_word(src_ + q_);                           \
             }                                                                                         \
         }                                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                            \
@@ -205,142 +205,70 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         DP_ISSUE_ITER(0)
 
 #pragma unroll 1
-        for (int it = 0; it < L + 3; ++it) {
-            const int lR = it, lG = it - 1, lD = it - 3;
-            const bool doR = lR < L, doG = lG >= 0 && lG < L, doD = lD >= 0;
+        for (int it = 0; it < L + 4; ++it) {
+            const int lR = it, lT = it - 1, lG = it - 2, lD = it - 4;
+            const bool doR = lR < L, doT = lT >= 0 && lT < L, doG = lG >= 0 && lG < L, doD = lD >= 0;
 
-            // ---- consume the polls: partial logits of layer lG, activations of layer lD ---------------
-            bool behind = false;
-            int tid_c = threadIdx.x;
-            asm volatile("" : "+v"(tid_c));
-            if (doG) {
-                const uint32_t tg = tag0 + (uint32_t)lG;
-                float *dst = lpart[it & 1];
-#pragma unroll
-                for (int k = 0; k < DP_POLL_L; ++k) {
-                    const int q = 2 * (tid_c + k * DP_THREADS);
-                    if (q < n_items1) {
-                        if (pl[k].y == tg && pl[k].w == tg) {
-                            dst[q] = __uint_as_float(pl[k].x);
-                            dst[q + 1] = __uint_as_float(pl[k].z);
-                        } else behind = true;
-                    }
-                }
-            }
-            if (doD) {
+            // ---- consume the polls: partial logits of layer lT, activations of layer lD.  A word whose
+            // tag is not there yet (its producer is more than a pipeline stage behind) is asked for again
+            // by the wavefront that needs it, on its own, until it arrives or the wait limit passes; the
+            // one workgroup barrier behind this block is the only synchronisation of the iteration -------
+            {
+                int tid_c = threadIdx.x;
+                asm volatile("" : "+v"(tid_c));
+                const uint32_t tg = tag0 + (uint32_t)lT;
                 const uint32_t td = tag16(tag0 + (uint32_t)lD);
-                bf16_t *dst = hl[lD & 1];
-#pragma unroll
-                for (int k = 0; k < DP_POLL_H; ++k) {
-                    const int u = 2 * (tid_c + k * DP_THREADS);         // first of two wavefront words
-                    if (u * items_per_wave < KI) {
-                        const bool two = (u + 1) * items_per_wave < KI;
-                        if ((ph[k].y >> 16) == td && (!two || (ph[k].w >> 16) == td)) {
-                            const int i0 = u * items_per_wave;
-                            dst[i0] = (bf16_t)ph[k].x;
-                            if (items_per_wave > 1 && i0 + 1 < KI) dst[i0 + 1] = (bf16_t)(ph[k].x >> 16);
-                            if (items_per_wave > 2 && i0 + 2 < KI) dst[i0 + 2] = (bf16_t)ph[k].y;
-                            if (two) {
-                                const int i1 = i0 + items_per_wave;
-                                dst[i1] = (bf16_t)ph[k].z;
-                                if (items_per_wave > 1 && i1 + 1 < KI) dst[i1 + 1] = (bf16_t)(ph[k].z >> 16);
-                                if (items_per_wave > 2 && i1 + 2 < KI) dst[i1 + 2] = (bf16_t)ph[k].w;
-                            }
-                        } else behind = true;
-                    }
-                }
-            }
-            if (__any(behind) && lane == 0) behind_lds = 1;
-            DP_LDS_BARRIER();
-            if (behind_lds) {
-                // Slow path (a producer was more than a pipeline stage late): poll again until every
-                // tag matches, with the bounded wait.
+                const unsigned long long *srcl = a.logit_ring + (size_t)(lT & (DEC_RING - 1)) * n_items1;
+                const unsigned long long *srch = a.h_ring + (size_t)(lD & (DEC_RING - 1)) * a.h_slot;
+                float *dstl = lpart[it & 1];
+                bf16_t *dsth = hl[lD & 1];
+                uint32_t missing = 0;                  // bit k: logit word k, bit 8 + k: activation word k
                 unsigned long long t0 = 0;
                 bool timing = false;
                 for (;;) {
-                    DP_LDS_BARRIER();          // everyone has read behind_lds / bar_ok of the last round
-                    uint32_t ab = 0;
-                    if (tid == 0) ab = __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    bool still = false;
-                    if (doG) {
-                        const uint32_t tg = tag0 + (uint32_t)lG;
-                        const unsigned long long *src = a.logit_ring + (size_t)(lG & (DEC_RING - 1)) * n_items1;
-                        for (int q = tid; q < n_items1; q += DP_THREADS) {
-                            const unsigned long long w = poll_word(src + q);
-                            if ((uint32_t)(w >> 32) == tg) lpart[it & 1][q] = __uint_as_float((uint32_t)w);
-                            else still = true;
+                    if (doT) {
+#pragma unroll
+                        for (int k = 0; k < DP_POLL_L; ++k) {
+                            const int q = tid_c + k * DP_THREADS;
+                            if (q < n_items1 && (!timing || (missing >> k & 1))) {
+                                if ((uint32_t)(pl[k] >> 32) == tg) { dstl[q] = __uint_as_float((uint32_t)pl[k]); missing &= ~(1u << k); }
+                                else missing |= 1u << k;
+                            }
                         }
                     }
                     if (doD) {
-                        const uint32_t td = tag16(tag0 + (uint32_t)lD);
-                        const unsigned long long *src = a.h_ring + (size_t)(lD & (DEC_RING - 1)) * a.h_slot;
-                        bf16_t *dst = hl[lD & 1];
-                        for (int u = tid; u * items_per_wave < KI; u += DP_THREADS) {
-                            const unsigned long long w = poll_word(src + u);
-                            if ((uint32_t)(w >> 48) == td) {
-                                for (int v = 0; v < items_per_wave; ++v)
-                                    if (u * items_per_wave + v < KI) dst[u * items_per_wave + v] = (bf16_t)(w >> (16 * v));
-                            } else still = true;
+#pragma unroll
+                        for (int k = 0; k < DP_POLL_H; ++k) {
+                            const int i0 = (tid_c + k * DP_THREADS) * items_per_wave;   // wavefront (tid_c + k*512)'s word
+                            if (i0 < KI && (!timing || (missing >> (8 + k) & 1))) {
+                                if ((uint32_t)(ph[k] >> 48) == td) {
+                                    dsth[i0] = (bf16_t)ph[k];
+                                    if (items_per_wave > 1 && i0 + 1 < KI) dsth[i0 + 1] = (bf16_t)(ph[k] >> 16);
+                                    if (items_per_wave > 2 && i0 + 2 < KI) dsth[i0 + 2] = (bf16_t)(ph[k] >> 32);
+                                    missing &= ~(1u << (8 + k));
+                                } else missing |= 1u << (8 + k);
+                            }
                         }
                     }
-                    if (tid == 0) {
-                        int ok = 1;
-                        if (ab) ok = 0;
-                        if (!timing) { t0 = wall_clock64(); timing = true; }
-                        else if (wall_clock64() - t0 > a.spin_limit) {
-                            __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            ok = 0;
-                        }
-                        bar_ok = ok;
-                        behind_lds = 0;
+                    if (!__any(missing != 0)) break;
+                    // ask again for what is missing (agent-scope loads), with the bounded wait
+                    if (!timing) { t0 = wall_clock64(); timing = true; }
+                    const uint32_t ab = __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (ab || wall_clock64() - t0 > a.spin_limit) {
+                        if (!ab) __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (lane == 0) behind_lds = 1;     // the workgroup leaves together behind the barrier
+                        break;
                     }
-                    DP_LDS_BARRIER();          // behind_lds cleared, bar_ok set
-                    if (__any(still) && lane == 0) behind_lds = 1;
-                    DP_LDS_BARRIER();
-                    if (!bar_ok) return;
-                    if (!behind_lds) break;
+#pragma unroll
+                    for (int k = 0; k < DP_POLL_L; ++k)
+                        if (missing >> k & 1) pl[k] = poll_word(srcl + tid_c + k * DP_THREADS);
+#pragma unroll
+                    for (int k = 0; k < DP_POLL_H; ++k)
+                        if (missing >> (8 + k) & 1) ph[k] = poll_word(srch + tid_c + k * DP_THREADS);
                 }
             }
-
-            // ---- top-k and softmax of layer lG: every wavefront for itself (same result everywhere, no
-            // barrier): K rounds of wavefront maximum, ties to the lower id -------------------------------
-            if (doG) {
-                const float NEG_INF = -__builtin_inff();
-                const float *lp = lpart[it & 1];
-                float v0 = NEG_INF, v1 = NEG_INF;
-                if (lane < N) {
-                    v0 = 0.f;
-                    for (int q = 0; q < segs; ++q) v0 += lp[lane * segs + q];
-                }
-                if (lane + 64 < N) {
-                    v1 = 0.f;
-                    for (int q = 0; q < segs; ++q) v1 += lp[(lane + 64) * segs + q];
-                }
-                float m0 = v0, m1 = v1, my_z = NEG_INF, zmax = 0.f;
-                int my_e = 0;
-                for (int j = 0; j < K; ++j) {
-                    const float m = wave_max(fmaxf(m0, m1));
-                    const unsigned long long b0 = __ballot(m0 == m), b1 = __ballot(m1 == m);
-                    const int e = b0 ? __ffsll((long long)b0) - 1 : 63 + __ffsll((long long)b1);
-                    if (j == 0) zmax = m;
-                    if (lane == j) { my_z = m; my_e = e; }
-                    if (e == lane) m0 = NEG_INF;
-                    if (e == lane + 64) m1 = NEG_INF;
-                }
-                const float den = wave_sum(((lane < N) ? expf(v0 - zmax) : 0.f) + ((lane + 64 < N) ? expf(v1 - zmax) : 0.f));
-                const float my_p = (lane < K) ? expf(my_z - zmax) : 0.f;
-                float wgt = my_p / den;
-                if (a.renorm) wgt = my_p / wave_sum(my_p);
-                if (lane < K) {
-                    sel_e[lG & (DEC_RING - 1)][lane] = my_e;
-                    sel_w[lG & (DEC_RING - 1)][lane] = wgt;
-                    if (blockIdx.x == 0 && wave == 0) {
-                        const int64_t o = ((int64_t)lG * a.steps_total + g) * K + lane;
-                        a.out_idx[o] = my_e;
-                        a.out_w[o] = wgt;
-                    }
-                }
-            }
+            DP_LDS_BARRIER();
+            if (behind_lds) return;        // the grid is aborting (set by a wavefront whose wait ran out)
 
             // ---- G(lG): request the first two activations' gate and up rows ---------------------------
             u32x4_t gA[XCH], uA[XCH], gB[XCH], uB[XCH];
@@ -374,6 +302,47 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             if (nG > 0) DP_LOAD_ITEM(gA, uA, 0)
             if (nG > 1) DP_LOAD_ITEM(gB, uB, 1)
             __builtin_amdgcn_sched_barrier(0);
+
+            // ---- T(lT): top-k and softmax of layer lT by the wavefront whose turn it is: K rounds of
+            // wavefront maximum, ties to the lower id.  The result is first needed after the next
+            // iteration's barrier, so nobody waits for it ---------------------------------------------------
+            if (doT && wave == (it & (DP_WAVES - 1))) {
+                const float NEG_INF = -__builtin_inff();
+                const float *lp = lpart[it & 1];
+                float v0 = NEG_INF, v1 = NEG_INF;
+                if (lane < N) {
+                    v0 = 0.f;
+                    for (int q = 0; q < segs; ++q) v0 += lp[lane * segs + q];
+                }
+                if (lane + 64 < N) {
+                    v1 = 0.f;
+                    for (int q = 0; q < segs; ++q) v1 += lp[(lane + 64) * segs + q];
+                }
+                float m0 = v0, m1 = v1, my_z = NEG_INF, zmax = 0.f;
+                int my_e = 0;
+                for (int j = 0; j < K; ++j) {
+                    const float m = wave_max(fmaxf(m0, m1));
+                    const unsigned long long b0 = __ballot(m0 == m), b1 = __ballot(m1 == m);
+                    const int e = b0 ? __ffsll((long long)b0) - 1 : 63 + __ffsll((long long)b1);
+                    if (j == 0) zmax = m;
+                    if (lane == j) { my_z = m; my_e = e; }
+                    if (e == lane) m0 = NEG_INF;
+                    if (e == lane + 64) m1 = NEG_INF;
+                }
+                const float den = wave_sum(((lane < N) ? expf(v0 - zmax) : 0.f) + ((lane + 64 < N) ? expf(v1 - zmax) : 0.f));
+                const float my_p = (lane < K) ? expf(my_z - zmax) : 0.f;
+                float wgt = my_p / den;
+                if (a.renorm) wgt = my_p / wave_sum(my_p);
+                if (lane < K) {
+                    sel_e[lT & (DEC_RING - 1)][lane] = my_e;
+                    sel_w[lT & (DEC_RING - 1)][lane] = wgt;
+                    if (blockIdx.x == 0) {
+                        const int64_t o = ((int64_t)lT * a.steps_total + g) * K + lane;
+                        a.out_idx[o] = my_e;
+                        a.out_w[o] = wgt;
+                    }
+                }
+            }
 
             // ---- R(lR): this wavefront's router segment(s) -> tagged partial logits ---------------------
             if (doR) {
@@ -437,7 +406,7 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             // memory pipe never runs dry between iterations ----------------------------------------------
             if (nG > 1) { DP_REDUCE_ITEM(gA, uA, 0) if (nG > 2) DP_LOAD_ITEM(gA, uA, 2) }
             if (nG > 2) { DP_REDUCE_ITEM(gB, uB, 1) }
-            if (it + 1 < L + 3) { DP_ISSUE_ITER(it + 1) }
+            if (it + 1 < L + 4) { DP_ISSUE_ITER(it + 1) }
             if (nG > 0) {
                 if ((nG - 1) & 1) { DP_REDUCE_ITEM(gB, uB, nG - 1) } else { DP_REDUCE_ITEM(gA, uA, nG - 1) }
                 if (lane == 0)
@@ -497,8 +466,8 @@ remoe_status launch_decode_pipelined(const DecodeLaunch &d, hipStream_t stream)
     const int W = G * DP_WAVES;
     const DecodeWsLayout wl0 = decode_ws_layout(d.H, d.N, d.I, d.K);
     if (G > DEC_MAX_GRID) return fail(REMOE_E_UNSUPPORTED, "decode: %d compute units exceed the barrier's %d flags", G, DEC_MAX_GRID);
-    if (W > 2 * DP_POLL_H * DP_THREADS || W > wl0.n_h)
-        return fail(REMOE_E_UNSUPPORTED, "decode: %d wavefronts exceed the %d exchange words a workgroup polls", W, 2 * DP_POLL_H * DP_THREADS);
+    if (W > DP_POLL_H * DP_THREADS || W > wl0.n_h)
+        return fail(REMOE_E_UNSUPPORTED, "decode: %d wavefronts exceed the %d exchange words a workgroup polls", W, DP_POLL_H * DP_THREADS);
     if ((d.K * d.I + W - 1) / W > DP_MAX_ITEMS)
         return fail(REMOE_E_UNSUPPORTED, "decode: top_k * inter = %d needs more than %d activations per wavefront on %d compute units",
                     d.K * d.I, DP_MAX_ITEMS, G);
