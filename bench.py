@@ -53,6 +53,28 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+def counter_traffic(kernel, field):
+    """HBM bytes from the hardware-counter runs recorded in profiles/hbm_traffic.txt, or None when
+    there is no record or the kernel's source has changed since the counters were taken."""
+    import hashlib
+
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if not parts or parts[0] != kernel:
+            continue
+        kv = dict(p.split("=", 1) for p in parts[1:])
+        src = os.path.join(ROOT, kv.get("source", ""))
+        if field not in kv or not os.path.isfile(src):
+            return None
+        if hashlib.sha256(open(src, "rb").read()).hexdigest() != kv.get("sha256"):
+            return None
+        return int(kv[field])
+    return None
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -165,7 +187,12 @@ def main():
         peak = BF16_MFMA_PEAK_TFLOPS if cfg.dtype == "bf16" else F32_VECTOR_PEAK_TFLOPS
         roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": "grouped_gemm (gate/up + SwiGLU)",
                     "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 4),
-                    "traffic": None, "avg_launch_ms": round(dom["ms_avg"], 4), "launches": dom["launches"]}
+                    "traffic": (counter_traffic("gate_up", "bytes_per_launch")
+                                if (cfg.name == "qwen3_prefill" and cfg.dtype == "bf16") else None),
+                    "traffic_unit": "HBM-side bytes per launch (L2 misses; FETCH_SIZE + WRITE_SIZE scaled by a copy of "
+                                    "known size), against %d algorithmic" % int(T * H * 2 + 2 * N * cfg.inter * H * 2
+                                                                                + T * K * cfg.inter * 2),
+                    "avg_launch_ms": round(dom["ms_avg"], 4), "launches": dom["launches"]}
 
     eor = float(ov_sum.sum()) / (K * (Ts - 1) * n_tr) if Ts > 1 else float("nan")
     total_miss = int(miss_tot.sum())

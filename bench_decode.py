@@ -86,6 +86,8 @@ def run_decode(args, cfg):
         return 4
 
     tokens_per_s = steps / elapsed
+    from bench import counter_traffic
+    per_ls = counter_traffic("decode_pipelined", "bytes_per_layer_step") if order == remoe.REMOE_DECODE_PIPELINED else None
     bytes_step = cfg.decode_bytes_per_layer_step * L           # algorithmic bytes of one step
     ach = bytes_step * steps / (ms_kernel * 1e-3) / 1e9         # GB/s over the kernel's own time
     done_steps = warmup + steps
@@ -99,9 +101,12 @@ def run_decode(args, cfg):
                    "inter": I, "top_k": K, "rho": rho, "lru_capacities": caps, "seed": cfg.seed,
                    "steps_per_launch": chunk,
                    "layer_order": "chained" if order == remoe.REMOE_DECODE_CHAINED else "pipelined"},
-        "roofline": {"bound": "hbm", "kernel": "decode_kernel (router + K experts gather-GEMV)",
+        "roofline": {"bound": "hbm", "kernel": ("decode_kernel" if order == remoe.REMOE_DECODE_CHAINED else "decode_pipe_kernel") + " (router + K experts gather-GEMV)",
                      "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(ach / HBM_PEAK_GBS, 4),
+                     "traffic": (None if per_ls is None else per_ls * L * chunk),
+                     "traffic_unit": "HBM bytes per launch of %d steps (FETCH_SIZE + WRITE_SIZE scaled by a copy of known "
+                                     "size), against %d algorithmic" % (chunk, bytes_step * chunk),
                      "avg_launch_ms": round(ms_kernel / max(launches, 1), 4), "launches": launches,
                      "bytes_per_step": bytes_step, "us_per_layer_step": round(ms_kernel * 1e3 / (steps * L), 3)},
         "trace": {"eor": round(eor, 5),
