@@ -43,6 +43,13 @@ def lib() -> ctypes.CDLL:
         _lib.oracle_lru_list.restype = _c_int
         _lib.oracle_lru_list.argtypes = [_c_ptr, _c_i64, _c_i64, _c_int, _c_int, _c_int, ctypes.c_uint64,
                                          _c_ptr, _c_ptr, _c_ptr]
+        _lib.oracle_cache_policy.restype = _c_int
+        _lib.oracle_cache_policy.argtypes = [_c_ptr, _c_i64, _c_i64, _c_int, _c_int, _c_int, _c_int, ctypes.c_uint64,
+                                             _c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_ptr]
+        _lib.oracle_step_summary.restype = _c_int
+        _lib.oracle_step_summary.argtypes = [_c_ptr, _c_i64, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_i64, _c_ptr]
+        _lib.oracle_balance.restype = _c_int
+        _lib.oracle_balance.argtypes = [_c_ptr, _c_i64, _c_i64, _c_int, _c_int, _c_ptr, _c_ptr, _c_ptr, _c_ptr]
     return _lib
 
 
@@ -179,3 +186,49 @@ def lru_list(idx: torch.Tensor, n_experts: int, capacity: int, expert_bytes: int
     if rc != 0:
         raise RuntimeError(f"oracle_lru_list failed ({rc})")
     return miss, tot, nbytes
+
+
+POLICIES = {"lru": 0, "fifo": 1, "lfu": 2, "belady": 3}
+
+
+def cache_policy(idx: torch.Tensor, n_experts: int, capacity: int, policy: str, expert_bytes: int = 0):
+    """Expert cache of one replacement policy per trace (App. E.2; Belady: App. F.1).  idx [S, T, K] int32.
+    Returns dict: miss, uniq, hit_tok uint8 [S, T]; total_miss, total_uniq, bytes int64 [S]."""
+    idx = _chk(idx, torch.int32)
+    S, T, K = idx.shape
+    out = {k: torch.zeros(S, T, dtype=torch.uint8) for k in ("miss", "uniq", "hit_tok")}
+    out.update({k: torch.zeros(S, dtype=torch.int64) for k in ("total_miss", "total_uniq", "bytes")})
+    rc = lib().oracle_cache_policy(_p(idx), S, T, K, n_experts, capacity, POLICIES[policy], expert_bytes,
+                                   _p(out["miss"]), _p(out["uniq"]), _p(out["hit_tok"]), _p(out["total_miss"]),
+                                   _p(out["total_uniq"]), _p(out["bytes"]))
+    if rc != 0:
+        raise ValueError(f"oracle_cache_policy failed ({rc})")
+    return out
+
+
+def step_summary(miss: torch.Tensor, hist_len: int):
+    """Per-step sums over layers and their P50/P95/P99 (App. E.2).  miss uint8 [L, S, T].
+    Returns (all uint16-valued int32 [S, T], hist int64 [hist_len], pct int32 [3])."""
+    miss = _chk(miss, torch.uint8)
+    L, S, T = miss.shape
+    allm = torch.zeros(S, T, dtype=torch.int16)
+    hist = torch.zeros(hist_len, dtype=torch.int64)
+    pct = torch.zeros(3, dtype=torch.int32)
+    rc = lib().oracle_step_summary(_p(miss), L, S, T, _p(allm), _p(hist), hist_len, _p(pct))
+    if rc != 0:
+        raise ValueError(f"oracle_step_summary failed ({rc})")
+    return allm.to(torch.int32) & 0xFFFF, hist, pct
+
+
+def balance(idx: torch.Tensor, n_experts: int):
+    """Expert-load balance per trace: load int64 [S, N], used int32 [S], entropy, cv fp64 [S]."""
+    idx = _chk(idx, torch.int32)
+    S, T, K = idx.shape
+    load = torch.zeros(S, n_experts, dtype=torch.int32)
+    used = torch.zeros(S, dtype=torch.int32)
+    ent = torch.zeros(S, dtype=torch.float64)
+    cv = torch.zeros(S, dtype=torch.float64)
+    rc = lib().oracle_balance(_p(idx), S, T, K, n_experts, _p(load), _p(used), _p(ent), _p(cv))
+    if rc != 0:
+        raise ValueError(f"oracle_balance failed ({rc})")
+    return load.to(torch.int64), used, ent, cv

@@ -1,0 +1,200 @@
+"""Pins of the cache-policy, step-summary and balance oracles (CPU only).
+
+Each pin fixes the oracle to something other than itself: textbook single-request simulations
+written here with Python containers, the list LRU of the first oracle file, exhaustive search for
+the least possible number of misses, the paper's own table, numpy's percentile, closed forms.
+"""
+import collections
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _trace(seed, S, T, K, N, distinct=True):
+    g = torch.Generator().manual_seed(seed)
+    if distinct:
+        rows = [torch.randperm(N, generator=g)[:K] for _ in range(S * T)]
+        return torch.stack(rows).reshape(S, T, K).to(torch.int32)
+    return torch.randint(0, N, (S, T, K), generator=g, dtype=torch.int32)
+
+
+# ---- LRU through the generic rule == the list form of the first file ---------------------------
+@pytest.mark.parametrize("K,N,C", [(1, 6, 3), (2, 9, 4), (4, 16, 4), (6, 20, 3), (3, 8, 8)])
+def test_lru_policy_equals_list_lru(K, N, C):
+    idx = _trace(K * 100 + C, 3, 60, K, N, distinct=(K > 1))
+    a = oracle.cache_policy(idx, N, C, "lru", 7)
+    miss, tot, nbytes = oracle.lru_list(idx, N, C, 7)
+    assert torch.equal(a["miss"], miss) and torch.equal(a["total_miss"], tot) and torch.equal(a["bytes"], nbytes)
+
+
+# ---- FIFO / LFU at one request per step == the textbook algorithms ------------------------------
+def _textbook_fifo(seq, C):
+    q, miss = collections.deque(), []
+    for e in seq:
+        if e in q:
+            miss.append(0)
+            continue
+        miss.append(1)
+        q.append(e)
+        if len(q) > C:
+            q.popleft()
+    return miss
+
+
+def _textbook_lfu(seq, C):
+    """LFU with request counts kept for the whole sequence, least-recently-used among equals."""
+    cache, freq, last, miss = set(), collections.Counter(), {}, []
+    for t, e in enumerate(seq):
+        miss.append(0 if e in cache else 1)
+        freq[e] += 1
+        last[e] = t
+        cache.add(e)
+        if len(cache) > C:
+            cache.remove(min(cache, key=lambda x: (freq[x], last[x], x)))
+    return miss
+
+
+@pytest.mark.parametrize("N,C", [(5, 2), (8, 3), (12, 5)])
+def test_fifo_lfu_single_request_match_textbook(N, C):
+    idx = _trace(N + C, 4, 200, 1, N, distinct=False)
+    fifo = oracle.cache_policy(idx, N, C, "fifo")
+    lfu = oracle.cache_policy(idx, N, C, "lfu")
+    for s in range(idx.shape[0]):
+        seq = idx[s, :, 0].tolist()
+        assert fifo["miss"][s].tolist() == _textbook_fifo(seq, C)
+        assert lfu["miss"][s].tolist() == _textbook_lfu(seq, C)
+
+
+def test_fifo_hit_does_not_renew():
+    # C = 2: 0, 1, then 0 again (hit), then 2 evicts 0 (the oldest arrival) under FIFO but 1 under LRU
+    idx = torch.tensor([[[0], [1], [0], [2], [0], [1]]], dtype=torch.int32)
+    assert oracle.cache_policy(idx, 3, 2, "fifo")["miss"][0].tolist() == [1, 1, 0, 1, 1, 1]
+    assert oracle.cache_policy(idx, 3, 2, "lru")["miss"][0].tolist() == [1, 1, 0, 1, 0, 1]
+
+
+# ---- Belady == the least number of misses any replacement choice can reach ----------------------
+def _least_misses(steps, C):
+    """Exhaustive search: after every step keep any subset (of size <= C) of resident | requested."""
+    best = {frozenset(): 0}
+    for req in steps:
+        nxt = {}
+        for res, m in best.items():
+            m2 = m + len(req - res)
+            cand = res | req
+            keeps = [cand] if len(cand) <= C else [frozenset(c) for c in itertools.combinations(cand, C)]
+            for k in keeps:
+                if k not in nxt or nxt[k] > m2:
+                    nxt[k] = m2
+        best = nxt
+    return min(best.values())
+
+
+@pytest.mark.parametrize("seed,K,N,C,T", [(1, 1, 4, 2, 10), (2, 2, 5, 2, 8), (3, 2, 5, 3, 9), (4, 3, 6, 3, 7),
+                                          (5, 2, 6, 4, 9), (6, 1, 5, 3, 12)])
+def test_belady_is_optimal_on_tiny_traces(seed, K, N, C, T):
+    idx = _trace(seed, 6, T, K, N, distinct=(K > 1))
+    got = oracle.cache_policy(idx, N, C, "belady")["total_miss"].tolist()
+    for s in range(idx.shape[0]):
+        steps = [frozenset(idx[s, t].tolist()) for t in range(T)]
+        assert got[s] == _least_misses(steps, C)
+
+
+@pytest.mark.parametrize("K,N,C", [(2, 16, 4), (6, 64, 12), (8, 128, 32), (4, 60, 12)])
+def test_belady_never_worse_and_all_bounded(K, N, C):
+    idx = _trace(K + N, 4, 300, K, N)
+    tot = {p: oracle.cache_policy(idx, N, C, p)["total_miss"] for p in oracle.POLICIES}
+    for p in ("lru", "fifo", "lfu"):
+        assert (tot["belady"] <= tot[p]).all()
+    # every policy pays at least the compulsory (first-use) misses and at most K per step
+    for s in range(idx.shape[0]):
+        first_use = len(set(idx[s].reshape(-1).tolist()))
+        for p in oracle.POLICIES:
+            assert first_use <= int(tot[p][s]) <= 300 * K
+
+
+# ---- accounting (App. E.2): hits + misses = requests; token hits; capacity >= N_r ---------------
+@pytest.mark.parametrize("policy", list(oracle.POLICIES))
+def test_accounting_identities(policy):
+    idx = _trace(11, 3, 80, 4, 12, distinct=False)          # repeated ids inside a step allowed
+    o = oracle.cache_policy(idx, 12, 5, policy, 1000)
+    assert torch.equal(o["total_miss"], o["miss"].sum(1)) and torch.equal(o["total_uniq"], o["uniq"].sum(1))
+    assert torch.equal(o["bytes"], o["total_miss"] * 1000)
+    assert (o["miss"] <= o["uniq"]).all() and (o["uniq"] <= 4).all() and (o["hit_tok"] <= 4).all()
+    # with distinct ids in every step, token hits are exactly the unique hits
+    idx2 = _trace(12, 3, 80, 4, 12, distinct=True)
+    o2 = oracle.cache_policy(idx2, 12, 5, policy)
+    assert torch.equal(o2["hit_tok"], o2["uniq"] - o2["miss"])
+    # a cache that holds every expert only pays first uses
+    o3 = oracle.cache_policy(idx2, 12, 12, policy)
+    for s in range(3):
+        assert int(o3["total_miss"][s]) == len(set(idx2[s].reshape(-1).tolist()))
+    # cold start: the first step misses all of its distinct experts
+    assert torch.equal(o["miss"][:, 0], o["uniq"][:, 0])
+
+
+def test_paper_full_cache_table_identity():
+    """#uMiss = (1 - uHR) * (prompts * steps * layers * K) for the LFU / FIFO rows as well, and Belady's
+    counts lie below the LRU counts of the same capacity (App. F.1)."""
+    requests = 128 * 64 * 26 * 6
+    lru = {4: (1.0150, 0.9746), 6: (0.8707, 0.8068)}
+    with open(os.path.join(HERE, "golden", "paper_cache_policies.txt")) as f:
+        rows = [l.split() for l in f if l.strip() and not l.startswith("#")]
+    seen = 0
+    for r in rows:
+        if r[0] in ("LFU", "FIFO", "LRU"):
+            for uhr, um in ((float(r[2]), float(r[4])), (float(r[3]), float(r[5]))):
+                assert abs((1.0 - uhr) * requests / 1e6 - um) < 6e-5 * requests / 1e6 + 5e-5
+            seen += 1
+        else:
+            c = int(r[1])
+            assert int(r[2]) < lru[c][0] * 1e6 and int(r[3]) < lru[c][1] * 1e6
+            seen += 1
+    assert seen == 5
+
+
+# ---- per-step sums over layers and percentiles ------------------------------------------------------
+@pytest.mark.parametrize("L,S,T", [(3, 2, 50), (26, 4, 64), (1, 1, 7)])
+def test_step_summary_matches_numpy(L, S, T):
+    g = torch.Generator().manual_seed(L * S)
+    miss = torch.randint(0, 7, (L, S, T), generator=g, dtype=torch.uint8)
+    allm, hist, pct = oracle.step_summary(miss, L * 6 + 1)
+    ref = miss.to(torch.int64).sum(0)
+    assert torch.equal(allm.to(torch.int64), ref)
+    assert torch.equal(hist, torch.bincount(ref.reshape(-1), minlength=L * 6 + 1))
+    want = [int(np.percentile(ref.numpy().reshape(-1), p, method="inverted_cdf")) for p in (50, 95, 99)]
+    assert pct.tolist() == want
+
+
+# ---- balance: closed forms ----------------------------------------------------------------------
+def test_balance_closed_forms():
+    N = 8
+    even = torch.arange(N, dtype=torch.int32).repeat(5).reshape(1, 20, 2)       # every expert 5 times
+    load, used, ent, cv = oracle.balance(even, N)
+    assert load[0].tolist() == [5] * N and int(used[0]) == N
+    assert abs(float(ent[0]) - 1.0) < 1e-15 and abs(float(cv[0])) < 1e-15
+    one = torch.full((1, 10, 1), 3, dtype=torch.int32)                           # one expert only
+    load, used, ent, cv = oracle.balance(one, N)
+    assert int(used[0]) == 1 and float(ent[0]) == 0.0
+    assert abs(float(cv[0]) - math.sqrt(N - 1)) < 1e-14                         # std / mean of a one-hot load
+    two = torch.tensor([[[0, 1]] * 6], dtype=torch.int32)                        # two experts, evenly
+    _, used, ent, cv = oracle.balance(two, 4)
+    assert int(used[0]) == 2 and abs(float(ent[0]) - 0.5) < 1e-15 and abs(float(cv[0]) - 1.0) < 1e-15
+
+
+def test_balance_matches_numpy():
+    idx = _trace(5, 3, 100, 4, 20)
+    load, used, ent, cv = oracle.balance(idx, 20)
+    for s in range(3):
+        c = np.bincount(idx[s].reshape(-1).numpy(), minlength=20).astype(np.float64)
+        p = c[c > 0] / c.sum()
+        assert load[s].tolist() == c.astype(int).tolist() and int(used[s]) == int((c > 0).sum())
+        assert abs(float(ent[s]) - float(-(p * np.log(p)).sum() / np.log(20))) < 1e-14
+        assert abs(float(cv[s]) - float(c.std() / c.mean())) < 1e-14
