@@ -76,7 +76,8 @@ typedef enum {
     REMOE_PROF_TRACE_REUSE = 7,    /* adjacent-step overlap                          */
     REMOE_PROF_LRU = 8,            /* LRU cache misses                               */
     REMOE_PROF_DECODE = 9,         /* M = 1 decode kernel                            */
-    REMOE_PROF_KINDS = 10
+    REMOE_PROF_CACHE = 10,         /* cache_simulate (FIFO / LFU / Belady / LRU walk) */
+    REMOE_PROF_KINDS = 11
 } remoe_prof_kind;
 remoe_status remoe_profile_enable(int32_t on);
 remoe_status remoe_profile_read(int32_t kind, double *total_ms, int64_t *launches, int32_t reset);
@@ -242,6 +243,71 @@ remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers,
                         uint64_t *sum_overlap, uint64_t *total_miss, uint64_t *bytes_fetched,
                         void *workspace, size_t workspace_bytes, uint64_t spin_limit_us,
                         int32_t layer_order, void *stream);
+
+/*
+ * cache_simulate -- the paper's expert-cache simulator for the replacement policies it reports
+ * besides LRU (App. E.2 "Cache state": LRU / LFU / FIFO; App. F.1: Belady's MIN under the same
+ * per-request resets).  One cold cache of `capacity` experts per trace.  Per step, against the
+ * resident set BEFORE the step (App. E.2, "Per-step hits and misses"):
+ *
+ *   out_miss[s, t]    = |U_t \ C_t|   unique misses           out_uniq[s, t] = |U_t|
+ *   out_hit_tok[s, t] = number of routed slots (with multiplicity) whose expert is resident
+ *   out_total_miss[s] = sum_t out_miss   (#uMiss)      out_total_uniq[s] = sum_t out_uniq
+ *   out_bytes[s]      = out_total_miss[s] * expert_bytes       (uHR = 1 - total_miss / total_uniq)
+ *
+ * After the step every requested expert is held; while more than `capacity` are held, the one its
+ * policy ranks last is dropped (the paper names the policies only; these are the rules taken):
+ *   REMOE_CACHE_LRU     least recently used; inside one step the higher id counts as later
+ *   REMOE_CACHE_FIFO    earliest fetched (a hit does not renew); inside one step the higher id is later
+ *   REMOE_CACHE_LFU     fewest requesting steps so far in the trace (kept across evictions), then
+ *                       least recently used
+ *   REMOE_CACHE_BELADY  next request farthest ahead (never again = farthest), then the higher id;
+ *                       needs a workspace of remoe_cache_workspace_bytes() for the next-request table
+ *
+ *   idx [S, T, K] int32; n_experts <= 128, top_k <= 64, capacity >= 1, n_steps < 2^24.
+ *   All pointers are device pointers; workspace may be NULL when no bytes are needed.
+ */
+typedef enum { REMOE_CACHE_LRU = 0, REMOE_CACHE_FIFO = 1, REMOE_CACHE_LFU = 2, REMOE_CACHE_BELADY = 3 } remoe_cache_policy;
+
+size_t remoe_cache_workspace_bytes(int64_t n_seq, int64_t n_steps, int32_t top_k, int32_t policy);
+remoe_status cache_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps, int32_t top_k,
+                            int32_t n_experts, int32_t capacity, int32_t policy, uint64_t expert_bytes,
+                            uint8_t *out_miss, uint8_t *out_uniq, uint8_t *out_hit_tok,
+                            uint64_t *out_total_miss, uint64_t *out_total_uniq, uint64_t *out_bytes,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * step_miss_summary -- per-step aggregates across all MoE layers and their percentiles (App. E.2,
+ * "Per-step (edge) reporting"):
+ *
+ *   out_all[s, t] = sum over layers l of miss[l, s, t]                (#uMiss^(all)_{s,t})
+ *   out_hist[v]   = number of steps (s, t) with out_all = v; sums >= hist_len share the last bin
+ *   out_pct[0..2] = P50, P95, P99 of out_all over all steps: the smallest value whose cumulative
+ *                   count reaches that percentage of the steps (-1 when there are no steps)
+ *
+ *   miss [L, S, T] uint8 (e.g. out_miss of lru_simulate / cache_simulate for every layer);
+ *   out_all [S, T] uint16; out_hist [hist_len] uint64, 1 <= hist_len <= 4097; out_pct [3] int32.
+ */
+remoe_status step_miss_summary(const uint8_t *miss, int64_t n_layers, int64_t n_seq, int64_t n_steps,
+                               uint16_t *out_all, uint64_t *out_hist, int64_t hist_len,
+                               int32_t *out_pct, void *stream);
+
+/*
+ * routing_balance -- how evenly a trace spreads its routed slots over the experts (the routing
+ * entropy, load variation and experts used that Sec. 5.2 tracks; the paper does not spell the
+ * formulas out, these are the ones taken).  With load[e] = number of slots (t, j) that name expert
+ * e and p_e = load[e] / (T K):
+ *
+ *   out_entropy[s] = -sum_e p_e ln p_e / ln N_r      (1 = even, 0 = a single expert; 0 if N_r = 1)
+ *   out_cv[s]      = sqrt(mean_e (load[e] - m)^2) / m,  m = T K / N_r     (population form)
+ *   out_used[s]    = number of experts with load > 0
+ *
+ *   idx [S, T, K] int32; out_load [S, N_r] uint32; out_used [S] int32; out_entropy, out_cv [S]
+ *   double (computed in fp64).  n_experts <= 128.  Empty traces give 0, 0, 0.
+ */
+remoe_status routing_balance(const int32_t *idx, int64_t n_seq, int64_t n_steps, int32_t top_k,
+                             int32_t n_experts, uint32_t *out_load, int32_t *out_used,
+                             double *out_entropy, double *out_cv, void *stream);
 
 #ifdef __cplusplus
 }

@@ -152,9 +152,9 @@ int oracle_step_summary(const uint8_t *miss, int64_t n_layers, int64_t n_seq, in
     for (int64_t i = 0; i < n; ++i) {
         uint32_t a = 0;
         for (int64_t l = 0; l < n_layers; ++l) a += miss[l * n + i];
-        if ((int64_t)a >= hist_len || a > 65535u) return -2;
+        if (a > 65535u) return -2;
         out_all[i] = (uint16_t)a;
-        out_hist[a] += 1;
+        out_hist[(int64_t)a < hist_len ? (int64_t)a : hist_len - 1] += 1;   /* sums beyond the table share its last bin */
     }
     const int pcts[3] = {50, 95, 99};
     for (int k = 0; k < 3; ++k) {

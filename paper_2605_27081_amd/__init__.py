@@ -6,6 +6,14 @@ loudly when the library has not been built.
 """
 from .binding import (  # noqa: F401
     LayerDesc,
+    REMOE_CACHE_BELADY,
+    REMOE_CACHE_FIFO,
+    REMOE_CACHE_LFU,
+    REMOE_CACHE_LRU,
+    cache_simulate,
+    remoe_cache_workspace_bytes,
+    routing_balance,
+    step_miss_summary,
     REMOE_DECODE_CHAINED,
     REMOE_DECODE_PIPELINED,
     RemoeError,

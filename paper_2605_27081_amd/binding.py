@@ -16,6 +16,7 @@ _lib: Optional[ctypes.CDLL] = None
 
 REMOE_F32, REMOE_BF16 = 0, 1
 REMOE_DECODE_CHAINED, REMOE_DECODE_PIPELINED = 0, 1
+REMOE_CACHE_LRU, REMOE_CACHE_FIFO, REMOE_CACHE_LFU, REMOE_CACHE_BELADY = 0, 1, 2, 3
 
 
 class RemoeError(RuntimeError):
@@ -77,6 +78,14 @@ def load_library() -> ctypes.CDLL:
     lib.remoe_profile_enable.argtypes = [I32]
     lib.remoe_profile_read.restype = ctypes.c_int
     lib.remoe_profile_read.argtypes = [I32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(I64), I32]
+    lib.remoe_cache_workspace_bytes.restype = SZ
+    lib.remoe_cache_workspace_bytes.argtypes = [I64, I64, I32, I32]
+    lib.cache_simulate.restype = ctypes.c_int
+    lib.cache_simulate.argtypes = [P, I64, I64, I32, I32, I32, I32, U64, P, P, P, P, P, P, P, SZ, P]
+    lib.step_miss_summary.restype = ctypes.c_int
+    lib.step_miss_summary.argtypes = [P, I64, I64, I64, P, P, I64, P, P]
+    lib.routing_balance.restype = ctypes.c_int
+    lib.routing_balance.argtypes = [P, I64, I64, I32, I32, P, P, P, P, P]
     _lib = lib
     return lib
 
@@ -109,7 +118,7 @@ def remoe_last_error() -> str:
 
 
 PROF_KINDS = ("route", "permute", "gate_up", "down", "shared_gate_up", "shared_down", "combine",
-              "trace_reuse", "lru", "decode")
+              "trace_reuse", "lru", "decode", "cache")
 
 
 def remoe_profile_enable(on: bool) -> None:
@@ -195,3 +204,32 @@ def moe_decode(desc: LayerDesc, layer_weights: torch.Tensor, x: torch.Tensor, st
                                      _ptr(sum_overlap), _ptr(total_miss), _ptr(bytes_fetched), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), spin_limit_us, layer_order,
                                      _stream()))
+
+
+def remoe_cache_workspace_bytes(n_seq: int, n_steps: int, top_k: int, policy: int) -> int:
+    return int(load_library().remoe_cache_workspace_bytes(n_seq, n_steps, top_k, policy))
+
+
+def cache_simulate(idx: torch.Tensor, n_experts: int, capacity: int, policy: int, expert_bytes: int,
+                   out_miss: torch.Tensor, out_uniq: torch.Tensor, out_hit_tok: torch.Tensor,
+                   out_total_miss: torch.Tensor, out_total_uniq: torch.Tensor, out_bytes: torch.Tensor,
+                   workspace: Optional[torch.Tensor] = None) -> None:
+    n_seq, n_steps, top_k = idx.shape
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().cache_simulate(_ptr(idx), n_seq, n_steps, top_k, n_experts, capacity, policy, expert_bytes,
+                                         _ptr(out_miss), _ptr(out_uniq), _ptr(out_hit_tok), _ptr(out_total_miss),
+                                         _ptr(out_total_uniq), _ptr(out_bytes), _ptr(workspace), ws_bytes, _stream()))
+
+
+def step_miss_summary(miss: torch.Tensor, out_all: torch.Tensor, out_hist: torch.Tensor, out_pct: torch.Tensor) -> None:
+    """miss uint8 [L, S, T]; out_all int16 [S, T] (holds uint16); out_hist int64 [hist_len]; out_pct int32 [3]."""
+    n_layers, n_seq, n_steps = miss.shape
+    _check(load_library().step_miss_summary(_ptr(miss), n_layers, n_seq, n_steps, _ptr(out_all), _ptr(out_hist),
+                                            out_hist.numel(), _ptr(out_pct), _stream()))
+
+
+def routing_balance(idx: torch.Tensor, n_experts: int, out_load: torch.Tensor, out_used: torch.Tensor,
+                    out_entropy: torch.Tensor, out_cv: torch.Tensor) -> None:
+    n_seq, n_steps, top_k = idx.shape
+    _check(load_library().routing_balance(_ptr(idx), n_seq, n_steps, top_k, n_experts, _ptr(out_load), _ptr(out_used),
+                                          _ptr(out_entropy), _ptr(out_cv), _stream()))

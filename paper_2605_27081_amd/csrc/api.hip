@@ -440,5 +440,60 @@ remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers, const vo
                                                  : launch_decode(d, static_cast<hipStream_t>(stream));
 }
 
+size_t remoe_cache_workspace_bytes(int64_t n_seq, int64_t n_steps, int32_t top_k, int32_t policy)
+{
+    if (n_seq < 0 || n_steps < 0 || top_k < 1) return 0;
+    return cache_workspace_bytes(n_seq, n_steps, top_k, policy);
+}
+
+remoe_status cache_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps, int32_t top_k, int32_t n_experts,
+                            int32_t capacity, int32_t policy, uint64_t expert_bytes, uint8_t *out_miss,
+                            uint8_t *out_uniq, uint8_t *out_hit_tok, uint64_t *out_total_miss,
+                            uint64_t *out_total_uniq, uint64_t *out_bytes, void *workspace, size_t workspace_bytes,
+                            void *stream)
+{
+    if (capacity < 1) return fail(REMOE_E_INVALID_ARG, "capacity %d must be at least 1", capacity);
+    if (policy < REMOE_CACHE_LRU || policy > REMOE_CACHE_BELADY)
+        return fail(REMOE_E_INVALID_ARG, "unknown cache policy %d", policy);
+    if (n_steps >= (1 << 24)) return fail(REMOE_E_INVALID_ARG, "n_steps %lld must stay below 2^24", (long long)n_steps);
+    remoe_status st = validate_trace(idx, n_seq, n_steps, top_k, n_experts);
+    if (st != REMOE_OK) return st;
+    if (n_seq == 0) return REMOE_OK;
+    if (!out_total_miss || !out_total_uniq || !out_bytes || (n_steps > 0 && (!out_miss || !out_uniq || !out_hit_tok)))
+        return fail(REMOE_E_INVALID_ARG, "an output pointer is NULL");
+    const size_t need = cache_workspace_bytes(n_seq, n_steps, top_k, policy);
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15)))
+        return fail(REMOE_E_WORKSPACE, "cache_simulate needs a 16-byte aligned workspace of %zu bytes for this policy", need);
+    ProfScope prof(REMOE_PROF_CACHE, static_cast<hipStream_t>(stream));
+    return launch_cache_policy(idx, n_seq, n_steps, top_k, n_experts, capacity, policy, expert_bytes, out_miss, out_uniq,
+                               out_hit_tok, out_total_miss, out_total_uniq, out_bytes, workspace,
+                               static_cast<hipStream_t>(stream));
+}
+
+remoe_status step_miss_summary(const uint8_t *miss, int64_t n_layers, int64_t n_seq, int64_t n_steps,
+                               uint16_t *out_all, uint64_t *out_hist, int64_t hist_len, int32_t *out_pct, void *stream)
+{
+    if (n_layers < 0 || n_seq < 0 || n_steps < 0) return fail(REMOE_E_INVALID_ARG, "negative dimensions");
+    if (n_layers > 257) return fail(REMOE_E_INVALID_ARG, "n_layers %lld: sums of uint8 over more than 257 layers do not fit uint16", (long long)n_layers);
+    if (hist_len < 1 || hist_len > step_summary_max_hist())
+        return fail(REMOE_E_INVALID_ARG, "hist_len %lld outside 1..%d", (long long)hist_len, step_summary_max_hist());
+    if (!out_hist || !out_pct) return fail(REMOE_E_INVALID_ARG, "out_hist and out_pct must not be NULL");
+    if (n_seq * n_steps > 0 && ((n_layers > 0 && !miss) || !out_all))
+        return fail(REMOE_E_INVALID_ARG, "miss and out_all must not be NULL");
+    return launch_step_summary(miss, n_layers, n_seq, n_steps, out_all, out_hist, (int)hist_len, out_pct,
+                               static_cast<hipStream_t>(stream));
+}
+
+remoe_status routing_balance(const int32_t *idx, int64_t n_seq, int64_t n_steps, int32_t top_k, int32_t n_experts,
+                             uint32_t *out_load, int32_t *out_used, double *out_entropy, double *out_cv, void *stream)
+{
+    remoe_status st = validate_trace(idx, n_seq, n_steps, top_k, n_experts);
+    if (st != REMOE_OK) return st;
+    if (n_seq == 0) return REMOE_OK;
+    if (!out_load || !out_used || !out_entropy || !out_cv) return fail(REMOE_E_INVALID_ARG, "an output pointer is NULL");
+    return launch_balance(idx, n_seq, n_steps, top_k, n_experts, out_load, out_used, out_entropy, out_cv,
+                          static_cast<hipStream_t>(stream));
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

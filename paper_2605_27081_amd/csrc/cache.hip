@@ -1,0 +1,347 @@
+// The rest of the paper's expert-cache simulator on routing traces, and routing-balance statistics.
+//
+// cache_policy_kernel: per-layer expert cache of capacity C under LRU, FIFO, LFU or Belady's MIN
+// (App. E.2 "Cache state": the update rule depends on the policy, the hit / miss definitions do
+// not; App. F.1 evaluates Belady under the same per-request resets).  Per step it reports the
+// unique misses |U_t \ C_t| and the token hits against the resident set BEFORE the step, and |U_t|
+// (App. E.2, "Per-step hits and misses"); per trace the totals that give #uMiss and uHR.
+// These policies carry state from step to step (unlike LRU, whose resident set is a function of
+// the last requests alone), so a trace is walked in order: one wavefront per trace, lane l owning
+// experts l and l + 64 with their resident bit and retention key in registers.  After a step every
+// requested expert is held; while more than C are held, the one with the smallest key is dropped
+// (two wavefront-wide minimum reductions: primary key, then secondary key, which ends in the
+// expert id and is therefore unique).  Keys (larger = kept longer):
+//   LRU    (step of last use, id)                 FIFO  (step of last fetch, id)
+//   LFU    requests so far, then (step of last use, id)
+//   Belady (steps_total - step of next request, 127 - id): the next request farthest ahead goes first
+// The next-request table of Belady comes from next_use_kernel, a backward walk over the same trace.
+//
+// step_summary_kernel / step_percentile_kernel: per-step sums of a miss table over the MoE layers,
+// their histogram and P50 / P95 / P99 (App. E.2, "Per-step (edge) reporting").
+//
+// balance_kernel: expert loads of a trace, experts used, normalised routing entropy and the
+// coefficient of variation of the loads (the quantities Sec. 5.2 tracks to show that routing stays
+// balanced).
+#include "common.h"
+#include "topk.h"
+
+namespace remoe {
+
+namespace {
+
+constexpr int CP_BATCH = 64;            // steps staged in LDS at a time
+constexpr int CP_MAX_K = 64;
+constexpr uint32_t CP_NONE = 0xFFFFFFFFu;
+
+// rows [t0, t0 + n) of a [T, K] int32 table -> LDS, coalesced
+__device__ __forceinline__ void stage_rows(const int32_t *__restrict__ table, int64_t t0, int n, int K, int32_t *lds)
+{
+    const int lane = threadIdx.x & 63;
+    for (int q = lane; q < n * K; q += 64) lds[q] = table[t0 * K + q];
+}
+
+// Belady: nxt[t, j] = first step after t that requests expert idx[t, j] again, or T (never).
+__global__ __launch_bounds__(64) void next_use_kernel(const int32_t *__restrict__ idx, int64_t T, int K, int N,
+                                                      int32_t *__restrict__ nxt)
+{
+    __shared__ int32_t ids[CP_BATCH * CP_MAX_K];
+    __shared__ int32_t outs[CP_BATCH * CP_MAX_K];
+    const int64_t s = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int32_t *tr = idx + s * T * K;
+    int32_t *no = nxt + s * T * K;
+    int32_t seen0 = (int32_t)T, seen1 = (int32_t)T;      // next request of experts lane, lane + 64 seen so far
+    for (int64_t hi = T; hi > 0; hi -= CP_BATCH) {
+        const int64_t t0 = hi >= CP_BATCH ? hi - CP_BATCH : 0;
+        const int n = (int)(hi - t0);
+        stage_rows(tr, t0, n, K, ids);
+        __syncthreads();
+        for (int tt = n - 1; tt >= 0; --tt) {
+            int32_t mine = (int32_t)T;
+            for (int j = 0; j < K; ++j) {
+                const int e = ids[tt * K + j];
+                int32_t v = (int32_t)T;
+                if (e >= 0 && e < N) v = __shfl(e < 64 ? seen0 : seen1, e & 63, 64);
+                if (lane == j) mine = v;
+            }
+            if (lane < K) outs[tt * K + lane] = mine;
+            for (int j = 0; j < K; ++j) {
+                const int e = ids[tt * K + j];
+                if (e == lane) seen0 = (int32_t)(t0 + tt);
+                if (e == lane + 64) seen1 = (int32_t)(t0 + tt);
+            }
+        }
+        __syncthreads();
+        for (int q = lane; q < n * K; q += 64) no[t0 * K + q] = outs[q];
+        __syncthreads();
+    }
+}
+
+template <int POLICY>
+__global__ __launch_bounds__(64) void cache_policy_kernel(const int32_t *__restrict__ idx, int64_t T, int K, int N, int C,
+                                                          unsigned long long expert_bytes,
+                                                          const int32_t *__restrict__ nxt,
+                                                          uint8_t *__restrict__ out_miss, uint8_t *__restrict__ out_uniq,
+                                                          uint8_t *__restrict__ out_hit_tok,
+                                                          unsigned long long *__restrict__ out_total_miss,
+                                                          unsigned long long *__restrict__ out_total_uniq,
+                                                          unsigned long long *__restrict__ out_bytes)
+{
+    __shared__ int32_t ids[CP_BATCH * CP_MAX_K];
+    __shared__ int32_t nus[(POLICY == REMOE_CACHE_BELADY) ? CP_BATCH * CP_MAX_K : 1];
+    __shared__ uint8_t o_miss[CP_BATCH], o_uniq[CP_BATCH], o_hit[CP_BATCH];
+    const int64_t s = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int32_t *tr = idx + s * T * K;
+    bool res0 = false, res1 = false;
+    uint32_t khi0 = 0, khi1 = 0, klo0 = 0, klo1 = 0;
+    unsigned long long total = 0, total_u = 0;
+    for (int64_t t0 = 0; t0 < T; t0 += CP_BATCH) {
+        const int n = (int)((T - t0 < CP_BATCH) ? T - t0 : CP_BATCH);
+        stage_rows(tr, t0, n, K, ids);
+        if (POLICY == REMOE_CACHE_BELADY) stage_rows(nxt + s * T * K, t0, n, K, nus);
+        __syncthreads();
+        for (int tt = 0; tt < n; ++tt) {
+            const uint32_t t = (uint32_t)(t0 + tt);
+            bool req0 = false, req1 = false;
+            uint32_t nu0 = (uint32_t)T, nu1 = (uint32_t)T;
+            int hit_tok = 0;
+            for (int j = 0; j < K; ++j) {
+                const int e = ids[tt * K + j];
+                const bool in0 = e == lane, in1 = e == lane + 64 && e < N;
+                req0 |= in0 && e < N;
+                req1 |= in1;
+                hit_tok += (__ballot((in0 && res0) || (in1 && res1)) != 0ull) ? 1 : 0;
+                if (POLICY == REMOE_CACHE_BELADY) {
+                    if (in0) nu0 = (uint32_t)nus[tt * K + j];
+                    if (in1) nu1 = (uint32_t)nus[tt * K + j];
+                }
+            }
+            const int n_u = __popcll(__ballot(req0)) + __popcll(__ballot(req1));
+            const int miss = __popcll(__ballot(req0 && !res0)) + __popcll(__ballot(req1 && !res1));
+            // serve the step: every requested expert is held now; refresh its key
+            const uint32_t stamp = ((t + 1u) << 7);
+            if (POLICY == REMOE_CACHE_LRU || POLICY == REMOE_CACHE_LFU) {
+                if (req0) klo0 = stamp | (uint32_t)lane;
+                if (req1) klo1 = stamp | (uint32_t)(lane + 64);
+            }
+            if (POLICY == REMOE_CACHE_FIFO) {
+                if (req0 && !res0) klo0 = stamp | (uint32_t)lane;
+                if (req1 && !res1) klo1 = stamp | (uint32_t)(lane + 64);
+            }
+            if (POLICY == REMOE_CACHE_LFU) {
+                khi0 += req0 ? 1u : 0u;
+                khi1 += req1 ? 1u : 0u;
+            }
+            if (POLICY == REMOE_CACHE_BELADY) {
+                if (req0) klo0 = (((uint32_t)T - nu0) << 7) | (uint32_t)(127 - lane);
+                if (req1) klo1 = (((uint32_t)T - nu1) << 7) | (uint32_t)(127 - (lane + 64));
+            }
+            res0 |= req0;
+            res1 |= req1;
+            int held = __popcll(__ballot(res0)) + __popcll(__ballot(res1));
+            while (held > C) {
+                bool c0 = res0, c1 = res1;
+                if (POLICY == REMOE_CACHE_LFU) {
+                    const uint32_t a0 = res0 ? khi0 : CP_NONE, a1 = res1 ? khi1 : CP_NONE;
+                    const uint32_t mhi = wave_min_u32(a0 < a1 ? a0 : a1);
+                    c0 = res0 && khi0 == mhi;
+                    c1 = res1 && khi1 == mhi;
+                }
+                const uint32_t b0 = c0 ? klo0 : CP_NONE, b1 = c1 ? klo1 : CP_NONE;
+                const uint32_t mlo = wave_min_u32(b0 < b1 ? b0 : b1);
+                if (c0 && klo0 == mlo) res0 = false;
+                if (c1 && klo1 == mlo) res1 = false;
+                --held;
+            }
+            if (lane == 0) {
+                o_miss[tt] = (uint8_t)miss;
+                o_uniq[tt] = (uint8_t)n_u;
+                o_hit[tt] = (uint8_t)hit_tok;
+            }
+            total += (unsigned long long)miss;
+            total_u += (unsigned long long)n_u;
+        }
+        __syncthreads();
+        if (lane < n) {
+            out_miss[s * T + t0 + lane] = o_miss[lane];
+            out_uniq[s * T + t0 + lane] = o_uniq[lane];
+            out_hit_tok[s * T + t0 + lane] = o_hit[lane];
+        }
+        __syncthreads();
+    }
+    if (lane == 0) {
+        out_total_miss[s] = total;
+        out_total_uniq[s] = total_u;
+        out_bytes[s] = total * expert_bytes;
+    }
+}
+
+// ---- per-step sums over layers, histogram, percentiles -----------------------------------------------
+constexpr int SS_MAX_HIST = 4097;       // sums up to 64 layers x 64 experts
+
+__global__ void zero_u64_kernel(unsigned long long *p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0ull;
+}
+
+__global__ __launch_bounds__(256) void step_summary_kernel(const uint8_t *__restrict__ miss, int64_t L, int64_t n,
+                                                           uint16_t *__restrict__ out_all,
+                                                           unsigned long long *__restrict__ hist, int hist_len)
+{
+    __shared__ uint32_t lh[SS_MAX_HIST];
+    for (int v = threadIdx.x; v < hist_len; v += blockDim.x) lh[v] = 0u;
+    __syncthreads();
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        uint32_t a = 0;
+        for (int64_t l = 0; l < L; ++l) a += miss[l * n + i];
+        out_all[i] = (uint16_t)a;
+        atomicAdd(&lh[(int)a < hist_len ? a : (uint32_t)(hist_len - 1)], 1u);   // sums beyond the table share its last bin
+    }
+    __syncthreads();
+    for (int v = threadIdx.x; v < hist_len; v += blockDim.x)
+        if (lh[v]) atomicAdd(&hist[v], (unsigned long long)lh[v]);   // integer sums: exact in any order
+}
+
+// percentile p = smallest v whose cumulative count reaches p percent of the n steps
+__global__ void step_percentile_kernel(const unsigned long long *__restrict__ hist, int hist_len, unsigned long long n,
+                                       int32_t *__restrict__ out_pct)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const unsigned long long pcts[3] = {50ull, 95ull, 99ull};
+    for (int k = 0; k < 3; ++k) {
+        unsigned long long cum = 0;
+        int32_t ans = -1;
+        for (int v = 0; v < hist_len && ans < 0; ++v) {
+            cum += hist[v];
+            if (n > 0 && 100ull * cum >= pcts[k] * n) ans = v;
+        }
+        out_pct[k] = ans;
+    }
+}
+
+// ---- expert-load balance of a trace -------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+        const unsigned lo = __shfl_xor((unsigned)(b & 0xFFFFFFFFull), off, 64);
+        const unsigned hi = __shfl_xor((unsigned)(b >> 32), off, 64);
+        v += __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(256) void balance_kernel(const int32_t *__restrict__ idx, int64_t T, int K, int N,
+                                                      uint32_t *__restrict__ out_load, int32_t *__restrict__ out_used,
+                                                      double *__restrict__ out_entropy, double *__restrict__ out_cv)
+{
+    __shared__ uint32_t load[128];
+    const int64_t s = blockIdx.x;
+    if (threadIdx.x < 128) load[threadIdx.x] = 0u;
+    __syncthreads();
+    const int32_t *tr = idx + s * T * K;
+    for (int64_t q = threadIdx.x; q < T * K; q += blockDim.x) {
+        const int e = tr[q];
+        if (e >= 0 && e < N) atomicAdd(&load[e], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x < N) out_load[s * N + threadIdx.x] = load[threadIdx.x];
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        const double total = (double)T * (double)K;
+        const double m = total / (double)N;
+        double h = 0.0, var = 0.0;
+        int used = 0;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int e = lane + 64 * half;
+            if (e < N) {
+                const double c = (double)load[e];
+                if (load[e] > 0u) {
+                    const double p = c / total;
+                    h -= p * log(p);
+                }
+                var += (c - m) * (c - m);
+            }
+            used += __popcll(__ballot(e < N && load[e] > 0u));
+        }
+        h = wave_sum_f64(h);
+        var = wave_sum_f64(var);
+        if (lane == 0) {
+            out_used[s] = used;
+            out_entropy[s] = (total > 0.0 && N > 1) ? h / log((double)N) : 0.0;
+            out_cv[s] = (total > 0.0) ? sqrt(var / (double)N) / m : 0.0;
+        }
+    }
+}
+
+}  // namespace
+
+size_t cache_workspace_bytes(int64_t S, int64_t T, int K, int policy)
+{
+    return policy == REMOE_CACHE_BELADY ? align_up(sizeof(int32_t) * (size_t)S * (size_t)T * (size_t)K, 256) : 0;
+}
+
+remoe_status launch_cache_policy(const int32_t *idx, int64_t S, int64_t T, int K, int N, int C, int policy,
+                                 uint64_t expert_bytes, uint8_t *miss, uint8_t *uniq, uint8_t *hit_tok,
+                                 uint64_t *total_miss, uint64_t *total_uniq, uint64_t *bytes, void *workspace,
+                                 hipStream_t stream)
+{
+    if (S == 0) return REMOE_OK;
+    const dim3 grid((unsigned)S), block(64);
+    unsigned long long *tm = reinterpret_cast<unsigned long long *>(total_miss);
+    unsigned long long *tu = reinterpret_cast<unsigned long long *>(total_uniq);
+    unsigned long long *tb = reinterpret_cast<unsigned long long *>(bytes);
+    int32_t *nxt = static_cast<int32_t *>(workspace);
+    switch (policy) {
+    case REMOE_CACHE_LRU:
+        hipLaunchKernelGGL(cache_policy_kernel<REMOE_CACHE_LRU>, grid, block, 0, stream, idx, T, K, N, C, expert_bytes, nxt, miss,
+                           uniq, hit_tok, tm, tu, tb);
+        break;
+    case REMOE_CACHE_FIFO:
+        hipLaunchKernelGGL(cache_policy_kernel<REMOE_CACHE_FIFO>, grid, block, 0, stream, idx, T, K, N, C, expert_bytes, nxt, miss,
+                           uniq, hit_tok, tm, tu, tb);
+        break;
+    case REMOE_CACHE_LFU:
+        hipLaunchKernelGGL(cache_policy_kernel<REMOE_CACHE_LFU>, grid, block, 0, stream, idx, T, K, N, C, expert_bytes, nxt, miss,
+                           uniq, hit_tok, tm, tu, tb);
+        break;
+    case REMOE_CACHE_BELADY:
+        hipLaunchKernelGGL(next_use_kernel, grid, block, 0, stream, idx, T, K, N, nxt);
+        hipLaunchKernelGGL(cache_policy_kernel<REMOE_CACHE_BELADY>, grid, block, 0, stream, idx, T, K, N, C, expert_bytes, nxt,
+                           miss, uniq, hit_tok, tm, tu, tb);
+        break;
+    default:
+        return fail(REMOE_E_INVALID_ARG, "unknown cache policy %d", policy);
+    }
+    return check_hip(hipGetLastError(), "cache_policy_kernel launch");
+}
+
+int step_summary_max_hist() { return SS_MAX_HIST; }
+
+remoe_status launch_step_summary(const uint8_t *miss, int64_t L, int64_t S, int64_t T, uint16_t *out_all,
+                                 uint64_t *hist, int hist_len, int32_t *pct, hipStream_t stream)
+{
+    const int64_t n = S * T;
+    unsigned long long *h = reinterpret_cast<unsigned long long *>(hist);
+    hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(256), 0, stream, h, (int64_t)hist_len);
+    if (n > 0) {
+        int64_t blocks = ceil_div(n, 256);
+        if (blocks > 2048) blocks = 2048;
+        hipLaunchKernelGGL(step_summary_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, miss, L, n, out_all, h, hist_len);
+    }
+    hipLaunchKernelGGL(step_percentile_kernel, dim3(1), dim3(64), 0, stream, h, hist_len, (unsigned long long)n, pct);
+    return check_hip(hipGetLastError(), "step_summary launch");
+}
+
+remoe_status launch_balance(const int32_t *idx, int64_t S, int64_t T, int K, int N, uint32_t *load, int32_t *used,
+                            double *entropy, double *cv, hipStream_t stream)
+{
+    if (S == 0) return REMOE_OK;
+    hipLaunchKernelGGL(balance_kernel, dim3((unsigned)S), dim3(256), 0, stream, idx, T, K, N, load, used, entropy, cv);
+    return check_hip(hipGetLastError(), "balance_kernel launch");
+}
+
+}  // namespace remoe

@@ -142,6 +142,18 @@ remoe_status launch_lru(const int32_t *idx, int64_t S, int64_t T, int K, int N, 
                         uint64_t expert_bytes, int64_t step0, uint32_t *state, uint8_t *miss,
                         uint64_t *total, uint64_t *bytes, hipStream_t stream);
 
+// Cache policies beyond LRU, per-step sums over layers, routing balance.
+size_t cache_workspace_bytes(int64_t S, int64_t T, int K, int policy);
+remoe_status launch_cache_policy(const int32_t *idx, int64_t S, int64_t T, int K, int N, int C, int policy,
+                                 uint64_t expert_bytes, uint8_t *miss, uint8_t *uniq, uint8_t *hit_tok,
+                                 uint64_t *total_miss, uint64_t *total_uniq, uint64_t *bytes, void *workspace,
+                                 hipStream_t stream);
+int step_summary_max_hist();
+remoe_status launch_step_summary(const uint8_t *miss, int64_t L, int64_t S, int64_t T, uint16_t *out_all,
+                                 uint64_t *hist, int hist_len, int32_t *pct, hipStream_t stream);
+remoe_status launch_balance(const int32_t *idx, int64_t S, int64_t T, int K, int N, uint32_t *load, int32_t *used,
+                            double *entropy, double *cv, hipStream_t stream);
+
 // Plain copy of known size (yardstick for hardware byte counters).
 remoe_status launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t stream);
 

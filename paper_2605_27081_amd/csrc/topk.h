@@ -49,4 +49,24 @@ __device__ __forceinline__ float wave_max(float v)
     return fmaxf(fmaxf(read_lane(v, 0), read_lane(v, 16)), fmaxf(read_lane(v, 32), read_lane(v, 48)));
 }
 
+// Minimum of an unsigned value over the 64 lanes, the same value in every lane.
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+#define REMOE_DPP_U32(x, ctrl) ((uint32_t)__builtin_amdgcn_update_dpp(0, (int)(x), ctrl, 0xF, 0xF, true))
+    uint32_t o;
+    o = REMOE_DPP_U32(v, 0xB1); v = o < v ? o : v;
+    o = REMOE_DPP_U32(v, 0x4E); v = o < v ? o : v;
+    o = REMOE_DPP_U32(v, 0x141); v = o < v ? o : v;
+    o = REMOE_DPP_U32(v, 0x140); v = o < v ? o : v;
+#undef REMOE_DPP_U32
+    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+    const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+    const uint32_t ab = a < b ? a : b, cd = c < d ? c : d;
+    return ab < cd ? ab : cd;
+#else
+    return v;
+#endif
+}
+
 }  // namespace remoe

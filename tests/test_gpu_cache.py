@@ -1,0 +1,153 @@
+"""GPU parity of cache_simulate, step_miss_summary and routing_balance against the CPU oracle.
+
+Integer results (misses, hits, totals, bytes, sums, histogram, percentiles, loads, experts used) are
+compared bit for bit; the two fp64 balance figures to 1e-12 (the kernel adds the per-expert terms
+in a tree, the oracle one after the other).
+"""
+import pytest
+import torch
+
+import oracle
+import paper_2605_27081_amd as remoe
+import workload as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+POLICY = {"lru": remoe.REMOE_CACHE_LRU, "fifo": remoe.REMOE_CACHE_FIFO, "lfu": remoe.REMOE_CACHE_LFU,
+          "belady": remoe.REMOE_CACHE_BELADY}
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _trace(seed, S, T, K, N, distinct=True, skew=0.0):
+    g = torch.Generator().manual_seed(seed)
+    if distinct:
+        w = torch.arange(1, N + 1, dtype=torch.float64) ** (-skew)
+        rows = torch.stack([torch.multinomial(w, K, replacement=False, generator=g) for _ in range(S * T)])
+        return rows.reshape(S, T, K).to(torch.int32)
+    return torch.randint(0, N, (S, T, K), generator=g, dtype=torch.int32)
+
+
+def _gpu_cache(idx, N, C, policy, expert_bytes):
+    S, T, K = idx.shape
+    d = idx.to(DEV)
+    out = {k: torch.full((S, T), 255, dtype=torch.uint8, device=DEV) for k in ("miss", "uniq", "hit_tok")}
+    out.update({k: torch.full((S,), -1, dtype=torch.int64, device=DEV) for k in ("total_miss", "total_uniq", "bytes")})
+    nb = remoe.remoe_cache_workspace_bytes(S, T, K, POLICY[policy])
+    ws = torch.empty(max(nb, 16), dtype=torch.uint8, device=DEV) if nb else None
+    remoe.cache_simulate(d, N, C, POLICY[policy], expert_bytes, out["miss"], out["uniq"], out["hit_tok"],
+                         out["total_miss"], out["total_uniq"], out["bytes"], ws)
+    torch.cuda.synchronize()
+    return {k: v.cpu() for k, v in out.items()}
+
+
+@pytest.mark.parametrize("policy", ["lru", "fifo", "lfu", "belady"])
+@pytest.mark.parametrize("S,T,K,N,C,distinct,skew", [
+    (3, 50, 1, 6, 3, False, 0.0),       # one request per step
+    (5, 130, 2, 16, 4, True, 0.0),      # several 64-step batches and a ragged tail
+    (4, 200, 6, 64, 16, True, 1.0),     # DeepSeek-V2-Lite-shaped trace, skewed popularity
+    (2, 300, 8, 128, 32, True, 0.5),    # Qwen3-shaped trace: both halves of the expert range
+    (3, 90, 4, 60, 12, True, 0.0),      # Qwen1.5-shaped
+    (2, 70, 4, 12, 5, False, 0.0),      # repeated ids inside a step
+    (2, 40, 6, 20, 3, True, 0.0),       # C < K
+    (2, 33, 4, 9, 9, True, 0.0),        # C = N_r
+    (1, 1, 3, 8, 2, True, 0.0),         # a single step
+])
+def test_cache_policies_match_oracle(policy, S, T, K, N, C, distinct, skew):
+    _say(f"cache {policy} S={S} T={T} K={K} N={N} C={C}")
+    idx = _trace(S * 1000 + T + K, S, T, K, N, distinct, skew)
+    got = _gpu_cache(idx, N, C, policy, 9437184)
+    ref = oracle.cache_policy(idx, N, C, policy, 9437184)
+    for k in ("miss", "uniq", "hit_tok", "total_miss", "total_uniq", "bytes"):
+        assert torch.equal(got[k], ref[k]), k
+
+
+def test_cache_lru_equals_lru_simulate():
+    """The sequential LRU of cache_simulate and the parallel walk of lru_simulate are two kernels for one definition."""
+    idx = _trace(77, 6, 500, 8, 128, True, 0.7).to(DEV)
+    S, T, K = idx.shape
+    a = _gpu_cache(idx.cpu(), 128, 32, "lru", 11)
+    miss = torch.empty(S, T, dtype=torch.uint8, device=DEV)
+    tot = torch.empty(S, dtype=torch.int64, device=DEV)
+    nb = torch.empty(S, dtype=torch.int64, device=DEV)
+    remoe.lru_simulate(idx, 128, 32, 11, 0, None, miss, tot, nb)
+    torch.cuda.synchronize()
+    assert torch.equal(a["miss"], miss.cpu()) and torch.equal(a["total_miss"], tot.cpu()) and torch.equal(a["bytes"], nb.cpu())
+
+
+def test_cache_full_length_trace_sampled():
+    """A full-length (4096-step) trace of the Qwen3-shaped configuration: totals of every policy against the
+    oracle on a few traces, and Belady below the others on all of them."""
+    cfg = wl.get_config("qwen3_prefill")
+    idx = _trace(5, 4, cfg.seq_len, cfg.top_k, cfg.n_experts, True, 0.8)
+    tot = {}
+    for p in POLICY:
+        got = _gpu_cache(idx, cfg.n_experts, 32, p, cfg.expert_bytes)
+        ref = oracle.cache_policy(idx[:2], cfg.n_experts, 32, p, cfg.expert_bytes)
+        assert torch.equal(got["miss"][:2], ref["miss"]) and torch.equal(got["total_miss"][:2], ref["total_miss"])
+        tot[p] = got["total_miss"]
+    for p in ("lru", "fifo", "lfu"):
+        assert (tot["belady"] <= tot[p]).all()
+
+
+def test_cache_rejects_bad_arguments():
+    idx = torch.zeros(1, 4, 2, dtype=torch.int32, device=DEV)
+    z8 = torch.zeros(1, 4, dtype=torch.uint8, device=DEV)
+    z64 = torch.zeros(1, dtype=torch.int64, device=DEV)
+    with pytest.raises(remoe.RemoeError, match="capacity"):
+        remoe.cache_simulate(idx, 8, 0, 0, 1, z8, z8, z8, z64, z64, z64)
+    with pytest.raises(remoe.RemoeError, match="policy"):
+        remoe.cache_simulate(idx, 8, 2, 9, 1, z8, z8, z8, z64, z64, z64)
+    with pytest.raises(remoe.RemoeError, match="workspace"):
+        remoe.cache_simulate(idx, 8, 2, remoe.REMOE_CACHE_BELADY, 1, z8, z8, z8, z64, z64, z64, None)
+
+
+@pytest.mark.parametrize("L,S,T,hist_len", [(3, 2, 50, 19), (26, 4, 64, 157), (48, 16, 500, 385), (1, 1, 7, 7), (4, 3, 9, 5)])
+def test_step_summary_matches_oracle(L, S, T, hist_len):
+    g = torch.Generator().manual_seed(L * S + T)
+    miss = torch.randint(0, 7, (L, S, T), generator=g, dtype=torch.uint8)
+    out_all = torch.zeros(S, T, dtype=torch.int16, device=DEV)
+    hist = torch.full((hist_len,), -1, dtype=torch.int64, device=DEV)
+    pct = torch.zeros(3, dtype=torch.int32, device=DEV)
+    remoe.step_miss_summary(miss.to(DEV), out_all, hist, pct)
+    torch.cuda.synchronize()
+    rall, rhist, rpct = oracle.step_summary(miss, hist_len)
+    assert torch.equal(out_all.cpu().to(torch.int32) & 0xFFFF, rall)
+    assert torch.equal(hist.cpu(), rhist) and torch.equal(pct.cpu(), rpct)
+
+
+def test_step_summary_of_gpu_misses_end_to_end():
+    """Layers x sequences of LRU misses -> per-step sums and percentiles, all on the GPU, against the oracle chain."""
+    L, S, T, K, N, C = 6, 3, 120, 4, 32, 8
+    idx = _trace(3, L * S, T, K, N)
+    d = idx.to(DEV)
+    miss = torch.empty(L * S, T, dtype=torch.uint8, device=DEV)
+    tot = torch.empty(L * S, dtype=torch.int64, device=DEV)
+    nb = torch.empty(L * S, dtype=torch.int64, device=DEV)
+    remoe.lru_simulate(d, N, C, 1, 0, None, miss, tot, nb)
+    out_all = torch.zeros(S, T, dtype=torch.int16, device=DEV)
+    hist = torch.zeros(L * K + 1, dtype=torch.int64, device=DEV)
+    pct = torch.zeros(3, dtype=torch.int32, device=DEV)
+    remoe.step_miss_summary(miss.view(L, S, T), out_all, hist, pct)
+    torch.cuda.synchronize()
+    rmiss, _, _ = oracle.lru_list(idx, N, C, 1)
+    rall, rhist, rpct = oracle.step_summary(rmiss.view(L, S, T), L * K + 1)
+    assert torch.equal(out_all.cpu().to(torch.int32) & 0xFFFF, rall) and torch.equal(hist.cpu(), rhist)
+    assert torch.equal(pct.cpu(), rpct)
+
+
+@pytest.mark.parametrize("S,T,K,N,skew", [(3, 100, 4, 20, 0.0), (4, 2048, 6, 64, 1.0), (2, 4096, 8, 128, 0.5),
+                                          (2, 10, 1, 1, 0.0), (1, 5, 2, 60, 0.0)])
+def test_balance_matches_oracle(S, T, K, N, skew):
+    idx = _trace(S + T, S, T, K, N, True, skew)
+    load = torch.zeros(S, N, dtype=torch.int32, device=DEV)
+    used = torch.zeros(S, dtype=torch.int32, device=DEV)
+    ent = torch.zeros(S, dtype=torch.float64, device=DEV)
+    cv = torch.zeros(S, dtype=torch.float64, device=DEV)
+    remoe.routing_balance(idx.to(DEV), N, load, used, ent, cv)
+    torch.cuda.synchronize()
+    rload, rused, rent, rcv = oracle.balance(idx, N)
+    assert torch.equal(load.cpu().to(torch.int64), rload) and torch.equal(used.cpu(), rused)
+    assert torch.allclose(ent.cpu(), rent, rtol=1e-12, atol=1e-14) and torch.allclose(cv.cpu(), rcv, rtol=1e-12, atol=1e-14)
