@@ -309,6 +309,30 @@ remoe_status routing_balance(const int32_t *idx, int64_t n_seq, int64_t n_steps,
                              int32_t n_experts, uint32_t *out_load, int32_t *out_used,
                              double *out_entropy, double *out_cv, void *stream);
 
+/*
+ * reroute_lru -- cache-aware rerouting at inference time (App. G, "Setup"): experts that are in the
+ * per-layer LRU cache get a residency bonus beta on their pre-top-k router score; beta = 0 is the
+ * unmodified router.  Routing and cache state depend on each other, so every trace is one
+ * sequential pass from a cold cache.
+ *
+ *   score_t[e]  = probs[s, t, e] * factor   if e is resident before step t,  else probs[s, t, e]
+ *                 (factor = exp(beta): the same order as adding beta to the resident experts' logits;
+ *                 one fp32 multiply, so the selection is decided in fp32)
+ *   out_idx[s, t, :]  the K experts of largest score, descending, ties to the lower id
+ *   out_w[s, t, j]    probs[s, t, out_idx[s, t, j]] (the unmodified probability), divided by the
+ *                     sum over the K chosen when renorm
+ *   out_miss[s, t]    |E_t \ C_t| against the cache before the step; then E_t becomes the most
+ *                     recent (ascending id inside the step) and the cache keeps `capacity` experts
+ *   out_total_miss[s] sum_t out_miss[s, t]      (uHR = 1 - total_miss / (K T))
+ *
+ *   probs [S, T, N_r] fp32 (e.g. out_probs of moe_route); out_idx int32 [S, T, K]; out_w fp32 [S, T, K];
+ *   out_miss uint8 [S, T]; out_total_miss uint64 [S].  n_experts <= 128, top_k <= min(n_experts, 64),
+ *   capacity >= 1, factor > 0 and finite, n_steps < 2^24.
+ */
+remoe_status reroute_lru(const float *probs, int64_t n_seq, int64_t n_steps, int32_t n_experts, int32_t top_k,
+                         int32_t capacity, float factor, int32_t renorm, int32_t *out_idx, float *out_w,
+                         uint8_t *out_miss, uint64_t *out_total_miss, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

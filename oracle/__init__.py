@@ -50,6 +50,9 @@ def lib() -> ctypes.CDLL:
         _lib.oracle_step_summary.argtypes = [_c_ptr, _c_i64, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_i64, _c_ptr]
         _lib.oracle_balance.restype = _c_int
         _lib.oracle_balance.argtypes = [_c_ptr, _c_i64, _c_i64, _c_int, _c_int, _c_ptr, _c_ptr, _c_ptr, _c_ptr]
+        _lib.oracle_reroute_lru.restype = _c_int
+        _lib.oracle_reroute_lru.argtypes = [_c_ptr, _c_i64, _c_i64, _c_int, _c_int, _c_int, ctypes.c_float, _c_int,
+                                            _c_ptr, _c_ptr, _c_ptr, _c_ptr]
     return _lib
 
 
@@ -232,3 +235,17 @@ def balance(idx: torch.Tensor, n_experts: int):
     if rc != 0:
         raise ValueError(f"oracle_balance failed ({rc})")
     return load.to(torch.int64), used, ent, cv
+
+
+def reroute_lru(probs: torch.Tensor, top_k: int, capacity: int, factor: float, renorm: bool):
+    """Cache-aware rerouting (App. G): probs fp32 [S, T, N]; factor = exp(beta) as an fp32 value.
+    Returns dict idx int32 [S,T,K], w fp64 [S,T,K], miss uint8 [S,T], total_miss int64 [S]."""
+    probs = _chk(probs, torch.float32)
+    S, T, N = probs.shape
+    out = {"idx": torch.zeros(S, T, top_k, dtype=torch.int32), "w": torch.zeros(S, T, top_k, dtype=torch.float64),
+           "miss": torch.zeros(S, T, dtype=torch.uint8), "total_miss": torch.zeros(S, dtype=torch.int64)}
+    rc = lib().oracle_reroute_lru(_p(probs), S, T, N, top_k, capacity, float(factor), int(renorm), _p(out["idx"]),
+                                  _p(out["w"]), _p(out["miss"]), _p(out["total_miss"]))
+    if rc != 0:
+        raise ValueError(f"oracle_reroute_lru failed ({rc})")
+    return out

@@ -206,3 +206,82 @@ int oracle_balance(const int32_t *idx, int64_t n_seq, int64_t n_steps, int top_k
     }
     return 0;
 }
+
+/*
+ * Cache-aware rerouting at inference time (App. G, "Setup"): a residency bonus beta is added to the
+ * pre-Top-K router scores of the experts that are in the (LRU) cache, beta = 0 being the unmodified
+ * router.  The routing of step t therefore depends on the cache left by steps < t, and the cache
+ * on the routing: one sequential pass per trace, cold at its start.
+ * Readings (the appendix gives the idea only):
+ *   - the bonus is additive on the logits.  With P = softmax(logits) that is the same ordering as
+ *     P_e * exp(beta) for resident experts against P_e for the others, which is the form used here
+ *     (`factor` = exp(beta), applied in fp32 to fp32 probabilities: the selection is decided in
+ *     that precision on both sides); ties go to the lower id;
+ *   - the selected experts keep their unmodified probabilities as gate weights (the intervention
+ *     moves the choice, not the mixture), divided by their sum when `renorm`;
+ *   - the cache is the LRU of oracle_lru_list (misses against the state before the step, the
+ *     step's experts touched in ascending id).
+ * Outputs: idx [S,T,K] (descending boosted score), w [S,T,K] fp64, miss [S,T], total_miss [S].
+ */
+int oracle_reroute_lru(const float *probs, int64_t n_seq, int64_t n_steps, int n_experts, int top_k,
+                       int capacity, float factor, int renorm,
+                       int32_t *out_idx, double *out_w, uint8_t *out_miss, uint64_t *out_total_miss)
+{
+    if (!probs || !out_idx || !out_w || !out_miss || !out_total_miss) return -1;
+    if (top_k < 1 || top_k > n_experts || capacity < 1) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t s = 0; s < n_seq; ++s) {
+        int32_t *lst = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_experts + top_k));   /* resident ids, least recent first */
+        float *score = (float *)malloc(sizeof(float) * (size_t)n_experts);
+        uint8_t *taken = (uint8_t *)malloc((size_t)n_experts);
+        int len = 0;
+        uint64_t total = 0;
+        for (int64_t t = 0; t < n_steps; ++t) {
+            const float *p = probs + (s * n_steps + t) * n_experts;
+            for (int e = 0; e < n_experts; ++e) {
+                int resident = 0;
+                for (int r = 0; r < len; ++r) resident |= (lst[r] == e);
+                const volatile float boosted = p[e] * factor;      /* one fp32 multiply, rounded to fp32 */
+                score[e] = resident ? boosted : p[e];
+                taken[e] = 0;
+            }
+            int32_t *sel = out_idx + (s * n_steps + t) * top_k;
+            double wsum = 0.0;
+            for (int j = 0; j < top_k; ++j) {          /* K times: the largest remaining score, lowest id first */
+                int best = -1;
+                for (int e = 0; e < n_experts; ++e)
+                    if (!taken[e] && (best < 0 || score[e] > score[best])) best = e;
+                taken[best] = 1;
+                sel[j] = best;
+                wsum += (double)p[best];
+            }
+            for (int j = 0; j < top_k; ++j)
+                out_w[(s * n_steps + t) * top_k + j] = renorm ? (double)p[sel[j]] / wsum : (double)p[sel[j]];
+            /* LRU step on the selected set (distinct by construction) */
+            int miss = 0;
+            for (int e = 0; e < n_experts; ++e) {
+                if (!taken[e]) continue;
+                int found = 0;
+                for (int r = 0; r < len; ++r) found |= (lst[r] == e);
+                miss += !found;
+            }
+            for (int e = 0; e < n_experts; ++e) {      /* ascending id: move to the most-recent end */
+                if (!taken[e]) continue;
+                int r = 0;
+                while (r < len && lst[r] != e) ++r;
+                if (r < len) { for (; r + 1 < len; ++r) lst[r] = lst[r + 1]; --len; }
+                lst[len++] = e;
+            }
+            if (len > capacity) {
+                const int drop = len - capacity;
+                for (int r = 0; r + drop < len; ++r) lst[r] = lst[r + drop];
+                len = capacity;
+            }
+            out_miss[s * n_steps + t] = (uint8_t)miss;
+            total += (uint64_t)miss;
+        }
+        out_total_miss[s] = total;
+        free(lst); free(score); free(taken);
+    }
+    return 0;
+}

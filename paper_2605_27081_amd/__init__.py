@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     REMOE_CACHE_LRU,
     cache_simulate,
     remoe_cache_workspace_bytes,
+    reroute_lru,
     routing_balance,
     step_miss_summary,
     REMOE_DECODE_CHAINED,

@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
     lib.step_miss_summary.argtypes = [P, I64, I64, I64, P, P, I64, P, P]
     lib.routing_balance.restype = ctypes.c_int
     lib.routing_balance.argtypes = [P, I64, I64, I32, I32, P, P, P, P, P]
+    lib.reroute_lru.restype = ctypes.c_int
+    lib.reroute_lru.argtypes = [P, I64, I64, I32, I32, I32, ctypes.c_float, I32, P, P, P, P, P]
     _lib = lib
     return lib
 
@@ -233,3 +235,11 @@ def routing_balance(idx: torch.Tensor, n_experts: int, out_load: torch.Tensor, o
     n_seq, n_steps, top_k = idx.shape
     _check(load_library().routing_balance(_ptr(idx), n_seq, n_steps, top_k, n_experts, _ptr(out_load), _ptr(out_used),
                                           _ptr(out_entropy), _ptr(out_cv), _stream()))
+
+
+def reroute_lru(probs: torch.Tensor, top_k: int, capacity: int, factor: float, renorm: bool, out_idx: torch.Tensor,
+                out_w: torch.Tensor, out_miss: torch.Tensor, out_total_miss: torch.Tensor) -> None:
+    """probs fp32 [S, T, N]; factor = exp(beta)."""
+    n_seq, n_steps, n_experts = probs.shape
+    _check(load_library().reroute_lru(_ptr(probs), n_seq, n_steps, n_experts, top_k, capacity, factor, int(renorm),
+                                      _ptr(out_idx), _ptr(out_w), _ptr(out_miss), _ptr(out_total_miss), _stream()))

@@ -495,5 +495,23 @@ remoe_status routing_balance(const int32_t *idx, int64_t n_seq, int64_t n_steps,
                           static_cast<hipStream_t>(stream));
 }
 
+remoe_status reroute_lru(const float *probs, int64_t n_seq, int64_t n_steps, int32_t n_experts, int32_t top_k,
+                         int32_t capacity, float factor, int32_t renorm, int32_t *out_idx, float *out_w,
+                         uint8_t *out_miss, uint64_t *out_total_miss, void *stream)
+{
+    if (n_seq < 0 || n_steps < 0 || n_seq > 0x7FFFFFFF) return fail(REMOE_E_INVALID_ARG, "bad trace dimensions");
+    if (n_steps >= (1 << 24)) return fail(REMOE_E_INVALID_ARG, "n_steps %lld must stay below 2^24", (long long)n_steps);
+    if (n_experts < 1 || n_experts > MAX_EXPERTS) return fail(REMOE_E_INVALID_ARG, "n_experts %d outside 1..%d", n_experts, MAX_EXPERTS);
+    if (top_k < 1 || top_k > n_experts || top_k > 64) return fail(REMOE_E_INVALID_ARG, "top_k %d outside 1..min(n_experts, 64)", top_k);
+    if (capacity < 1) return fail(REMOE_E_INVALID_ARG, "capacity %d must be at least 1", capacity);
+    if (!(factor > 0.0f) || factor > 3.0e38f) return fail(REMOE_E_INVALID_ARG, "factor must be positive and finite");
+    if (n_seq == 0) return REMOE_OK;
+    if (!out_total_miss || (n_steps > 0 && (!probs || !out_idx || !out_w || !out_miss)))
+        return fail(REMOE_E_INVALID_ARG, "a required pointer is NULL");
+    ProfScope prof(REMOE_PROF_CACHE, static_cast<hipStream_t>(stream));
+    return launch_reroute(probs, n_seq, n_steps, n_experts, top_k, capacity, factor, renorm, out_idx, out_w, out_miss,
+                          out_total_miss, static_cast<hipStream_t>(stream));
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

@@ -19,6 +19,11 @@
 // step_summary_kernel / step_percentile_kernel: per-step sums of a miss table over the MoE layers,
 // their histogram and P50 / P95 / P99 (App. E.2, "Per-step (edge) reporting").
 //
+// reroute_kernel: cache-aware rerouting at inference time (App. G): experts resident in the LRU cache
+// get a bonus on their pre-top-k score, so each step's routing depends on the cache the earlier
+// steps left.  Same walk as above, one wavefront per trace; the top-k of a step is K rounds of
+// wavefront maximum over the boosted scores.
+//
 // balance_kernel: expert loads of a trace, experts used, normalised routing entropy and the
 // coefficient of variation of the loads (the quantities Sec. 5.2 tracks to show that routing stays
 // balanced).
@@ -177,6 +182,83 @@ __global__ __launch_bounds__(64) void cache_policy_kernel(const int32_t *__restr
     }
 }
 
+// Routing with a residency bonus + LRU, one wavefront per trace.  Score of expert e at step t:
+// P_t[e] * factor if e is resident before the step, else P_t[e] (factor = exp(beta): the same order
+// as adding beta to the resident experts' logits); ties to the lower id; gate weights are the
+// unmodified probabilities of the chosen experts (divided by their sum when renorm).
+constexpr int RR_AHEAD = 4;             // probability rows in flight
+
+__global__ __launch_bounds__(64) void reroute_kernel(const float *__restrict__ probs, int64_t T, int N, int K, int C,
+                                                     float factor, int renorm, int32_t *__restrict__ out_idx,
+                                                     float *__restrict__ out_w, uint8_t *__restrict__ out_miss,
+                                                     unsigned long long *__restrict__ out_total_miss)
+{
+    const int64_t s = blockIdx.x;
+    const int lane = threadIdx.x;
+    const float *pr = probs + s * T * N;
+    const float NEG_INF = -__builtin_inff();
+    bool res0 = false, res1 = false;
+    uint32_t key0 = 0, key1 = 0;
+    unsigned long long total = 0;
+    float q0[RR_AHEAD], q1[RR_AHEAD];
+#pragma unroll
+    for (int a = 0; a < RR_AHEAD; ++a) {
+        q0[a] = (a < T && lane < N) ? pr[(int64_t)a * N + lane] : 0.f;
+        q1[a] = (a < T && lane + 64 < N) ? pr[(int64_t)a * N + lane + 64] : 0.f;
+    }
+    for (int64_t tb = 0; tb < T; tb += RR_AHEAD) {
+#pragma unroll
+        for (int a = 0; a < RR_AHEAD; ++a) {
+            const int64_t t = tb + a;
+            if (t >= T) break;
+            const float p0 = q0[a], p1 = q1[a];
+            // the row RR_AHEAD steps ahead takes this slot
+            const int64_t tn = t + RR_AHEAD;
+            q0[a] = (tn < T && lane < N) ? pr[tn * N + lane] : 0.f;
+            q1[a] = (tn < T && lane + 64 < N) ? pr[tn * N + lane + 64] : 0.f;
+
+            float m0 = lane < N ? (res0 ? p0 * factor : p0) : NEG_INF;
+            float m1 = lane + 64 < N ? (res1 ? p1 * factor : p1) : NEG_INF;
+            bool sel0 = false, sel1 = false;
+            int my_e = 0;
+            float my_p = 0.f;
+            for (int j = 0; j < K; ++j) {
+                const float m = wave_max(fmaxf(m0, m1));
+                const unsigned long long b0 = __ballot(m0 == m), b1 = __ballot(m1 == m);
+                const int e = b0 ? __ffsll((long long)b0) - 1 : 63 + __ffsll((long long)b1);
+                const float pe = __shfl(e < 64 ? p0 : p1, e & 63, 64);
+                if (lane == j) { my_e = e; my_p = pe; }
+                if (e == lane) { sel0 = true; m0 = NEG_INF; }
+                if (e == lane + 64) { sel1 = true; m1 = NEG_INF; }
+            }
+            float wgt = my_p;
+            if (renorm) wgt = my_p / wave_sum(lane < K ? my_p : 0.f);
+            if (lane < K) {
+                out_idx[(s * T + t) * K + lane] = my_e;
+                out_w[(s * T + t) * K + lane] = wgt;
+            }
+            // LRU: misses against the state before the step, then the chosen experts become the most recent
+            const int miss = __popcll(__ballot(sel0 && !res0)) + __popcll(__ballot(sel1 && !res1));
+            const uint32_t stamp = ((uint32_t)(t + 1) << 7);
+            if (sel0) key0 = stamp | (uint32_t)lane;
+            if (sel1) key1 = stamp | (uint32_t)(lane + 64);
+            res0 |= sel0;
+            res1 |= sel1;
+            int held = __popcll(__ballot(res0)) + __popcll(__ballot(res1));
+            while (held > C) {
+                const uint32_t b0 = res0 ? key0 : CP_NONE, b1 = res1 ? key1 : CP_NONE;
+                const uint32_t mk = wave_min_u32(b0 < b1 ? b0 : b1);
+                if (res0 && key0 == mk) res0 = false;
+                if (res1 && key1 == mk) res1 = false;
+                --held;
+            }
+            if (lane == 0) out_miss[s * T + t] = (uint8_t)miss;
+            total += (unsigned long long)miss;
+        }
+    }
+    if (lane == 0) out_total_miss[s] = total;
+}
+
 // ---- per-step sums over layers, histogram, percentiles -----------------------------------------------
 constexpr int SS_MAX_HIST = 4097;       // sums up to 64 layers x 64 experts
 
@@ -317,6 +399,15 @@ remoe_status launch_cache_policy(const int32_t *idx, int64_t S, int64_t T, int K
         return fail(REMOE_E_INVALID_ARG, "unknown cache policy %d", policy);
     }
     return check_hip(hipGetLastError(), "cache_policy_kernel launch");
+}
+
+remoe_status launch_reroute(const float *probs, int64_t S, int64_t T, int N, int K, int C, float factor, int renorm,
+                            int32_t *idx, float *w, uint8_t *miss, uint64_t *total_miss, hipStream_t stream)
+{
+    if (S == 0) return REMOE_OK;
+    hipLaunchKernelGGL(reroute_kernel, dim3((unsigned)S), dim3(64), 0, stream, probs, T, N, K, C, factor, renorm, idx, w, miss,
+                       reinterpret_cast<unsigned long long *>(total_miss));
+    return check_hip(hipGetLastError(), "reroute_kernel launch");
 }
 
 int step_summary_max_hist() { return SS_MAX_HIST; }

@@ -148,6 +148,8 @@ remoe_status launch_cache_policy(const int32_t *idx, int64_t S, int64_t T, int K
                                  uint64_t expert_bytes, uint8_t *miss, uint8_t *uniq, uint8_t *hit_tok,
                                  uint64_t *total_miss, uint64_t *total_uniq, uint64_t *bytes, void *workspace,
                                  hipStream_t stream);
+remoe_status launch_reroute(const float *probs, int64_t S, int64_t T, int N, int K, int C, float factor, int renorm,
+                            int32_t *idx, float *w, uint8_t *miss, uint64_t *total_miss, hipStream_t stream);
 int step_summary_max_hist();
 remoe_status launch_step_summary(const uint8_t *miss, int64_t L, int64_t S, int64_t T, uint16_t *out_all,
                                  uint64_t *hist, int hist_len, int32_t *pct, hipStream_t stream);

@@ -151,3 +151,60 @@ def test_balance_matches_oracle(S, T, K, N, skew):
     rload, rused, rent, rcv = oracle.balance(idx, N)
     assert torch.equal(load.cpu().to(torch.int64), rload) and torch.equal(used.cpu(), rused)
     assert torch.allclose(ent.cpu(), rent, rtol=1e-12, atol=1e-14) and torch.allclose(cv.cpu(), rcv, rtol=1e-12, atol=1e-14)
+
+
+def _probs(seed, S, T, N, temp=2.0):
+    g = torch.Generator().manual_seed(seed)
+    return torch.softmax(torch.randn(S, T, N, generator=g) * temp, -1).float().contiguous()
+
+
+@pytest.mark.parametrize("S,T,N,K,C,factor,renorm", [
+    (3, 40, 8, 2, 3, 1.0, False),          # no bonus: the plain router
+    (4, 130, 64, 6, 4, 2.718281828, False),   # DeepSeek-V2-Lite shape, C = 4 < K as in the appendix, beta = 1
+    (2, 200, 128, 8, 32, 7.389056099, True),  # Qwen3 shape, beta = 2, renormalised weights
+    (3, 77, 60, 4, 12, 54.59815003, False),   # beta = 4
+    (2, 50, 16, 16, 16, 3.0, True),        # K = N
+    (2, 9, 5, 1, 1, 1e12, False),          # overwhelming bonus
+])
+def test_reroute_matches_oracle(S, T, N, K, C, factor, renorm):
+    _say(f"reroute S={S} T={T} N={N} K={K} C={C} factor={factor}")
+    p = _probs(S * T + N, S, T, N)
+    idx = torch.full((S, T, K), -1, dtype=torch.int32, device=DEV)
+    w = torch.zeros(S, T, K, dtype=torch.float32, device=DEV)
+    miss = torch.full((S, T), 255, dtype=torch.uint8, device=DEV)
+    tot = torch.full((S,), -1, dtype=torch.int64, device=DEV)
+    remoe.reroute_lru(p.to(DEV), K, C, factor, renorm, idx, w, miss, tot)
+    torch.cuda.synchronize()
+    ref = oracle.reroute_lru(p, K, C, factor, renorm)
+    assert torch.equal(idx.cpu(), ref["idx"]) and torch.equal(miss.cpu(), ref["miss"])
+    assert torch.equal(tot.cpu(), ref["total_miss"])
+    assert torch.allclose(w.cpu().double(), ref["w"], rtol=2e-6, atol=1e-12)
+
+
+def test_reroute_of_router_probabilities_end_to_end():
+    """moe_route's full probabilities fed to reroute_lru: with factor 1 the rerouted ids are the router's own
+    and the misses are those of lru_simulate on them."""
+    H, N, K, C, S, T = 256, 64, 6, 8, 2, 64
+    x = wl.ar1_hidden_states(3, S, T, H, 0.8, torch.float32, DEV).reshape(S * T, H).contiguous()
+    wr = wl.gaussian(3, "w_router", (N, H), 0.05, 0, 0, torch.float32, DEV)
+    desc = remoe.LayerDesc(H, N, 64, K, 0, 0, 0, 0)
+    ridx = torch.empty(S * T, K, dtype=torch.int32, device=DEV)
+    rw = torch.empty(S * T, K, dtype=torch.float32, device=DEV)
+    probs = torch.empty(S * T, N, dtype=torch.float32, device=DEV)
+    remoe.moe_route(desc, x, wr, ridx, rw, None, probs)
+    idx = torch.empty(S, T, K, dtype=torch.int32, device=DEV)
+    w = torch.empty(S, T, K, dtype=torch.float32, device=DEV)
+    miss = torch.empty(S, T, dtype=torch.uint8, device=DEV)
+    tot = torch.empty(S, dtype=torch.int64, device=DEV)
+    remoe.reroute_lru(probs.view(S, T, N), K, C, 1.0, False, idx, w, miss, tot)
+    lmiss = torch.empty(S, T, dtype=torch.uint8, device=DEV)
+    ltot = torch.empty(S, dtype=torch.int64, device=DEV)
+    lb = torch.empty(S, dtype=torch.int64, device=DEV)
+    remoe.lru_simulate(ridx.view(S, T, K), N, C, 1, 0, None, lmiss, ltot, lb)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.sort(idx.cpu(), -1).values, torch.sort(ridx.view(S, T, K).cpu(), -1).values)
+    assert torch.equal(miss.cpu(), lmiss.cpu()) and torch.equal(tot.cpu(), ltot.cpu())
+    # a bonus can only be tried on the same probabilities: it must not lose to no bonus here
+    remoe.reroute_lru(probs.view(S, T, N), K, C, 20.0, False, idx, w, miss, tot)
+    torch.cuda.synchronize()
+    assert int(tot.sum()) < int(ltot.sum())

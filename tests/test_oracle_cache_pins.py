@@ -198,3 +198,50 @@ def test_balance_matches_numpy():
         assert load[s].tolist() == c.astype(int).tolist() and int(used[s]) == int((c > 0).sum())
         assert abs(float(ent[s]) - float(-(p * np.log(p)).sum() / np.log(20))) < 1e-14
         assert abs(float(cv[s]) - float(c.std() / c.mean())) < 1e-14
+
+
+# ---- cache-aware rerouting (App. G) -----------------------------------------------------------------
+def _probs(seed, S, T, N):
+    g = torch.Generator().manual_seed(seed)
+    return torch.softmax(torch.randn(S, T, N, generator=g) * 2.0, -1).float().contiguous()
+
+
+@pytest.mark.parametrize("K,N,C", [(2, 8, 3), (6, 64, 16), (8, 128, 32)])
+def test_reroute_without_bonus_is_plain_topk_and_lru(K, N, C):
+    p = _probs(K, 3, 60, N)
+    o = oracle.reroute_lru(p, K, C, 1.0, False)
+    want = torch.sort(torch.topk(p, K, dim=-1).indices, -1).values
+    assert torch.equal(torch.sort(o["idx"].long(), -1).values, want)
+    miss, tot, _ = oracle.lru_list(o["idx"], N, C, 0)
+    assert torch.equal(o["miss"], miss) and torch.equal(o["total_miss"], tot)
+    assert torch.allclose(o["w"], torch.gather(p.double(), -1, o["idx"].long()))
+
+
+def test_reroute_with_overwhelming_bonus_locks_onto_the_cache():
+    """When the bonus outweighs every score gap and C >= K, every step after the first is served from the cache:
+    K cold misses and none afterwards; with renormalisation the gate weights still sum to one."""
+    K, N, C = 4, 32, 6
+    p = _probs(9, 2, 50, N).clamp_min(1e-6)
+    p = (p / p.sum(-1, keepdim=True)).float()
+    o = oracle.reroute_lru(p, K, C, 1e12, True)
+    assert o["miss"][:, 0].tolist() == [K, K] and int(o["miss"][:, 1:].sum()) == 0
+    assert o["total_miss"].tolist() == [K, K]
+    assert torch.allclose(o["w"].sum(-1), torch.ones(2, 50, dtype=torch.float64))
+    # the resident set can only ever be the first step's choice, so every later step repeats that set
+    first = torch.sort(o["idx"][:, :1], -1).values
+    assert torch.equal(torch.sort(o["idx"], -1).values, first.expand(-1, 50, -1))
+
+
+def test_reroute_hand_worked():
+    # N = 4, K = 1, C = 1, factor 3: step 0 picks 0 (0.5); step 1 scores (0.2*3, 0.5, ..) = 0.6 > 0.5 keeps 0;
+    # step 2 scores (0.1*3, 0.6, ..) = 0.3 < 0.6 switches to 1 (miss); step 3 ties 0.3*... : (0.3, 0.1*3=0.3) -> lower id 0 wins
+    p = torch.tensor([[[0.5, 0.3, 0.1, 0.1], [0.2, 0.5, 0.2, 0.1], [0.1, 0.6, 0.2, 0.1], [0.3, 0.1, 0.3, 0.3]]])
+    o = oracle.reroute_lru(p.float(), 1, 1, 3.0, False)
+    assert o["idx"][0, :, 0].tolist() == [0, 0, 1, 0]
+    assert o["miss"][0].tolist() == [1, 0, 1, 1]
+
+
+def test_reroute_bonus_raises_hits_on_average():
+    p = _probs(21, 8, 200, 64)
+    tot = [int(oracle.reroute_lru(p, 6, 8, f, False)["total_miss"].sum()) for f in (1.0, 2.0, 8.0, 64.0)]
+    assert tot[0] > tot[1] > tot[2] > tot[3]
