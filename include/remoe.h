@@ -333,6 +333,34 @@ remoe_status reroute_lru(const float *probs, int64_t n_seq, int64_t n_steps, int
                          int32_t capacity, float factor, int32_t renorm, int32_t *out_idx, float *out_w,
                          uint8_t *out_miss, uint64_t *out_total_miss, void *stream);
 
+/*
+ * remoe_loss_forward -- forward values of the router regularisers ReMoE trains with (Sec. 4.2-4.4),
+ * per sequence, from the routing distributions of the trainable router (probs), of the frozen
+ * snapshot router (probs_ref) and the routed sets (idx; the previous step's set is a constant of
+ * the reuse mass):
+ *
+ *   out[s, 0] rho      = mean_{t>=2} m_t,  m_t = (1/K) sum_{k in E_{t-1}} P_t[k]          (Eq. 2, 7)
+ *   out[s, 1] L_Reuse  = -log(rho + 1e-8)                                                 (Eq. 7)
+ *   out[s, 2] L_Trust  = mean_t KL(P_t || P_t^ref)                                        (Eq. 5)
+ *   out[s, 3] L_Smooth = mean_{t>=2} SymKL(P_t, P_{t-1})                                  (Eq. 9)
+ *   out[s, 4] L_Lag    = mean_{t>=2} (1/|D|) sum_{d in D, t-d>=1} SymKL(P_t, P_{t-d})     (Eq. 10)
+ *   out[s, 5] L_WS     = mean over the floor(T/W) windows of H(window mean of P)          (Eq. 12)
+ *
+ * The weighted sums L_Loc (Eq. 6) and L (Eq. 3) and the warm-up factor are left to the caller.
+ * Conventions: 0 log 0 = 0; a sequence of one step has rho = 0 and no smoothness / lag term; no
+ * full window gives L_WS = 0.  Computed in fp64 from the fp32 probabilities.
+ *
+ *   probs, probs_ref [S, T, N_r] fp32 (out_probs of moe_route with the two gate matrices);
+ *   idx [S, T, K] int32; lags HOST array of n_lags (0..8) positive lags D; window W >= 1;
+ *   out [S, 6] double; workspace remoe_loss_workspace_bytes(S) bytes, 8-byte aligned.
+ *   n_experts <= 128, top_k <= 64, S <= 65535.
+ */
+size_t remoe_loss_workspace_bytes(int64_t n_seq);
+remoe_status remoe_loss_forward(const float *probs, const float *probs_ref, const int32_t *idx,
+                                int64_t n_seq, int64_t n_steps, int32_t n_experts, int32_t top_k,
+                                const int32_t *lags, int32_t n_lags, int32_t window, double *out,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

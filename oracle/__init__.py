@@ -53,6 +53,9 @@ def lib() -> ctypes.CDLL:
         _lib.oracle_reroute_lru.restype = _c_int
         _lib.oracle_reroute_lru.argtypes = [_c_ptr, _c_i64, _c_i64, _c_int, _c_int, _c_int, ctypes.c_float, _c_int,
                                             _c_ptr, _c_ptr, _c_ptr, _c_ptr]
+        _lib.oracle_remoe_losses.restype = _c_int
+        _lib.oracle_remoe_losses.argtypes = [_c_ptr, _c_ptr, _c_ptr, _c_i64, _c_i64, _c_int, _c_int, _c_ptr, _c_int,
+                                             _c_int, _c_ptr]
     return _lib
 
 
@@ -248,4 +251,21 @@ def reroute_lru(probs: torch.Tensor, top_k: int, capacity: int, factor: float, r
                                   _p(out["w"]), _p(out["miss"]), _p(out["total_miss"]))
     if rc != 0:
         raise ValueError(f"oracle_reroute_lru failed ({rc})")
+    return out
+
+
+LOSS_NAMES = ("rho", "reuse", "trust", "smooth", "lag", "ws")
+
+
+def remoe_losses(probs: torch.Tensor, probs_ref: torch.Tensor, idx: torch.Tensor, lags: Sequence[int], window: int):
+    """Forward values of ReMoE's router regularisers (Eq. 2-12) per sequence: fp64 [S, 6] in the order of
+    LOSS_NAMES.  probs, probs_ref fp32 [S, T, N]; idx int32 [S, T, K]."""
+    probs, probs_ref, idx = _chk(probs, torch.float32), _chk(probs_ref, torch.float32), _chk(idx, torch.int32)
+    S, T, N = probs.shape
+    lg = torch.tensor(list(lags), dtype=torch.int32)
+    out = torch.zeros(S, 6, dtype=torch.float64)
+    rc = lib().oracle_remoe_losses(_p(probs), _p(probs_ref), _p(idx), S, T, N, idx.shape[2], _p(lg), len(lags), window,
+                                   _p(out))
+    if rc != 0:
+        raise ValueError(f"oracle_remoe_losses failed ({rc})")
     return out

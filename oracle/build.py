@@ -4,7 +4,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRCS = [os.path.join(HERE, n) for n in ("remoe_oracle.c", "remoe_oracle_cache.c")]
+SRCS = [os.path.join(HERE, n) for n in ("remoe_oracle.c", "remoe_oracle_cache.c", "remoe_oracle_loss.c")]
 LIB = os.path.join(HERE, "liboracle.so")
 
 

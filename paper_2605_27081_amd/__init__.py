@@ -28,6 +28,8 @@ from .binding import (  # noqa: F401
     moe_route,
     PROF_KINDS,
     remoe_last_error,
+    remoe_loss_forward,
+    remoe_loss_workspace_bytes,
     remoe_profile_enable,
     remoe_profile_read,
     remoe_version,

@@ -88,6 +88,10 @@ def load_library() -> ctypes.CDLL:
     lib.routing_balance.argtypes = [P, I64, I64, I32, I32, P, P, P, P, P]
     lib.reroute_lru.restype = ctypes.c_int
     lib.reroute_lru.argtypes = [P, I64, I64, I32, I32, I32, ctypes.c_float, I32, P, P, P, P, P]
+    lib.remoe_loss_workspace_bytes.restype = SZ
+    lib.remoe_loss_workspace_bytes.argtypes = [I64]
+    lib.remoe_loss_forward.restype = ctypes.c_int
+    lib.remoe_loss_forward.argtypes = [P, P, P, I64, I64, I32, I32, ctypes.POINTER(I32), I32, I32, P, P, SZ, P]
     _lib = lib
     return lib
 
@@ -243,3 +247,17 @@ def reroute_lru(probs: torch.Tensor, top_k: int, capacity: int, factor: float, r
     n_seq, n_steps, n_experts = probs.shape
     _check(load_library().reroute_lru(_ptr(probs), n_seq, n_steps, n_experts, top_k, capacity, factor, int(renorm),
                                       _ptr(out_idx), _ptr(out_w), _ptr(out_miss), _ptr(out_total_miss), _stream()))
+
+
+def remoe_loss_workspace_bytes(n_seq: int) -> int:
+    return int(load_library().remoe_loss_workspace_bytes(n_seq))
+
+
+def remoe_loss_forward(probs: torch.Tensor, probs_ref: torch.Tensor, idx: torch.Tensor, lags, window: int,
+                       out: torch.Tensor, workspace: torch.Tensor) -> None:
+    """probs, probs_ref fp32 [S, T, N]; idx int32 [S, T, K]; out fp64 [S, 6] (rho, reuse, trust, smooth, lag, ws)."""
+    n_seq, n_steps, n_experts = probs.shape
+    lg = (ctypes.c_int32 * max(len(lags), 1))(*lags)
+    _check(load_library().remoe_loss_forward(_ptr(probs), _ptr(probs_ref), _ptr(idx), n_seq, n_steps, n_experts,
+                                             idx.shape[2], lg, len(lags), window, _ptr(out), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream()))

@@ -513,5 +513,26 @@ remoe_status reroute_lru(const float *probs, int64_t n_seq, int64_t n_steps, int
                           out_total_miss, static_cast<hipStream_t>(stream));
 }
 
+size_t remoe_loss_workspace_bytes(int64_t n_seq) { return n_seq < 0 ? 0 : loss_workspace_bytes(n_seq); }
+
+remoe_status remoe_loss_forward(const float *probs, const float *probs_ref, const int32_t *idx, int64_t n_seq,
+                                int64_t n_steps, int32_t n_experts, int32_t top_k, const int32_t *lags, int32_t n_lags,
+                                int32_t window, double *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    remoe_status st = validate_trace(idx, n_seq, n_steps, top_k, n_experts);
+    if (st != REMOE_OK) return st;
+    if (n_lags < 0 || n_lags > 8 || (n_lags > 0 && !lags)) return fail(REMOE_E_INVALID_ARG, "n_lags %d outside 0..8 or lags is NULL", n_lags);
+    for (int i = 0; i < n_lags; ++i)
+        if (lags[i] < 1) return fail(REMOE_E_INVALID_ARG, "lag %d must be positive", lags[i]);
+    if (window < 1) return fail(REMOE_E_INVALID_ARG, "window %d must be positive", window);
+    if (n_seq == 0) return REMOE_OK;
+    if (!out || (n_steps > 0 && (!probs || !probs_ref))) return fail(REMOE_E_INVALID_ARG, "a required pointer is NULL");
+    const size_t need = loss_workspace_bytes(n_seq);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 7))
+        return fail(REMOE_E_WORKSPACE, "remoe_loss_forward needs an 8-byte aligned workspace of %zu bytes", need);
+    return launch_loss_forward(probs, probs_ref, idx, n_seq, n_steps, n_experts, top_k, lags, n_lags, window, out, workspace,
+                               static_cast<hipStream_t>(stream));
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

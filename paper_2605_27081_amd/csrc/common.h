@@ -156,6 +156,12 @@ remoe_status launch_step_summary(const uint8_t *miss, int64_t L, int64_t S, int6
 remoe_status launch_balance(const int32_t *idx, int64_t S, int64_t T, int K, int N, uint32_t *load, int32_t *used,
                             double *entropy, double *cv, hipStream_t stream);
 
+// ReMoE's router regularisers, forward values.
+size_t loss_workspace_bytes(int64_t S);
+remoe_status launch_loss_forward(const float *probs, const float *probs_ref, const int32_t *idx, int64_t S, int64_t T,
+                                 int N, int K, const int32_t *lags, int n_lags, int window, double *out, void *workspace,
+                                 hipStream_t stream);
+
 // Plain copy of known size (yardstick for hardware byte counters).
 remoe_status launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t stream);
 
