@@ -312,7 +312,8 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             }                                                                                       \
         }                                                                                           \
     }
-    // staging array st -> global memory, 16 bytes per lane
+    // staging array st -> global memory, 16 bytes per lane (non-temporal: the output is not read again by
+    // this kernel and should not push operand lines out of the L2)
 #define GM_EPI_STORE(mi, st, e_row0, e_rows, e_nt)                                                  \
     _Pragma("unroll") for (int j = 0; j < 64 * CPR / THREADS; ++j) {                                 \
         const int q2 = tid + THREADS * j;                                                           \
@@ -323,7 +324,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         const int m = ((R >> 5) * TM + (mi)) * 32 + row;                                            \
         const int col = (e_nt) * BN_OUT + ch * 8;                                                   \
         if (m < (e_rows) && col < p.n_out)                                                          \
-            *reinterpret_cast<u32x4_t *>(p.c + (p.c_row_offset + (e_row0) + m) * p.ldc + col) = v;  \
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(p.c + (p.c_row_offset + (e_row0) + m) * p.ldc + col)); \
     }
 #define GM_EPI_BAND(mi, st, e_row0, e_rows, e_nt, e_par)                                            \
     GM_EPI_STAGE(mi, st, e_par)                                                                     \
