@@ -18,8 +18,10 @@ constexpr int DEC_FLAG_BYTES = 256 + DEC_MAX_GRID * 4;   // abort flag at byte 1
 constexpr int DEC_SEG = 256;            // router row segment per wavefront (floats)
 constexpr int DEC_RING = 4;             // layer-steps whose exchanged values are kept apart (pipelined kernel)
 
-// Workspace: flags, then DEC_RING slots of tagged partial logits, then DEC_RING slots of tagged
-// SwiGLU activations.  The chained kernel uses the first slot of each region.
+constexpr int DEC_GROUPS = 8;           // workgroup groups of the pipelined kernel, each with its own rings
+
+// Workspace: flags, then per group DEC_RING slots of tagged partial logits, then per group DEC_RING
+// slots of tagged SwiGLU activations.  The chained kernel uses the first slot of each region.
 struct DecodeWsLayout {
     size_t logit_off, h_off, total;
     int n_logit, n_h;                   // 8-byte words per ring slot
@@ -30,8 +32,8 @@ inline DecodeWsLayout decode_ws_layout(int H, int N, int I, int K)
     l.n_logit = N * (H / DEC_SEG);
     l.n_h = K * I > DEC_MAX_GRID * 8 ? K * I : DEC_MAX_GRID * 8;   // chained: K*I floats; pipelined: one word per wavefront
     l.logit_off = DEC_FLAG_BYTES;
-    l.h_off = l.logit_off + align_up(sizeof(unsigned long long) * (size_t)DEC_RING * l.n_logit, 256);
-    l.total = l.h_off + align_up(sizeof(unsigned long long) * (size_t)DEC_RING * l.n_h, 256);
+    l.h_off = l.logit_off + align_up(sizeof(unsigned long long) * (size_t)DEC_GROUPS * DEC_RING * l.n_logit, 256);
+    l.total = l.h_off + align_up(sizeof(unsigned long long) * (size_t)DEC_GROUPS * DEC_RING * l.n_h, 256);
     return l;
 }
 

@@ -1,31 +1,35 @@
-// M = 1 decode with the layers of a step overlapped (software pipeline over layers).
+// M = 1 decode with the layers of a step overlapped: one layer per XCD at a time, software pipeline
+// over each XCD's layers.
 //
 // Per layer-step the work is the same as in the layer-chained kernel: the fp32 router matrix and the
 // three matrices of the K selected experts are streamed once from HBM (Sec. 3.1 routing; the B = 1
-// regime of Sec. 3), about one flop per byte.  What differs is the order.  Every layer of a step reads
-// the same input row, so the layers of one step do not depend on each other, and the two exchanges a
-// layer needs between workgroups (all partial logits before the top-k, all SwiGLU activations before
-// the down projection) can each be given a whole pipeline stage to arrive instead of a grid barrier:
+// regime of Sec. 3), about one flop per byte.  What differs is who works on what, and when.  Every
+// layer of a step reads the same input row, so the layers of one step do not depend on each other:
 //
-//   iteration i of a step:   R(i)    partial router logits of layer i            -> published, tagged
-//                            T(i-1)  top-k / softmax of layer i-1 from the logits published an iteration
-//                                    ago (one wavefront per workgroup, off the others' critical path)
-//                            G(i-2)  gate/up rows of layer i-2's experts, SwiGLU  -> published, tagged
-//                            D(i-4)  down projection of layer i-4 from the activations published two
-//                                    iterations ago
+//   * The workgroups are split into 8 groups (workgroup b belongs to group b % 8: with round-robin
+//     dispatch that is one XCD per group).  Group x owns layers x, x + 8, x + 16, ...  A layer-step is
+//     therefore spread over 32 compute units instead of 256: eight times more bytes per exchange
+//     between workgroups, so the fixed cost of those exchanges is amortised eight times better.
+//   * Inside a group the two exchanges a layer needs (all partial logits before the top-k, all SwiGLU
+//     activations before the down projection) are each given a pipeline stage to arrive instead of a
+//     barrier.  Iteration i of a step works on the group's layers number
+//         R(i)    partial router logits                                   -> published, tagged
+//         T(i-1)  top-k / softmax from the logits published an iteration ago (one wavefront per
+//                 workgroup, in turn; the result is used from the next iteration on)
+//         G(i-2)  gate/up rows of the selected experts, SwiGLU            -> published, tagged
+//         D(i-4)  down projection from the activations published two iterations ago
 //
-// Exchanged values carry the number of the layer-step that produced them (one 8-byte word), so a
-// reader needs no barrier: it polls (agent-scope loads, which bypass the per-XCD L2 and its stale
-// copies) until the tags match, and in steady state they already do.  The
-// polls and the weight loads of the next iteration are issued before the last activation of the
-// current one is reduced, so HBM keeps streaming across iterations.  Steps stay strictly sequential:
-// a grid barrier closes every step (the statistics of step t+1 need those of step t, and a decoder
-// would need the step's output before it has the next input).
-//
-// A wavefront's (up to three) SwiGLU activations travel as one 8-byte word: three bf16 values and a
-// 16-bit tag.  bf16 is what the batched path stores between its two GEMMs as well; it lets both the
-// gate/up and the down products run as packed bf16 dot instructions (v_dot2_f32_bf16: exact products,
-// fp32 accumulation) against x and h kept in bf16 in LDS.
+// Exchanged values carry the number of the layer-step that produced them (partial logits: fp32 and a
+// 32-bit tag; three SwiGLU activations of one wavefront: 3 x bf16 and a 16-bit tag, one 8-byte word),
+// so a reader needs no barrier: it polls (agent-scope loads, which bypass the per-XCD L2 and its stale
+// copies) until the tags match, and in steady state they already do; a missing word is asked for
+// again by the wavefront that needs it.  The polls and the first weight rows of the next iteration
+// are issued before the last activation of the current one is reduced, so HBM keeps streaming across
+// iterations.  bf16 activations are what the batched path stores between its two GEMMs as well; they
+// let the gate/up and the down products run as packed bf16 dot instructions (exact products, fp32
+// accumulation) against x and h kept in bf16 in LDS.  Steps stay strictly sequential: a grid barrier
+// over all workgroups closes every step (the statistics of step t+1 need those of step t, and a
+// decoder would need the step's output before it has the next input).
 //
 // One workgroup of 8 wavefronts per compute unit; every wait is bounded as in the chained kernel.
 #include "common.h"
@@ -38,11 +42,13 @@ namespace {
 
 constexpr int DP_THREADS = DEC_THREADS;
 constexpr int DP_WAVES = DP_THREADS / 64;
+constexpr int DP_GROUPS = DEC_GROUPS; // groups of workgroups, each on its own layers (one per XCD)
 constexpr int DP_MAX_KI = 6144;      // K * I activations of one layer
 constexpr int DP_MAX_DCH = 12;       // down-projection 16-byte chunks per lane per output row
 constexpr int DP_POLL_L = 4;         // tagged logit words per thread (N * H / 256 <= 2048)
-constexpr int DP_POLL_H = 4;         // activation words per thread (one word per wavefront, <= 2048)
-constexpr int DP_MAX_ITEMS = 3;      // gate/up activations per wavefront (they share one exchanged word)
+constexpr int DP_POLL_H = 4;         // activation words per thread (<= 2048 words per layer)
+constexpr int DP_MAX_R = 4;          // router segments per wavefront, fetched ahead
+constexpr int DP_SEL = 8;            // layers whose selection is kept (a layer's is used for 4 iterations)
 
 struct PipeArgs {
     const void *const *layers;   // [L][4] device pointers: w_router, w_gate, w_up, w_down
@@ -61,8 +67,8 @@ struct PipeArgs {
     unsigned long long *sum_overlap;
     unsigned long long *total_miss;
     unsigned long long *bytes_fetched;
-    unsigned long long *logit_ring;   // [DEC_RING][N * H / 256]  (tag << 32) | float bits
-    unsigned long long *h_ring;       // [DEC_RING][h_slot]: word w = wavefront w's activations, 3 x bf16 | tag16 << 48
+    unsigned long long *logit_ring;   // [groups][DEC_RING][N * H / 256]  (tag << 32) | float bits
+    unsigned long long *h_ring;       // [groups][DEC_RING][h_slot]: 3 x bf16 | tag16 << 48 per word
     int h_slot;                       // words per ring slot
     uint32_t *bar;
     uint32_t *abort_flag;
@@ -74,7 +80,8 @@ struct PipeArgs {
 #define DP_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
 // 16-bit tag of a layer-step (never 0, the value of a cleared word).  A ring slot is rewritten every
-// DEC_RING layer-steps, so a word 65535 layer-steps old cannot survive to be mistaken for a new one.
+// DEC_RING layers of its group, so a word 65535 layer-steps old cannot survive to be mistaken for a
+// new one.
 __device__ __forceinline__ uint32_t tag16(uint32_t tag) { return tag % 65535u + 1u; }
 
 __device__ __forceinline__ unsigned long long poll_word(const unsigned long long *p)
@@ -88,62 +95,63 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
     __shared__ __attribute__((aligned(16))) bf16_t hl[2][DP_MAX_KI];   // activations of two layers (bf16)
     __shared__ __attribute__((aligned(16))) bf16_t xs[4096];           // the step's input row
     __shared__ float lpart[2][128 * 16]; // partial logits of the layer being ranked (two iterations apart)
-    __shared__ int sel_e[DEC_RING][8];     // selections of the last DEC_RING layers: written by the wavefront on
-    __shared__ float sel_w[DEC_RING][8];   // top-k duty, read by everyone from the next iteration on
+    __shared__ int sel_e[DP_SEL][8];     // selections of the group's last DP_SEL layers: written by the wavefront
+    __shared__ float sel_w[DP_SEL][8];   // on top-k duty, read by everyone from the next iteration on
     __shared__ int behind_lds;           // set when a wait ran out: the workgroup returns
     __shared__ int bar_ok;
     __shared__ TraceLds ts;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int G = gridDim.x;
-    const int W = G * DP_WAVES;
-    const int gw = blockIdx.x * DP_WAVES + wave;
+    const int NG = (G % DP_GROUPS == 0) ? DP_GROUPS : 1;   // groups
+    const int group = blockIdx.x % NG;
+    const int gr = blockIdx.x / NG;                      // this workgroup's rank in its group
+    const int GS = G / NG;                               // workgroups per group
+    const int W = GS * DP_WAVES;                         // wavefronts per group
+    const int gw = gr * DP_WAVES + wave;                 // this wavefront's index in its group
     const int H = a.H, N = a.N, I = a.I, K = a.K, L = a.n_layers;
     const int segs = H / DEC_SEG;
     const int KI = K * I;
     const int n_items1 = N * segs;
-    const int items_per_wave = (KI + W - 1) / W;          // <= DP_MAX_ITEMS (checked by the launcher)
+    const int ipw = (KI + W - 1) / W;                    // activations per wavefront
+    const int wpw = (ipw + 2) / 3;                       // exchange words per wavefront (3 activations each)
+    const int n_words = W * wpw;                         // <= DP_POLL_H * DP_THREADS (checked by the launcher)
     const int rows_per_wave = (H + W - 1) / W;
     const int dchunks = KI / 8;
     const int chunks_per_row = I / 8;
-    const bool stats_wave = blockIdx.x == G - 1 && wave == DP_WAVES - 1;
+    const int n_mine = group < L ? (L - group + NG - 1) / NG : 0;      // layers group, group + NG, ...
+    const bool stats_wave = gr == GS - 1 && wave == DP_WAVES - 1;
+    unsigned long long *const logit_ring = a.logit_ring + (size_t)group * DEC_RING * n_items1;
+    unsigned long long *const h_ring = a.h_ring + (size_t)group * DEC_RING * a.h_slot;
     uint32_t bar_phase = 0;
 
-    if (blockIdx.x == G - 1) {
-        for (int q = tid; q < L * 128; q += DP_THREADS) {
-            const int l = q >> 7, e = q & 127;
+    if (gr == GS - 1) {                                  // trace state of this group's layers -> LDS
+        for (int q = tid; q < n_mine * 128; q += DP_THREADS) {
+            const int l = group + NG * (q >> 7), e = q & 127;
             ts.last[l][e] = (e < N) ? a.lru_state[l * N + e] : 0u;
         }
-        for (int q = tid; q < L; q += DP_THREADS) {
-            ts.sum_ov[q] = a.sum_overlap[q];
-            for (int c = 0; c < a.n_caps; ++c) ts.tot[c][q] = a.total_miss[c * L + q];
+        for (int q = tid; q < n_mine; q += DP_THREADS) {
+            const int l = group + NG * q;
+            ts.sum_ov[l] = a.sum_overlap[l];
+            for (int c = 0; c < a.n_caps; ++c) ts.tot[c][l] = a.total_miss[c * L + l];
         }
     }
     if (tid == 0) behind_lds = 0;
     __syncthreads();
 
-    // ---- per-wavefront constants: which activations, which output row, which router segment ----------
-    const int item0 = gw * items_per_wave;
+    // ---- per-wavefront constants ---------------------------------------------------------------------
+    const int item0 = gw * ipw;
     int nit = KI - item0;
-    if (nit > items_per_wave) nit = items_per_wave;
+    if (nit > ipw) nit = ipw;
     if (nit < 0) nit = 0;
-    int it_j[DP_MAX_ITEMS], it_i[DP_MAX_ITEMS];          // (expert slot, intermediate index) of each activation
-#pragma unroll
-    for (int u = 0; u < DP_MAX_ITEMS; ++u) {
-        const int item = item0 + u;
-        const int j = (u < nit) ? item / I : 0;
-        it_j[u] = __builtin_amdgcn_readfirstlane(j);
-        it_i[u] = __builtin_amdgcn_readfirstlane((u < nit) ? item - j * I : 0);
-    }
     const int row_first = gw * rows_per_wave;
-    uint32_t d_pos[DP_MAX_DCH];                          // byte offset inside a down row | expert slot << 24
-#pragma unroll
-    for (int c = 0; c < DP_MAX_DCH; ++c) {
-        const int q = c * 64 + lane;
-        const int j = (q < dchunks) ? q / chunks_per_row : 0;
-        d_pos[c] = (uint32_t)(((q < dchunks) ? (q - j * chunks_per_row) * 16 : 0) | (j << 24));
-    }
-    const int r_e = gw / segs, r_k = (gw - r_e * segs) * DEC_SEG + lane * 4;   // first router work item
+    int n_rows = H - row_first;
+    if (n_rows > rows_per_wave) n_rows = rows_per_wave;
+    if (n_rows < 0) n_rows = 0;
+    // chunk q of a wavefront's down-row work is chunk q % chunks_per_row of expert slot q / chunks_per_row;
+    // the quotient by multiplication (exact for q < 2^16, chunks_per_row <= 2^16)
+    const uint32_t cpr_magic = (uint32_t)((0x100000000ull + (unsigned)chunks_per_row - 1) / (unsigned)chunks_per_row);
+#define DP_SLOT_OF(q) ((int)__umulhi((uint32_t)(q), cpr_magic))
     const int loff = lane * 8;
 
 #pragma unroll 1
@@ -160,54 +168,59 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
 
         // registers that carry loads across the iteration boundary
         unsigned long long pl[DP_POLL_L], ph[DP_POLL_H];
-        u32x4_t dv[DP_MAX_DCH];
-        floatx4_t wr = {0.f, 0.f, 0.f, 0.f};
+        u32x4_t dvA[DP_MAX_DCH], dvB[DP_MAX_DCH];
+
+        // one down-projection row of this wavefront (row_first + rw) of layer number md_ -> dv
+#define DP_LOAD_DROW(dv, md_, rw)                                                                     \
+    {                                                                                                 \
+        int lane_ = threadIdx.x & 63;                                                                 \
+        asm volatile("" : "+v"(lane_));   /* offsets are recomputed here, not kept in registers */     \
+        const char *wd_ = static_cast<const char *>(a.layers[(group + NG * (md_)) * 4 + 3]);          \
+        const int *se_ = sel_e[(md_) & (DP_SEL - 1)];                                                 \
+        _Pragma("unroll") for (int c = 0; c < DP_MAX_DCH; ++c) {                                       \
+            const int q_ = c * 64 + lane_;                                                            \
+            if (q_ < dchunks) {                                                                       \
+                const int j_ = DP_SLOT_OF(q_);                                                        \
+                const uint32_t off_ = (uint32_t)(((int64_t)se_[j_] * H + row_first + (rw)) * I * 2) + (uint32_t)(q_ - j_ * chunks_per_row) * 16u; \
+                dv[c] = load_global<u32x4_t>(wd_ + off_);                                             \
+            }                                                                                         \
+        }                                                                                             \
+    }
 
         // Loads of iteration `itn`: the polls first (loads return in order, so whatever is issued
-        // behind them does not delay them), then the down rows of layer itn-3 and the router segment
-        // of layer itn.
+        // behind them does not delay them), then the first down row of the layer it finishes.  (With a
+        // layer spread over one group an iteration is long; what is not fetched ahead costs little.)
 #define DP_ISSUE_ITER(itn)                                                                            \
     {                                                                                                 \
-        const int lT_ = (itn) - 1, lD_ = (itn) - 4;                                                   \
+        const int mT_ = (itn) - 1, mD_ = (itn) - 4;                                                   \
         int tid_ = threadIdx.x;                                                                       \
-        asm volatile("" : "+v"(tid_));   /* offsets are recomputed here, not kept in registers */      \
-        const int lane_ = tid_ & 63;                                                                  \
-        if (lT_ >= 0 && lT_ < L) {                                                                    \
-            const unsigned long long *src_ = a.logit_ring + (size_t)(lT_ & (DEC_RING - 1)) * n_items1; \
+        asm volatile("" : "+v"(tid_));                                                                \
+        if (mT_ >= 0 && mT_ < n_mine) {                                                               \
+            const unsigned long long *src_ = logit_ring + (size_t)(mT_ & (DEC_RING - 1)) * n_items1;  \
             _Pragma("unroll") for (int k = 0; k < DP_POLL_L; ++k) {                                    \
                 const int q_ = tid_ + k * DP_THREADS;                                                 \
                 if (q_ < n_items1) pl[k] = poll_word(src_ + q_);                                      \
             }                                                                                         \
         }                                                                                             \
-        if (lD_ >= 0) {                                                                               \
-            const unsigned long long *src_ = a.h_ring + (size_t)(lD_ & (DEC_RING - 1)) * a.h_slot;    \
+        if (mD_ >= 0) {                                                                               \
+            const unsigned long long *src_ = h_ring + (size_t)(mD_ & (DEC_RING - 1)) * a.h_slot;      \
             _Pragma("unroll") for (int k = 0; k < DP_POLL_H; ++k) {                                    \
                 const int q_ = tid_ + k * DP_THREADS;                                                 \
-                if (q_ * items_per_wave < KI) ph[k] = poll_word(src_ + q_);                           \
+                if (q_ < n_words) ph[k] = poll_word(src_ + q_);                                       \
             }                                                                                         \
         }                                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                            \
-        if (lD_ >= 0 && row_first < H) {                                                              \
-            const char *wd_ = static_cast<const char *>(a.layers[lD_ * 4 + 3]);                       \
-            const int *se_ = sel_e[lD_ & (DEC_RING - 1)];                                             \
-            _Pragma("unroll") for (int c = 0; c < DP_MAX_DCH; ++c) {                                   \
-                if (c * 64 + lane_ < dchunks) {                                                       \
-                    const uint32_t off_ = (uint32_t)(((int64_t)se_[d_pos[c] >> 24] * H + row_first) * I * 2) + (d_pos[c] & 0xFFFFFFu); \
-                    dv[c] = load_global<u32x4_t>(wd_ + off_);                           \
-                }                                                                                     \
-            }                                                                                         \
-        }                                                                                             \
-        if ((itn) < L && gw < n_items1)                                                               \
-            wr = load_global<floatx4_t>(static_cast<const float *>(a.layers[(itn) * 4]) + (int64_t)r_e * H + r_k); \
+        if (mD_ >= 0 && n_rows > 0) DP_LOAD_DROW(dvA, mD_, 0)                                         \
         __builtin_amdgcn_sched_barrier(0);                                                            \
     }
 
-        DP_ISSUE_ITER(0)
+        if (n_mine > 0) DP_ISSUE_ITER(0)
 
 #pragma unroll 1
-        for (int it = 0; it < L + 4; ++it) {
-            const int lR = it, lT = it - 1, lG = it - 2, lD = it - 4;
-            const bool doR = lR < L, doT = lT >= 0 && lT < L, doG = lG >= 0 && lG < L, doD = lD >= 0;
+        for (int it = 0; it < (n_mine > 0 ? n_mine + 4 : 0); ++it) {
+            const int mR = it, mT = it - 1, mG = it - 2, mD = it - 4;      // layer numbers inside the group
+            const bool doR = mR < n_mine, doT = mT >= 0 && mT < n_mine, doG = mG >= 0 && mG < n_mine, doD = mD >= 0;
+            const int lR = group + NG * mR, lT = group + NG * mT, lG = group + NG * mG, lD = group + NG * mD;
 
             // ---- consume the polls: partial logits of layer lT, activations of layer lD.  A word whose
             // tag is not there yet (its producer is more than a pipeline stage behind) is asked for again
@@ -218,10 +231,10 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
                 asm volatile("" : "+v"(tid_c));
                 const uint32_t tg = tag0 + (uint32_t)lT;
                 const uint32_t td = tag16(tag0 + (uint32_t)lD);
-                const unsigned long long *srcl = a.logit_ring + (size_t)(lT & (DEC_RING - 1)) * n_items1;
-                const unsigned long long *srch = a.h_ring + (size_t)(lD & (DEC_RING - 1)) * a.h_slot;
+                const unsigned long long *srcl = logit_ring + (size_t)(mT & (DEC_RING - 1)) * n_items1;
+                const unsigned long long *srch = h_ring + (size_t)(mD & (DEC_RING - 1)) * a.h_slot;
                 float *dstl = lpart[it & 1];
-                bf16_t *dsth = hl[lD & 1];
+                bf16_t *dsth = hl[mD & 1];
                 uint32_t missing = 0;                  // bit k: logit word k, bit 8 + k: activation word k
                 unsigned long long t0 = 0;
                 bool timing = false;
@@ -239,12 +252,18 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
                     if (doD) {
 #pragma unroll
                         for (int k = 0; k < DP_POLL_H; ++k) {
-                            const int i0 = (tid_c + k * DP_THREADS) * items_per_wave;   // wavefront (tid_c + k*512)'s word
-                            if (i0 < KI && (!timing || (missing >> (8 + k) & 1))) {
-                                if ((uint32_t)(ph[k] >> 48) == td) {
+                            const int u = tid_c + k * DP_THREADS;         // word u: wavefront u / wpw, its word u % wpw
+                            if (u < n_words && (!timing || (missing >> (8 + k) & 1))) {
+                                const int wv = u / wpw, kk = u - wv * wpw;
+                                const int i0 = wv * ipw + 3 * kk;          // first activation in the word
+                                int nv = ipw - 3 * kk;                     // how many it holds
+                                if (nv > 3) nv = 3;
+                                if (nv > KI - i0) nv = KI - i0;
+                                if (nv <= 0) { missing &= ~(1u << (8 + k)); }
+                                else if ((uint32_t)(ph[k] >> 48) == td) {
                                     dsth[i0] = (bf16_t)ph[k];
-                                    if (items_per_wave > 1 && i0 + 1 < KI) dsth[i0 + 1] = (bf16_t)(ph[k] >> 16);
-                                    if (items_per_wave > 2 && i0 + 2 < KI) dsth[i0 + 2] = (bf16_t)(ph[k] >> 32);
+                                    if (nv > 1) dsth[i0 + 1] = (bf16_t)(ph[k] >> 16);
+                                    if (nv > 2) dsth[i0 + 2] = (bf16_t)(ph[k] >> 32);
                                     missing &= ~(1u << (8 + k));
                                 } else missing |= 1u << (8 + k);
                             }
@@ -269,39 +288,6 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             }
             DP_LDS_BARRIER();
             if (behind_lds) return;        // the grid is aborting (set by a wavefront whose wait ran out)
-
-            // ---- G(lG): request the first two activations' gate and up rows ---------------------------
-            u32x4_t gA[XCH], uA[XCH], gB[XCH], uB[XCH];
-            const bf16_t *w_gate = doG ? static_cast<const bf16_t *>(a.layers[lG * 4 + 1]) : nullptr;
-            const bf16_t *w_up = doG ? static_cast<const bf16_t *>(a.layers[lG * 4 + 2]) : nullptr;
-            const int *se_g = sel_e[lG & (DEC_RING - 1)];
-#define DP_LOAD_ITEM(gv, uv, u)                                                                       \
-    {                                                                                                 \
-        const int e_ = __builtin_amdgcn_readfirstlane(se_g[it_j[u]]);                                 \
-        const bf16_t *gp_ = w_gate + ((int64_t)e_ * I + it_i[u]) * H;                                 \
-        const bf16_t *up_ = w_up + ((int64_t)e_ * I + it_i[u]) * H;                                   \
-        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
-            gv[c] = load_global<u32x4_t>(gp_ + loff + c * 512);                         \
-            uv[c] = load_global<u32x4_t>(up_ + loff + c * 512);                         \
-        }                                                                                             \
-    }
-#define DP_REDUCE_ITEM(gv, uv, u)                                                                     \
-    {                                                                                                 \
-        float gs_ = 0.f, us_ = 0.f;                                                                   \
-        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
-            const u32x4_t xq_ = *reinterpret_cast<const u32x4_t *>(&xs[(c * 64 + lane) * 8]);         \
-            gs_ = dot8_bf16(gv[c], xq_, gs_);                                                         \
-            us_ = dot8_bf16(uv[c], xq_, us_);                                                         \
-        }                                                                                             \
-        gs_ = wave_sum(gs_);                                                                          \
-        us_ = wave_sum(us_);                                                                          \
-        h_word |= (unsigned long long)f32_to_bf16(gs_ / (1.0f + expf(-gs_)) * us_) << (16 * (u));     \
-    }
-            const int nG = doG ? nit : 0;
-            unsigned long long h_word = (unsigned long long)tag16(tag0 + (uint32_t)lG) << 48;
-            if (nG > 0) DP_LOAD_ITEM(gA, uA, 0)
-            if (nG > 1) DP_LOAD_ITEM(gB, uB, 1)
-            __builtin_amdgcn_sched_barrier(0);
 
             // ---- T(lT): top-k and softmax of layer lT by the wavefront whose turn it is: K rounds of
             // wavefront maximum, ties to the lower id.  The result is first needed after the next
@@ -334,9 +320,9 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
                 float wgt = my_p / den;
                 if (a.renorm) wgt = my_p / wave_sum(my_p);
                 if (lane < K) {
-                    sel_e[lT & (DEC_RING - 1)][lane] = my_e;
-                    sel_w[lT & (DEC_RING - 1)][lane] = wgt;
-                    if (blockIdx.x == 0) {
+                    sel_e[mT & (DP_SEL - 1)][lane] = my_e;
+                    sel_w[mT & (DP_SEL - 1)][lane] = wgt;
+                    if (gr == 0) {
                         const int64_t o = ((int64_t)lT * a.steps_total + g) * K + lane;
                         a.out_idx[o] = my_e;
                         a.out_w[o] = wgt;
@@ -344,74 +330,146 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
                 }
             }
 
-            // ---- R(lR): this wavefront's router segment(s) -> tagged partial logits ---------------------
+            // ---- R(lR): this wavefront's router segments -> tagged partial logits ----------------------
             if (doR) {
+                unsigned long long *dstp = logit_ring + (size_t)(mR & (DEC_RING - 1)) * n_items1;
                 const float *w_router = static_cast<const float *>(a.layers[lR * 4]);
-                unsigned long long *dstp = a.logit_ring + (size_t)(lR & (DEC_RING - 1)) * n_items1;
-#pragma unroll 1
-                for (int item = gw; item < n_items1; item += W) {
-                    floatx4_t wv = wr;
-                    int k0 = r_k;
-                    if (item != gw) {
+                floatx4_t wr[DP_MAX_R];
+#pragma unroll
+                for (int r = 0; r < DP_MAX_R; ++r) {
+                    const int item = gw + r * W;
+                    if (item < n_items1) {
                         const int e = item / segs;
-                        k0 = (item - e * segs) * DEC_SEG + lane * 4;
-                        wv = load_global<floatx4_t>(w_router + (int64_t)e * H + k0);
+                        wr[r] = load_global<floatx4_t>(w_router + (int64_t)e * H + (item - e * segs) * DEC_SEG + lane * 4);
                     }
-                    const uint2 xb = *reinterpret_cast<const uint2 *>(&xs[k0]);
-                    float p = wv.x * __uint_as_float(xb.x << 16);
-                    p = fmaf(wv.y, __uint_as_float(xb.x & 0xFFFF0000u), p);
-                    p = fmaf(wv.z, __uint_as_float(xb.y << 16), p);
-                    p = fmaf(wv.w, __uint_as_float(xb.y & 0xFFFF0000u), p);
-                    p = wave_sum(p);
-                    if (lane == 0) put_tagged(dstp + item, p, tag0 + (uint32_t)lR);
+                }
+#pragma unroll
+                for (int r = 0; r < DP_MAX_R; ++r) {
+                    const int item = gw + r * W;
+                    if (item < n_items1) {
+                        const int e = item / segs;
+                        const int k0 = (item - e * segs) * DEC_SEG + lane * 4;
+                        const uint2 xb = *reinterpret_cast<const uint2 *>(&xs[k0]);
+                        float p = wr[r].x * __uint_as_float(xb.x << 16);
+                        p = fmaf(wr[r].y, __uint_as_float(xb.x & 0xFFFF0000u), p);
+                        p = fmaf(wr[r].z, __uint_as_float(xb.y << 16), p);
+                        p = fmaf(wr[r].w, __uint_as_float(xb.y & 0xFFFF0000u), p);
+                        p = wave_sum(p);
+                        if (lane == 0) put_tagged(dstp + item, p, tag0 + (uint32_t)lR);
+                    }
                 }
             }
 
-            // ---- statistics of layer lG (one wavefront of the grid), riding on the loads in flight -----
+            // ---- statistics of layer lG (one wavefront of the group), riding on the loads in flight ------
+            const int *se_g = sel_e[mG & (DP_SEL - 1)];
             if (doG && stats_wave) online_trace_stats(a, ts, lG, g, se_g, lane);
 
-            // ---- D(lD): output rows of layer lD ------------------------------------------------------
-            if (doD) {
-                const char *wd_bytes = static_cast<const char *>(a.layers[lD * 4 + 3]);
-                const int *se_d = sel_e[lD & (DEC_RING - 1)];
-                const bf16_t *hcur = hl[lD & 1];
-                const float *sw_d = sel_w[lD & (DEC_RING - 1)];
-                int lane_d = threadIdx.x & 63;
-                asm volatile("" : "+v"(lane_d));
+            // ---- G(lG) set-up: gate / up rows of the selected experts ------------------------------------
+            u32x4_t gA[XCH], uA[XCH], gB[XCH], uB[XCH];
+            const bf16_t *w_gate = doG ? static_cast<const bf16_t *>(a.layers[lG * 4 + 1]) : nullptr;
+            const bf16_t *w_up = doG ? static_cast<const bf16_t *>(a.layers[lG * 4 + 2]) : nullptr;
+            const int nG = doG ? nit : 0;
+            int g_j = item0 / I, g_i = item0 - g_j * I;  // (expert slot, intermediate index) of the next activation to load
+#define DP_LOAD_ITEM(gv, uv)                                                                          \
+    {                                                                                                 \
+        const int e_ = __builtin_amdgcn_readfirstlane(se_g[g_j]);                                     \
+        const bf16_t *gp_ = w_gate + ((int64_t)e_ * I + g_i) * H;                                     \
+        const bf16_t *up_ = w_up + ((int64_t)e_ * I + g_i) * H;                                       \
+        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
+            gv[c] = load_global<u32x4_t>(gp_ + loff + c * 512);                                       \
+            uv[c] = load_global<u32x4_t>(up_ + loff + c * 512);                                       \
+        }                                                                                             \
+        if (++g_i == I) { g_i = 0; ++g_j; }                                                           \
+    }
+            // reduce activation u (held in gv / uv); every third one closes an exchange word
+#define DP_REDUCE_ITEM(gv, uv, u)                                                                     \
+    {                                                                                                 \
+        float gs_ = 0.f, us_ = 0.f;                                                                   \
+        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
+            const u32x4_t xq_ = *reinterpret_cast<const u32x4_t *>(&xs[(c * 64 + lane) * 8]);         \
+            gs_ = dot8_bf16(gv[c], xq_, gs_);                                                         \
+            us_ = dot8_bf16(uv[c], xq_, us_);                                                         \
+        }                                                                                             \
+        gs_ = wave_sum(gs_);                                                                          \
+        us_ = wave_sum(us_);                                                                          \
+        const int sub_ = (u) % 3;                                                                     \
+        h_word |= (unsigned long long)f32_to_bf16(gs_ / (1.0f + expf(-gs_)) * us_) << (16 * sub_);    \
+        if (sub_ == 2 || (u) == nG - 1) {                                                             \
+            if (lane == 0)                                                                            \
+                __hip_atomic_store(&h_ring[(size_t)(mG & (DEC_RING - 1)) * a.h_slot + gw * wpw + (u) / 3], h_word, \
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);                       \
+            h_word = h_tag;                                                                           \
+        }                                                                                             \
+    }
+            const unsigned long long h_tag = (unsigned long long)tag16(tag0 + (uint32_t)lG) << 48;
+            unsigned long long h_word = h_tag;
+
+            // ---- D(lD): this wavefront's output rows of layer lD; rows alternate between two register
+            // sets, the row after next is requested as soon as a set is free; the first two gate/up
+            // activation of G is requested before the last row is reduced ------------------------------
+            {
+                const bf16_t *hcur = hl[mD & 1];
+                const float *sw_d = sel_w[mD & (DP_SEL - 1)];
+                const int nD = doD ? n_rows : 0;
+                bool g_issued = false;
+                if (nD > 1) DP_LOAD_DROW(dvB, mD, 1)            // row 0 was requested at the end of the previous iteration
+#define DP_REDUCE_DROW(dv, rw)                                                                        \
+    {                                                                                                 \
+        int lane_d = threadIdx.x & 63;                                                                \
+        asm volatile("" : "+v"(lane_d));                                                              \
+        float acc = 0.f;                                                                              \
+        _Pragma("unroll") for (int c = 0; c < DP_MAX_DCH; ++c) {                                       \
+            const int q = c * 64 + lane_d;                                                            \
+            if (q < dchunks) {                                                                        \
+                const u32x4_t hq = *reinterpret_cast<const u32x4_t *>(&hcur[q * 8]);                  \
+                acc = fmaf(sw_d[DP_SLOT_OF(q)], dot8_bf16(dv[c], hq, 0.f), acc);                      \
+            }                                                                                         \
+        }                                                                                             \
+        acc = wave_sum(acc);                                                                          \
+        if (lane == 0) a.y[(g * L + lD) * H + row_first + (rw)] = f32_to_bf16(acc);                   \
+    }
+#define DP_ISSUE_G01()                                                                                \
+    if (!g_issued) {                                                                                  \
+        if (nG > 0) DP_LOAD_ITEM(gA, uA)                                                              \
+        g_issued = true;                                                                              \
+    }
 #pragma unroll 1
-                for (int rw = 0; rw < rows_per_wave; ++rw) {
-                    const int o = row_first + rw;
-                    if (o >= H) break;
-                    float acc = 0.f;
-#pragma unroll
-                    for (int c = 0; c < DP_MAX_DCH; ++c) {
-                        const int q = c * 64 + lane_d;
-                        if (q < dchunks) {
-                            u32x4_t wv = dv[c];
-                            if (rw > 0) {
-                                const uint32_t off = (uint32_t)(((int64_t)se_d[d_pos[c] >> 24] * H + o) * I * 2) + (d_pos[c] & 0xFFFFFFu);
-                                wv = load_global<u32x4_t>(wd_bytes + off);
-                            }
-                            const u32x4_t hq = *reinterpret_cast<const u32x4_t *>(&hcur[q * 8]);
-                            acc = fmaf(sw_d[d_pos[c] >> 24], dot8_bf16(wv, hq, 0.f), acc);
-                        }
+                for (int rw = 0; rw < nD; rw += 2) {
+                    if (rw + 1 >= nD) { DP_ISSUE_G01() }       // rw is the last row
+                    DP_REDUCE_DROW(dvA, rw)
+                    if (rw + 2 < nD) DP_LOAD_DROW(dvA, mD, rw + 2)
+                    if (rw + 1 < nD) {
+                        if (rw + 2 >= nD) { DP_ISSUE_G01() }   // rw + 1 is the last row
+                        DP_REDUCE_DROW(dvB, rw + 1)
+                        if (rw + 3 < nD) DP_LOAD_DROW(dvB, mD, rw + 3)
                     }
-                    acc = wave_sum(acc);
-                    if (lane == 0) a.y[(g * L + lD) * H + o] = f32_to_bf16(acc);
                 }
+                DP_ISSUE_G01()
+                if (nG > 1) DP_LOAD_ITEM(gB, uB)
             }
 
             // ---- G(lG): roll over the activations (register sets A and B alternate); the next
-            // iteration's polls and weight loads go out right before the last one is reduced, so the
+            // iteration's polls and first weight rows go out right before the last one is reduced, so the
             // memory pipe never runs dry between iterations ----------------------------------------------
-            if (nG > 1) { DP_REDUCE_ITEM(gA, uA, 0) if (nG > 2) DP_LOAD_ITEM(gA, uA, 2) }
-            if (nG > 2) { DP_REDUCE_ITEM(gB, uB, 1) }
-            if (it + 1 < L + 4) { DP_ISSUE_ITER(it + 1) }
-            if (nG > 0) {
-                if ((nG - 1) & 1) { DP_REDUCE_ITEM(gB, uB, nG - 1) } else { DP_REDUCE_ITEM(gA, uA, nG - 1) }
-                if (lane == 0)
-                    __hip_atomic_store(&a.h_ring[(size_t)(lG & (DEC_RING - 1)) * a.h_slot + gw], h_word, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+            {
+                bool next_issued = false;
+#define DP_ISSUE_NEXT()                                                                               \
+    if (!next_issued) {                                                                               \
+        if (it + 1 < n_mine + 4) { DP_ISSUE_ITER(it + 1) }                                            \
+        next_issued = true;                                                                           \
+    }
+#pragma unroll 1
+                for (int u = 0; u < nG; u += 2) {
+                    if (u + 1 >= nG) { DP_ISSUE_NEXT() }       // u is the last activation
+                    DP_REDUCE_ITEM(gA, uA, u)
+                    if (u + 2 < nG) DP_LOAD_ITEM(gA, uA)
+                    if (u + 1 < nG) {
+                        if (u + 2 >= nG) { DP_ISSUE_NEXT() }   // u + 1 is the last activation
+                        DP_REDUCE_ITEM(gB, uB, u + 1)
+                        if (u + 3 < nG) DP_LOAD_ITEM(gB, uB)
+                    }
+                }
+                DP_ISSUE_NEXT()
             }
         }
 
@@ -419,17 +477,18 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         if (!grid_barrier(a, ++bar_phase, &bar_ok)) return;
     }
 
-    if (blockIdx.x == G - 1) {
+    if (gr == GS - 1) {                                  // trace state back to device memory
         __syncthreads();
-        for (int q = tid; q < L * 128; q += DP_THREADS) {
-            const int l = q >> 7, e = q & 127;
+        for (int q = tid; q < n_mine * 128; q += DP_THREADS) {
+            const int l = group + NG * (q >> 7), e = q & 127;
             if (e < N) a.lru_state[l * N + e] = ts.last[l][e];
         }
-        for (int q = tid; q < L; q += DP_THREADS) {
-            a.sum_overlap[q] = ts.sum_ov[q];
+        for (int q = tid; q < n_mine; q += DP_THREADS) {
+            const int l = group + NG * q;
+            a.sum_overlap[l] = ts.sum_ov[l];
             for (int c = 0; c < a.n_caps; ++c) {
-                a.total_miss[c * L + q] = ts.tot[c][q];
-                a.bytes_fetched[c * L + q] = ts.tot[c][q] * a.expert_bytes;
+                a.total_miss[c * L + l] = ts.tot[c][l];
+                a.bytes_fetched[c * L + l] = ts.tot[c][l] * a.expert_bytes;
             }
         }
     }
@@ -463,16 +522,19 @@ remoe_status launch_decode_pipelined(const DecodeLaunch &d, hipStream_t stream)
     REMOE_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
     if (n_cu < 1) return fail(REMOE_E_HIP, "device reports no compute units");
     const int G = n_cu;
-    const int W = G * DP_WAVES;
-    const DecodeWsLayout wl0 = decode_ws_layout(d.H, d.N, d.I, d.K);
+    const int NG = (G % DP_GROUPS == 0) ? DP_GROUPS : 1;
+    const int W = (G / NG) * DP_WAVES;                   // wavefronts per group
+    const DecodeWsLayout wl = decode_ws_layout(d.H, d.N, d.I, d.K);
     if (G > DEC_MAX_GRID) return fail(REMOE_E_UNSUPPORTED, "decode: %d compute units exceed the barrier's %d flags", G, DEC_MAX_GRID);
-    if (W > DP_POLL_H * DP_THREADS || W > wl0.n_h)
-        return fail(REMOE_E_UNSUPPORTED, "decode: %d wavefronts exceed the %d exchange words a workgroup polls", W, DP_POLL_H * DP_THREADS);
-    if ((d.K * d.I + W - 1) / W > DP_MAX_ITEMS)
-        return fail(REMOE_E_UNSUPPORTED, "decode: top_k * inter = %d needs more than %d activations per wavefront on %d compute units",
-                    d.K * d.I, DP_MAX_ITEMS, G);
-    if (d.N * (d.H / DEC_SEG) > DP_POLL_L * DP_THREADS)
-        return fail(REMOE_E_UNSUPPORTED, "decode: n_experts * hidden / 256 exceeds %d", DP_POLL_L * DP_THREADS);
+    const int ipw = (d.K * d.I + W - 1) / W;
+    const int n_words = W * ((ipw + 2) / 3);
+    if (n_words > DP_POLL_H * DP_THREADS || n_words > wl.n_h)
+        return fail(REMOE_E_UNSUPPORTED, "decode: %d exchange words per layer exceed the %d a workgroup polls", n_words,
+                    DP_POLL_H * DP_THREADS);
+    const int n_seg = d.N * (d.H / DEC_SEG);
+    if (n_seg > DP_POLL_L * DP_THREADS || n_seg > DP_MAX_R * W)
+        return fail(REMOE_E_UNSUPPORTED, "decode: n_experts * hidden / 256 = %d router segments are more than %d wavefronts x %d",
+                    n_seg, W, DP_MAX_R);
 
     PipeArgs a;
     a.layers = d.layers;
@@ -495,7 +557,6 @@ remoe_status launch_decode_pipelined(const DecodeLaunch &d, hipStream_t stream)
     a.total_miss = reinterpret_cast<unsigned long long *>(d.total_miss);
     a.bytes_fetched = reinterpret_cast<unsigned long long *>(d.bytes_fetched);
     char *ws = static_cast<char *>(d.workspace);
-    const DecodeWsLayout wl = decode_ws_layout(d.H, d.N, d.I, d.K);
     a.abort_flag = reinterpret_cast<uint32_t *>(ws + 128);
     a.bar = reinterpret_cast<uint32_t *>(ws + 256);
     a.logit_ring = reinterpret_cast<unsigned long long *>(ws + wl.logit_off);
@@ -503,7 +564,7 @@ remoe_status launch_decode_pipelined(const DecodeLaunch &d, hipStream_t stream)
     a.h_slot = wl.n_h;
     a.spin_limit = d.spin_limit_ticks;
 
-    // both rings are contiguous from logit_off to the end of the workspace
+    // both ring regions are contiguous from logit_off to the end of the workspace
     hipLaunchKernelGGL(decode_pipe_clear, dim3(1), dim3(1024), 0, stream, a.bar, G, a.abort_flag, a.logit_ring,
                        (int)((wl.total - wl.logit_off) / sizeof(unsigned long long)));
     void *params[] = {&a};

@@ -135,7 +135,7 @@ def test_decode_wait_limit_aborts_cleanly(order):
 def test_decode_rejects_unsupported_layers():
     x = torch.zeros(4, 768, dtype=torch.bfloat16, device=DEV)
     desc = remoe.LayerDesc(768, 16, 64, 4, 1, 0, 0, 1)
-    ws = torch.zeros(1 << 20, dtype=torch.uint8, device=DEV)
+    ws = torch.zeros(8 << 20, dtype=torch.uint8, device=DEV)
     t = torch.zeros(1, 4, dtype=torch.int64, device=DEV)
     z = torch.zeros(64, dtype=torch.int64, device=DEV)
     with pytest.raises(remoe.RemoeError, match="hidden"):
