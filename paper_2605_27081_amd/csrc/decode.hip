@@ -110,7 +110,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
     floatx4_t wr_pf = {0.f, 0.f, 0.f, 0.f};
     const int e1 = gw / segs, k1 = (gw - e1 * segs) * DC_SEG + lane * 4;
     if (gw < n_items1)
-        wr_pf = load_global<floatx4_t>(static_cast<const float *>(a.layers[0]) + (int64_t)e1 * H + k1);
+        wr_pf = load_global<floatx4_t>(static_cast<const float *>(table_ptr(a.layers, 0)) + (int64_t)e1 * H + k1);
 
 #pragma unroll 1
     for (int64_t s = 0; s < a.n_steps; ++s) {
@@ -118,10 +118,10 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
         const bf16_t *xg = a.x + g * H;
 #pragma unroll 1
         for (int layer = 0; layer < a.n_layers; ++layer) {
-            const float *w_router = static_cast<const float *>(a.layers[layer * 4 + 0]);
-            const bf16_t *w_gate = static_cast<const bf16_t *>(a.layers[layer * 4 + 1]);
-            const bf16_t *w_up = static_cast<const bf16_t *>(a.layers[layer * 4 + 2]);
-            const bf16_t *w_down = static_cast<const bf16_t *>(a.layers[layer * 4 + 3]);
+            const float *w_router = static_cast<const float *>(table_ptr(a.layers, layer * 4 + 0));
+            const bf16_t *w_gate = static_cast<const bf16_t *>(table_ptr(a.layers, layer * 4 + 1));
+            const bf16_t *w_up = static_cast<const bf16_t *>(table_ptr(a.layers, layer * 4 + 2));
+            const bf16_t *w_down = static_cast<const bf16_t *>(table_ptr(a.layers, layer * 4 + 3));
 
             // ---- phase 1: partial router logits --------------------------------------------------
 #pragma unroll 1
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                 int nl = layer + 1;
                 if (nl == a.n_layers) nl = 0;
                 if (gw < n_items1)
-                    wr_pf = load_global<floatx4_t>(static_cast<const float *>(a.layers[nl * 4]) + (int64_t)e1 * H + k1);
+                    wr_pf = load_global<floatx4_t>(static_cast<const float *>(table_ptr(a.layers, nl * 4)) + (int64_t)e1 * H + k1);
             }
             __syncthreads();
 #pragma unroll 1

@@ -47,6 +47,16 @@ __device__ __forceinline__ T load_global(const void *p)
     return *(const __attribute__((address_space(1))) T *)p;
 }
 
+// Entry idx (the same for every lane) of the launch's weight-pointer table, read with a scalar
+// load.  The host writes the table before the launch and no kernel ever does, so the constant
+// address space is safe; a vector load here returns the pointer in the same in-order queue as the
+// weight stream, and the wavefront would wait for every weight load in flight before using it.
+__device__ __forceinline__ const void *table_ptr(const void *const *table, int idx)
+{
+    typedef const unsigned long long __attribute__((address_space(4))) *const_u64_ptr;
+    return reinterpret_cast<const void *>(*(const_u64_ptr)(uintptr_t)(table + idx));
+}
+
 // Dot product of 8 bf16 pairs (two 16-byte registers) added to acc: four v_dot2c_f32_bf16 (exact
 // products, fp32 accumulation).  Written as assembly because the compiler's builtin for this
 // instruction picked the same source registers for all four elements of a 16-byte vector.  The

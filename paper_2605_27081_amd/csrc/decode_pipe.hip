@@ -89,7 +89,12 @@ __device__ __forceinline__ unsigned long long poll_word(const unsigned long long
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <int XCH>
+// XCH: 16-byte chunks per lane of one hidden row (hidden / 512).  DCH: 16-byte chunks per lane of one
+// down-projection output row over the K selected experts (K * inter / 512, rounded up to a supported
+// count).  Both fix the number of loads per unit of work at compile time: the steady-state loops
+// below then contain no branch, and the compiler can wait for exactly the loads an instruction needs
+// while the next unit's loads stay in flight.
+template <int XCH, int DCH>
 __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs a)
 {
     __shared__ __attribute__((aligned(16))) bf16_t hl[2][DP_MAX_KI];   // activations of two layers (bf16)
@@ -168,22 +173,21 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
 
         // registers that carry loads across the iteration boundary
         unsigned long long pl[DP_POLL_L], ph[DP_POLL_H];
-        u32x4_t dvA[DP_MAX_DCH], dvB[DP_MAX_DCH];
+        u32x4_t dvA[DCH], dvB[DCH];
 
         // one down-projection row of this wavefront (row_first + rw) of layer number md_ -> dv
 #define DP_LOAD_DROW(dv, md_, rw)                                                                     \
     {                                                                                                 \
         int lane_ = threadIdx.x & 63;                                                                 \
         asm volatile("" : "+v"(lane_));   /* offsets are recomputed here, not kept in registers */     \
-        const char *wd_ = static_cast<const char *>(a.layers[(group + NG * (md_)) * 4 + 3]);          \
+        const char *wd_ = static_cast<const char *>(table_ptr(a.layers, (group + NG * (md_)) * 4 + 3)); \
         const int *se_ = sel_e[(md_) & (DP_SEL - 1)];                                                 \
-        _Pragma("unroll") for (int c = 0; c < DP_MAX_DCH; ++c) {                                       \
-            const int q_ = c * 64 + lane_;                                                            \
-            if (q_ < dchunks) {                                                                       \
-                const int j_ = DP_SLOT_OF(q_);                                                        \
-                const uint32_t off_ = (uint32_t)(((int64_t)se_[j_] * H + row_first + (rw)) * I * 2) + (uint32_t)(q_ - j_ * chunks_per_row) * 16u; \
-                dv[c] = load_global<u32x4_t>(wd_ + off_);                                             \
-            }                                                                                         \
+        _Pragma("unroll") for (int c = 0; c < DCH; ++c) {                                              \
+            int q_ = c * 64 + lane_;                          /* past the end: the last chunk again, */ \
+            if (q_ >= dchunks) q_ = dchunks - 1;              /* weighted 0 when the row is reduced  */ \
+            const int j_ = DP_SLOT_OF(q_);                                                            \
+            const uint32_t off_ = (uint32_t)(((int64_t)se_[j_] * H + row_first + (rw)) * I * 2) + (uint32_t)(q_ - j_ * chunks_per_row) * 16u; \
+            dv[c] = load_global<u32x4_t>(wd_ + off_);                                                 \
         }                                                                                             \
     }
 
@@ -333,7 +337,7 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             // ---- R(lR): this wavefront's router segments -> tagged partial logits ----------------------
             if (doR) {
                 unsigned long long *dstp = logit_ring + (size_t)(mR & (DEC_RING - 1)) * n_items1;
-                const float *w_router = static_cast<const float *>(a.layers[lR * 4]);
+                const float *w_router = static_cast<const float *>(table_ptr(a.layers, lR * 4));
                 floatx4_t wr[DP_MAX_R];
 #pragma unroll
                 for (int r = 0; r < DP_MAX_R; ++r) {
@@ -366,8 +370,8 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
 
             // ---- G(lG) set-up: gate / up rows of the selected experts ------------------------------------
             u32x4_t gA[XCH], uA[XCH], gB[XCH], uB[XCH];
-            const bf16_t *w_gate = doG ? static_cast<const bf16_t *>(a.layers[lG * 4 + 1]) : nullptr;
-            const bf16_t *w_up = doG ? static_cast<const bf16_t *>(a.layers[lG * 4 + 2]) : nullptr;
+            const bf16_t *w_gate = doG ? static_cast<const bf16_t *>(table_ptr(a.layers, lG * 4 + 1)) : nullptr;
+            const bf16_t *w_up = doG ? static_cast<const bf16_t *>(table_ptr(a.layers, lG * 4 + 2)) : nullptr;
             const int nG = doG ? nit : 0;
             int g_j = item0 / I, g_i = item0 - g_j * I;  // (expert slot, intermediate index) of the next activation to load
 #define DP_LOAD_ITEM(gv, uv)                                                                          \
@@ -418,12 +422,12 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         int lane_d = threadIdx.x & 63;                                                                \
         asm volatile("" : "+v"(lane_d));                                                              \
         float acc = 0.f;                                                                              \
-        _Pragma("unroll") for (int c = 0; c < DP_MAX_DCH; ++c) {                                       \
+        _Pragma("unroll") for (int c = 0; c < DCH; ++c) {                                              \
             const int q = c * 64 + lane_d;                                                            \
-            if (q < dchunks) {                                                                        \
-                const u32x4_t hq = *reinterpret_cast<const u32x4_t *>(&hcur[q * 8]);                  \
-                acc = fmaf(sw_d[DP_SLOT_OF(q)], dot8_bf16(dv[c], hq, 0.f), acc);                      \
-            }                                                                                         \
+            const int qc = q < dchunks ? q : dchunks - 1;                                             \
+            const u32x4_t hq = *reinterpret_cast<const u32x4_t *>(&hcur[qc * 8]);                     \
+            const float w_ = q < dchunks ? sw_d[DP_SLOT_OF(qc)] : 0.f;                                \
+            acc = fmaf(w_, dot8_bf16(dv[c], hq, 0.f), acc);                                           \
         }                                                                                             \
         acc = wave_sum(acc);                                                                          \
         if (lane == 0) a.y[(g * L + lD) * H + row_first + (rw)] = f32_to_bf16(acc);                   \
@@ -433,8 +437,16 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         if (nG > 0) DP_LOAD_ITEM(gA, uA)                                                              \
         g_issued = true;                                                                              \
     }
+                int rw = 0;
 #pragma unroll 1
-                for (int rw = 0; rw < nD; rw += 2) {
+                for (; rw + 3 < nD; rw += 2) {                 // steady state: both sets are refilled, no branch
+                    DP_REDUCE_DROW(dvA, rw)
+                    DP_LOAD_DROW(dvA, mD, rw + 2)
+                    DP_REDUCE_DROW(dvB, rw + 1)
+                    DP_LOAD_DROW(dvB, mD, rw + 3)
+                }
+#pragma unroll 1
+                for (; rw < nD; rw += 2) {                     // the last rows
                     if (rw + 1 >= nD) { DP_ISSUE_G01() }       // rw is the last row
                     DP_REDUCE_DROW(dvA, rw)
                     if (rw + 2 < nD) DP_LOAD_DROW(dvA, mD, rw + 2)
@@ -458,8 +470,16 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         if (it + 1 < n_mine + 4) { DP_ISSUE_ITER(it + 1) }                                            \
         next_issued = true;                                                                           \
     }
+                int u = 0;
 #pragma unroll 1
-                for (int u = 0; u < nG; u += 2) {
+                for (; u + 3 < nG; u += 2) {                   // steady state: both sets are refilled, no branch
+                    DP_REDUCE_ITEM(gA, uA, u)
+                    DP_LOAD_ITEM(gA, uA)
+                    DP_REDUCE_ITEM(gB, uB, u + 1)
+                    DP_LOAD_ITEM(gB, uB)
+                }
+#pragma unroll 1
+                for (; u < nG; u += 2) {                       // the last activations
                     if (u + 1 >= nG) { DP_ISSUE_NEXT() }       // u is the last activation
                     DP_REDUCE_ITEM(gA, uA, u)
                     if (u + 2 < nG) DP_LOAD_ITEM(gA, uA)
@@ -569,11 +589,12 @@ remoe_status launch_decode_pipelined(const DecodeLaunch &d, hipStream_t stream)
                        (int)((wl.total - wl.logit_off) / sizeof(unsigned long long)));
     void *params[] = {&a};
     const void *fn = nullptr;
+    const bool few = d.K * d.I <= 4 * 512;               // down-row chunks per lane: 4 or DP_MAX_DCH
     switch (d.H / 512) {
-    case 1: fn = reinterpret_cast<const void *>(decode_pipe_kernel<1>); break;
-    case 2: fn = reinterpret_cast<const void *>(decode_pipe_kernel<2>); break;
-    case 4: fn = reinterpret_cast<const void *>(decode_pipe_kernel<4>); break;
-    case 8: fn = reinterpret_cast<const void *>(decode_pipe_kernel<8>); break;
+    case 1: fn = few ? reinterpret_cast<const void *>(decode_pipe_kernel<1, 4>) : reinterpret_cast<const void *>(decode_pipe_kernel<1, DP_MAX_DCH>); break;
+    case 2: fn = few ? reinterpret_cast<const void *>(decode_pipe_kernel<2, 4>) : reinterpret_cast<const void *>(decode_pipe_kernel<2, DP_MAX_DCH>); break;
+    case 4: fn = few ? reinterpret_cast<const void *>(decode_pipe_kernel<4, 4>) : reinterpret_cast<const void *>(decode_pipe_kernel<4, DP_MAX_DCH>); break;
+    case 8: fn = few ? reinterpret_cast<const void *>(decode_pipe_kernel<8, 4>) : reinterpret_cast<const void *>(decode_pipe_kernel<8, DP_MAX_DCH>); break;
     default: return fail(REMOE_E_UNSUPPORTED, "decode supports hidden in {512, 1024, 2048, 4096} (got %d)", d.H);
     }
     // Every workgroup must be resident (the exchanges and the step barrier wait for all of them): one
