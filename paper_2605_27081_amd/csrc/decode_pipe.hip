@@ -106,7 +106,8 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
     __shared__ int bar_ok;
     __shared__ TraceLds ts;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // known to be the same in every lane: what derives from it stays in scalar registers
     const int G = gridDim.x;
     const int NG = (G % DP_GROUPS == 0) ? DP_GROUPS : 1;   // groups
     const int group = blockIdx.x % NG;
@@ -174,6 +175,7 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         // registers that carry loads across the iteration boundary
         unsigned long long pl[DP_POLL_L], ph[DP_POLL_H];
         u32x4_t dvA[DCH], dvB[DCH];
+        floatx4_t wr[DP_MAX_R];
 
         // one down-projection row of this wavefront (row_first + rw) of layer number md_ -> dv
 #define DP_LOAD_DROW(dv, md_, rw)                                                                     \
@@ -192,11 +194,13 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
     }
 
         // Loads of iteration `itn`: the polls first (loads return in order, so whatever is issued
-        // behind them does not delay them), then the first down row of the layer it finishes.  (With a
-        // layer spread over one group an iteration is long; what is not fetched ahead costs little.)
+        // behind them does not delay them), then the first down row of the layer it finishes and the
+        // router segments of the layer it starts.  Under load a round trip to memory takes several
+        // microseconds: whatever an iteration would otherwise fetch and wait for at its start is
+        // requested here, from inside the previous iteration's stream.
 #define DP_ISSUE_ITER(itn)                                                                            \
     {                                                                                                 \
-        const int mT_ = (itn) - 1, mD_ = (itn) - 4;                                                   \
+        const int mR_ = (itn), mT_ = (itn) - 1, mD_ = (itn) - 4;                                      \
         int tid_ = threadIdx.x;                                                                       \
         asm volatile("" : "+v"(tid_));                                                                \
         if (mT_ >= 0 && mT_ < n_mine) {                                                               \
@@ -215,6 +219,17 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         }                                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                            \
         if (mD_ >= 0 && n_rows > 0) DP_LOAD_DROW(dvA, mD_, 0)                                         \
+        if (mR_ < n_mine) {                                                                           \
+            const float *w_router_ = static_cast<const float *>(table_ptr(a.layers, (group + NG * mR_) * 4)); \
+            _Pragma("unroll") for (int r = 0; r < DP_MAX_R; ++r) {                                     \
+                const int item_ = gw + r * W;                                                         \
+                if (item_ < n_items1) {                                                               \
+                    const int e_ = item_ / segs;                                                      \
+                    const uint32_t off_ = (uint32_t)(e_ * H + (item_ - e_ * segs) * DEC_SEG) * 4u;    \
+                    wr[r] = load_global<floatx4_t>(reinterpret_cast<const char *>(w_router_) + off_ + (uint32_t)(tid_ & 63) * 16u); \
+                }                                                                                     \
+            }                                                                                         \
+        }                                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                            \
     }
 
@@ -290,6 +305,9 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
                         if (missing >> (8 + k) & 1) ph[k] = poll_word(srch + tid_c + k * DP_THREADS);
                 }
             }
+            // the second down row depends on nothing behind the barrier: wavefronts that arrive early
+            // keep the memory pipe busy while they wait for the others
+            if (doD && n_rows > 1) DP_LOAD_DROW(dvB, mD, 1)
             DP_LDS_BARRIER();
             if (behind_lds) return;        // the grid is aborting (set by a wavefront whose wait ran out)
 
@@ -334,19 +352,10 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
                 }
             }
 
-            // ---- R(lR): this wavefront's router segments -> tagged partial logits ----------------------
+            // ---- R(lR): this wavefront's router segments (requested an iteration ago) -> tagged partial
+            // logits ---------------------------------------------------------------------------------------
             if (doR) {
                 unsigned long long *dstp = logit_ring + (size_t)(mR & (DEC_RING - 1)) * n_items1;
-                const float *w_router = static_cast<const float *>(table_ptr(a.layers, lR * 4));
-                floatx4_t wr[DP_MAX_R];
-#pragma unroll
-                for (int r = 0; r < DP_MAX_R; ++r) {
-                    const int item = gw + r * W;
-                    if (item < n_items1) {
-                        const int e = item / segs;
-                        wr[r] = load_global<floatx4_t>(w_router + (int64_t)e * H + (item - e * segs) * DEC_SEG + lane * 4);
-                    }
-                }
 #pragma unroll
                 for (int r = 0; r < DP_MAX_R; ++r) {
                     const int item = gw + r * W;
@@ -416,7 +425,7 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
                 const float *sw_d = sel_w[mD & (DP_SEL - 1)];
                 const int nD = doD ? n_rows : 0;
                 bool g_issued = false;
-                if (nD > 1) DP_LOAD_DROW(dvB, mD, 1)            // row 0 was requested at the end of the previous iteration
+                // (row 0 was requested at the end of the previous iteration, row 1 before the barrier)
 #define DP_REDUCE_DROW(dv, rw)                                                                        \
     {                                                                                                 \
         int lane_d = threadIdx.x & 63;                                                                \
