@@ -102,6 +102,8 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
     __shared__ float lpart[2][128 * 16]; // partial logits of the layer being ranked (two iterations apart)
     __shared__ int sel_e[DP_SEL][8];     // selections of the group's last DP_SEL layers: written by the wavefront
     __shared__ float sel_w[DP_SEL][8];   // on top-k duty, read by everyone from the next iteration on
+    __shared__ uint32_t sel_tag[DP_SEL]; // tag of the layer-step whose selection a slot of sel_e / sel_w holds
+    __shared__ uint32_t row_ctr[4];      // next output row of the workgroup's share, per iteration (mod 4)
     __shared__ int behind_lds;           // set when a wait ran out: the workgroup returns
     __shared__ int bar_ok;
     __shared__ TraceLds ts;
@@ -122,7 +124,7 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
     const int ipw = (KI + W - 1) / W;                    // activations per wavefront
     const int wpw = (ipw + 2) / 3;                       // exchange words per wavefront (3 activations each)
     const int n_words = W * wpw;                         // <= DP_POLL_H * DP_THREADS (checked by the launcher)
-    const int rows_per_wave = (H + W - 1) / W;
+    const int rows_per_wg = (H + GS - 1) / GS;
     const int dchunks = KI / 8;
     const int chunks_per_row = I / 8;
     const int n_mine = group < L ? (L - group + NG - 1) / NG : 0;      // layers group, group + NG, ...
@@ -143,6 +145,8 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         }
     }
     if (tid == 0) behind_lds = 0;
+    if (tid < DP_SEL) sel_tag[tid] = 0u;                 // tag 0 = no layer-step
+    if (tid < 4) row_ctr[tid] = 0u;
     __syncthreads();
 
     // ---- per-wavefront constants ---------------------------------------------------------------------
@@ -150,10 +154,10 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
     int nit = KI - item0;
     if (nit > ipw) nit = ipw;
     if (nit < 0) nit = 0;
-    const int row_first = gw * rows_per_wave;
-    int n_rows = H - row_first;
-    if (n_rows > rows_per_wave) n_rows = rows_per_wave;
-    if (n_rows < 0) n_rows = 0;
+    const int wg_row0 = gr * rows_per_wg;                // this workgroup's share of a layer's output rows
+    int wg_rows = H - wg_row0;
+    if (wg_rows > rows_per_wg) wg_rows = rows_per_wg;
+    if (wg_rows < 0) wg_rows = 0;
     // chunk q of a wavefront's down-row work is chunk q % chunks_per_row of expert slot q / chunks_per_row;
     // the quotient by multiplication (exact for q < 2^16, chunks_per_row <= 2^16)
     const uint32_t cpr_magic = (uint32_t)((0x100000000ull + (unsigned)chunks_per_row - 1) / (unsigned)chunks_per_row);
@@ -175,10 +179,13 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         // registers that carry loads across the iteration boundary
         unsigned long long pl[DP_POLL_L], ph[DP_POLL_H];
         u32x4_t dvA[DCH], dvB[DCH];
+        u32x4_t gA[XCH], uA[XCH], gB[XCH], uB[XCH];
         floatx4_t wr[DP_MAX_R];
 
-        // one down-projection row of this wavefront (row_first + rw) of layer number md_ -> dv
-#define DP_LOAD_DROW(dv, md_, rw)                                                                     \
+        // Output row `row` of layer number md_ (all K experts' pieces of it) -> dv.  A row number past
+        // the workgroup's share (valid_ false) turns every load into one of the tensor's first bytes:
+        // the number of loads per call stays fixed, which is what lets the loop below wait precisely.
+#define DP_LOAD_DROW(dv, md_, row, valid_)                                                            \
     {                                                                                                 \
         int lane_ = threadIdx.x & 63;                                                                 \
         asm volatile("" : "+v"(lane_));   /* offsets are recomputed here, not kept in registers */     \
@@ -188,19 +195,37 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             int q_ = c * 64 + lane_;                          /* past the end: the last chunk again, */ \
             if (q_ >= dchunks) q_ = dchunks - 1;              /* weighted 0 when the row is reduced  */ \
             const int j_ = DP_SLOT_OF(q_);                                                            \
-            const uint32_t off_ = (uint32_t)(((int64_t)se_[j_] * H + row_first + (rw)) * I * 2) + (uint32_t)(q_ - j_ * chunks_per_row) * 16u; \
+            uint32_t off_ = (uint32_t)(((int64_t)se_[j_] * H + (row)) * I * 2) + (uint32_t)(q_ - j_ * chunks_per_row) * 16u; \
+            if (!(valid_)) off_ = 0;                                                                  \
             dv[c] = load_global<u32x4_t>(wd_ + off_);                                                 \
         }                                                                                             \
     }
 
+        // gate and up rows of the next activation of layer number mg_ (expert slot g_j, index g_i)
+#define DP_LOAD_ITEM(gv, uv, mg_)                                                                     \
+    {                                                                                                 \
+        const int e_ = __builtin_amdgcn_readfirstlane(sel_e[(mg_) & (DP_SEL - 1)][g_j]);              \
+        const bf16_t *gp_ = static_cast<const bf16_t *>(table_ptr(a.layers, (group + NG * (mg_)) * 4 + 1)) + ((int64_t)e_ * I + g_i) * H; \
+        const bf16_t *up_ = static_cast<const bf16_t *>(table_ptr(a.layers, (group + NG * (mg_)) * 4 + 2)) + ((int64_t)e_ * I + g_i) * H; \
+        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
+            gv[c] = load_global<u32x4_t>(gp_ + loff + c * 512);                                       \
+            uv[c] = load_global<u32x4_t>(up_ + loff + c * 512);                                       \
+        }                                                                                             \
+        if (++g_i == I) { g_i = 0; ++g_j; }                                                           \
+    }
+
         // Loads of iteration `itn`: the polls first (loads return in order, so whatever is issued
-        // behind them does not delay them), then the first down row of the layer it finishes and the
-        // router segments of the layer it starts.  Under load a round trip to memory takes several
-        // microseconds: whatever an iteration would otherwise fetch and wait for at its start is
-        // requested here, from inside the previous iteration's stream.
+        // behind them does not delay them), then the router segments of the layer it starts and the
+        // gate / up rows of the first two activations of the layer whose experts it evaluates.  Under
+        // load a round trip to memory takes several microseconds: whatever an iteration would
+        // otherwise fetch and wait for at its start is requested here, from inside the previous
+        // iteration's stream.  The selection the gate / up rows depend on was made at the start of
+        // the previous iteration by one wavefront of this workgroup; its flag says whether it is
+        // there.  Nobody waits for it: a wavefront that gets here first (an iteration with nothing
+        // else to do) requests its rows behind the next barrier instead.
 #define DP_ISSUE_ITER(itn)                                                                            \
     {                                                                                                 \
-        const int mR_ = (itn), mT_ = (itn) - 1, mD_ = (itn) - 4;                                      \
+        const int mR_ = (itn), mT_ = (itn) - 1, mG_ = (itn) - 2, mD_ = (itn) - 4;                     \
         int tid_ = threadIdx.x;                                                                       \
         asm volatile("" : "+v"(tid_));                                                                \
         if (mT_ >= 0 && mT_ < n_mine) {                                                               \
@@ -218,7 +243,6 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             }                                                                                         \
         }                                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                            \
-        if (mD_ >= 0 && n_rows > 0) DP_LOAD_DROW(dvA, mD_, 0)                                         \
         if (mR_ < n_mine) {                                                                           \
             const float *w_router_ = static_cast<const float *>(table_ptr(a.layers, (group + NG * mR_) * 4)); \
             _Pragma("unroll") for (int r = 0; r < DP_MAX_R; ++r) {                                     \
@@ -230,9 +254,23 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
                 }                                                                                     \
             }                                                                                         \
         }                                                                                             \
+        g_j = item0 / I;                                                                              \
+        g_i = item0 - g_j * I;                                                                        \
+        g_ahead = false;                                                                              \
+        if (mG_ >= 0 && mG_ < n_mine && nit > 0) {                                                    \
+            const uint32_t want_ = tag0 + (uint32_t)(group + NG * mG_);                               \
+            const uint32_t have_ = __hip_atomic_load(&sel_tag[mG_ & (DP_SEL - 1)], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP); \
+            if (__builtin_amdgcn_readfirstlane(have_) == want_) {                                     \
+                DP_LOAD_ITEM(gA, uA, mG_)                                                             \
+                if (nit > 1) DP_LOAD_ITEM(gB, uB, mG_)                                                \
+                g_ahead = true;                                                                       \
+            }                                                                                         \
+        }                                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                            \
     }
 
+        int g_j = 0, g_i = 0;     // (expert slot, intermediate index) of the next activation to load
+        bool g_ahead = false;     // the first gate / up rows of the coming iteration are already requested
         if (n_mine > 0) DP_ISSUE_ITER(0)
 
 #pragma unroll 1
@@ -248,6 +286,8 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             {
                 int tid_c = threadIdx.x;
                 asm volatile("" : "+v"(tid_c));
+                // the row counter of the next iteration (last used three iterations ago)
+                if (tid_c == 0) row_ctr[(it + 1) & 3] = 0;
                 const uint32_t tg = tag0 + (uint32_t)lT;
                 const uint32_t td = tag16(tag0 + (uint32_t)lD);
                 const unsigned long long *srcl = logit_ring + (size_t)(mT & (DEC_RING - 1)) * n_items1;
@@ -305,15 +345,17 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
                         if (missing >> (8 + k) & 1) ph[k] = poll_word(srch + tid_c + k * DP_THREADS);
                 }
             }
-            // the second down row depends on nothing behind the barrier: wavefronts that arrive early
-            // keep the memory pipe busy while they wait for the others
-            if (doD && n_rows > 1) DP_LOAD_DROW(dvB, mD, 1)
             DP_LDS_BARRIER();
             if (behind_lds) return;        // the grid is aborting (set by a wavefront whose wait ran out)
 
+            if (doG && nit > 0 && !g_ahead) {          // the selection was not there yet when this iteration was set up
+                DP_LOAD_ITEM(gA, uA, mG)
+                if (nit > 1) DP_LOAD_ITEM(gB, uB, mG)
+            }
+
             // ---- T(lT): top-k and softmax of layer lT by the wavefront whose turn it is: K rounds of
-            // wavefront maximum, ties to the lower id.  The result is first needed after the next
-            // iteration's barrier, so nobody waits for it ---------------------------------------------------
+            // wavefront maximum, ties to the lower id.  The result is first needed when the next
+            // iteration's first gate / up rows are requested, at the end of this one ----------------------
             if (doT && wave == (it & (DP_WAVES - 1))) {
                 const float NEG_INF = -__builtin_inff();
                 const float *lp = lpart[it & 1];
@@ -350,6 +392,9 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
                         a.out_w[o] = wgt;
                     }
                 }
+                // LDS operations of one wavefront complete in order: the flag follows the selection
+                if (lane == 0)
+                    __hip_atomic_store(&sel_tag[mT & (DP_SEL - 1)], tag0 + (uint32_t)lT, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
 
             // ---- R(lR): this wavefront's router segments (requested an iteration ago) -> tagged partial
@@ -374,32 +419,51 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             }
 
             // ---- statistics of layer lG (one wavefront of the group), riding on the loads in flight ------
-            const int *se_g = sel_e[mG & (DP_SEL - 1)];
-            if (doG && stats_wave) online_trace_stats(a, ts, lG, g, se_g, lane);
+            if (doG && stats_wave) online_trace_stats(a, ts, lG, g, sel_e[mG & (DP_SEL - 1)], lane);
 
-            // ---- G(lG) set-up: gate / up rows of the selected experts ------------------------------------
-            u32x4_t gA[XCH], uA[XCH], gB[XCH], uB[XCH];
-            const bf16_t *w_gate = doG ? static_cast<const bf16_t *>(table_ptr(a.layers, lG * 4 + 1)) : nullptr;
-            const bf16_t *w_up = doG ? static_cast<const bf16_t *>(table_ptr(a.layers, lG * 4 + 2)) : nullptr;
-            const int nG = doG ? nit : 0;
-            int g_j = item0 / I, g_i = item0 - g_j * I;  // (expert slot, intermediate index) of the next activation to load
-#define DP_LOAD_ITEM(gv, uv)                                                                          \
+            // Takes the next output row of this workgroup's share of layer lD off the shared counter:
+            // rows go to whichever wavefront is free, so the wavefronts of a workgroup reach the next
+            // barrier together however unevenly memory served them during the gate / up phase.
+            const int nD = doD ? wg_rows : 0;
+            uint32_t *ctr = &row_ctr[it & 3];
+#define DP_GRAB_ROW(r)                                                                                \
     {                                                                                                 \
-        const int e_ = __builtin_amdgcn_readfirstlane(se_g[g_j]);                                     \
-        const bf16_t *gp_ = w_gate + ((int64_t)e_ * I + g_i) * H;                                     \
-        const bf16_t *up_ = w_up + ((int64_t)e_ * I + g_i) * H;                                       \
-        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
-            gv[c] = load_global<u32x4_t>(gp_ + loff + c * 512);                                       \
-            uv[c] = load_global<u32x4_t>(up_ + loff + c * 512);                                       \
-        }                                                                                             \
-        if (++g_i == I) { g_i = 0; ++g_j; }                                                           \
+        uint32_t got_ = 0;                                                                            \
+        if (lane == 0) got_ = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); \
+        r = __builtin_amdgcn_readfirstlane((int)got_);                                                \
     }
-            // reduce activation u (held in gv / uv); every third one closes an exchange word
+            int rA = nD, rB = nD;
+            bool d_issued = false;
+#define DP_ISSUE_D01()                                                                                \
+    if (!d_issued) {                                                                                  \
+        if (nD > 0) {                                                                                 \
+            DP_GRAB_ROW(rA)                                                                           \
+            DP_GRAB_ROW(rB)                                                                           \
+            __builtin_amdgcn_sched_barrier(0);    /* the loop counts on A's loads preceding B's */     \
+            DP_LOAD_DROW(dvA, mD, wg_row0 + rA, rA < nD)                                              \
+            __builtin_amdgcn_sched_barrier(0);                                                        \
+            DP_LOAD_DROW(dvB, mD, wg_row0 + rB, rB < nD)                                              \
+            __builtin_amdgcn_sched_barrier(0);                                                        \
+        } else {                          /* defined on every path: no register is kept for them */   \
+            _Pragma("unroll") for (int c = 0; c < DCH; ++c) { dvA[c] = u32x4_t{0, 0, 0, 0}; dvB[c] = u32x4_t{0, 0, 0, 0}; } \
+        }                                                                                             \
+        d_issued = true;                                                                              \
+    }
+
+            // ---- G(lG): roll over this wavefront's activations of layer lG; the gate / up rows of the
+            // first two are in flight since the previous iteration, register sets A and B alternate.
+            // Every third activation closes an exchange word.  The first output rows of D are requested
+            // before the last activation is reduced ---------------------------------------------------------
+            {
+                const int nG = doG ? nit : 0;
+                const unsigned long long h_tag = (unsigned long long)tag16(tag0 + (uint32_t)lG) << 48;
+                unsigned long long h_word = h_tag;
+                const bf16_t *xcur = xs;
 #define DP_REDUCE_ITEM(gv, uv, u)                                                                     \
     {                                                                                                 \
         float gs_ = 0.f, us_ = 0.f;                                                                   \
         _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
-            const u32x4_t xq_ = *reinterpret_cast<const u32x4_t *>(&xs[(c * 64 + lane) * 8]);         \
+            const u32x4_t xq_ = *reinterpret_cast<const u32x4_t *>(&xcur[(c * 64 + lane) * 8]);       \
             gs_ = dot8_bf16(gv[c], xq_, gs_);                                                         \
             us_ = dot8_bf16(uv[c], xq_, us_);                                                         \
         }                                                                                             \
@@ -414,19 +478,36 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             h_word = h_tag;                                                                           \
         }                                                                                             \
     }
-            const unsigned long long h_tag = (unsigned long long)tag16(tag0 + (uint32_t)lG) << 48;
-            unsigned long long h_word = h_tag;
+                int u = 0;
+#pragma unroll 1
+                for (; u + 3 < nG; u += 2) {                   // steady state: both sets are refilled, no branch
+                    DP_REDUCE_ITEM(gA, uA, u)
+                    DP_LOAD_ITEM(gA, uA, mG)
+                    DP_REDUCE_ITEM(gB, uB, u + 1)
+                    DP_LOAD_ITEM(gB, uB, mG)
+                }
+#pragma unroll 1
+                for (; u < nG; u += 2) {                       // the last activations
+                    if (u + 1 >= nG) { DP_ISSUE_D01() }        // u is the last activation
+                    DP_REDUCE_ITEM(gA, uA, u)
+                    if (u + 2 < nG) DP_LOAD_ITEM(gA, uA, mG)
+                    if (u + 1 < nG) {
+                        if (u + 2 >= nG) { DP_ISSUE_D01() }    // u + 1 is the last activation
+                        DP_REDUCE_ITEM(gB, uB, u + 1)
+                        if (u + 3 < nG) DP_LOAD_ITEM(gB, uB, mG)
+                    }
+                }
+                DP_ISSUE_D01()
+            }
 
-            // ---- D(lD): this wavefront's output rows of layer lD; rows alternate between two register
-            // sets, the row after next is requested as soon as a set is free; the first two gate/up
-            // activation of G is requested before the last row is reduced ------------------------------
+            // ---- D(lD): output rows of layer lD, taken one at a time off the workgroup's counter; the
+            // two register sets alternate, a set is refilled as soon as its row is reduced.  Row numbers
+            // come off the counter in order, so once a set draws a number past the end every later draw
+            // does too ------------------------------------------------------------------------------------
             {
                 const bf16_t *hcur = hl[mD & 1];
                 const float *sw_d = sel_w[mD & (DP_SEL - 1)];
-                const int nD = doD ? n_rows : 0;
-                bool g_issued = false;
-                // (row 0 was requested at the end of the previous iteration, row 1 before the barrier)
-#define DP_REDUCE_DROW(dv, rw)                                                                        \
+#define DP_REDUCE_DROW(dv, r_)                                                                        \
     {                                                                                                 \
         int lane_d = threadIdx.x & 63;                                                                \
         asm volatile("" : "+v"(lane_d));                                                              \
@@ -439,67 +520,22 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             acc = fmaf(w_, dot8_bf16(dv[c], hq, 0.f), acc);                                           \
         }                                                                                             \
         acc = wave_sum(acc);                                                                          \
-        if (lane == 0) a.y[(g * L + lD) * H + row_first + (rw)] = f32_to_bf16(acc);                   \
+        if (lane == 0 && (r_) < nD) a.y[(g * L + lD) * H + wg_row0 + (r_)] = f32_to_bf16(acc);        \
     }
-#define DP_ISSUE_G01()                                                                                \
-    if (!g_issued) {                                                                                  \
-        if (nG > 0) DP_LOAD_ITEM(gA, uA)                                                              \
-        g_issued = true;                                                                              \
-    }
-                int rw = 0;
 #pragma unroll 1
-                for (; rw + 3 < nD; rw += 2) {                 // steady state: both sets are refilled, no branch
-                    DP_REDUCE_DROW(dvA, rw)
-                    DP_LOAD_DROW(dvA, mD, rw + 2)
-                    DP_REDUCE_DROW(dvB, rw + 1)
-                    DP_LOAD_DROW(dvB, mD, rw + 3)
+                while (rA < nD) {                  // one exit: a set that drew no row costs one idle pass
+                    DP_REDUCE_DROW(dvA, rA)
+                    DP_GRAB_ROW(rA)
+                    DP_LOAD_DROW(dvA, mD, wg_row0 + rA, rA < nD)
+                    DP_REDUCE_DROW(dvB, rB)
+                    DP_GRAB_ROW(rB)
+                    DP_LOAD_DROW(dvB, mD, wg_row0 + rB, rB < nD)
                 }
-#pragma unroll 1
-                for (; rw < nD; rw += 2) {                     // the last rows
-                    if (rw + 1 >= nD) { DP_ISSUE_G01() }       // rw is the last row
-                    DP_REDUCE_DROW(dvA, rw)
-                    if (rw + 2 < nD) DP_LOAD_DROW(dvA, mD, rw + 2)
-                    if (rw + 1 < nD) {
-                        if (rw + 2 >= nD) { DP_ISSUE_G01() }   // rw + 1 is the last row
-                        DP_REDUCE_DROW(dvB, rw + 1)
-                        if (rw + 3 < nD) DP_LOAD_DROW(dvB, mD, rw + 3)
-                    }
-                }
-                DP_ISSUE_G01()
-                if (nG > 1) DP_LOAD_ITEM(gB, uB)
             }
 
-            // ---- G(lG): roll over the activations (register sets A and B alternate); the next
-            // iteration's polls and first weight rows go out right before the last one is reduced, so the
-            // memory pipe never runs dry between iterations ----------------------------------------------
-            {
-                bool next_issued = false;
-#define DP_ISSUE_NEXT()                                                                               \
-    if (!next_issued) {                                                                               \
-        if (it + 1 < n_mine + 4) { DP_ISSUE_ITER(it + 1) }                                            \
-        next_issued = true;                                                                           \
-    }
-                int u = 0;
-#pragma unroll 1
-                for (; u + 3 < nG; u += 2) {                   // steady state: both sets are refilled, no branch
-                    DP_REDUCE_ITEM(gA, uA, u)
-                    DP_LOAD_ITEM(gA, uA)
-                    DP_REDUCE_ITEM(gB, uB, u + 1)
-                    DP_LOAD_ITEM(gB, uB)
-                }
-#pragma unroll 1
-                for (; u < nG; u += 2) {                       // the last activations
-                    if (u + 1 >= nG) { DP_ISSUE_NEXT() }       // u is the last activation
-                    DP_REDUCE_ITEM(gA, uA, u)
-                    if (u + 2 < nG) DP_LOAD_ITEM(gA, uA)
-                    if (u + 1 < nG) {
-                        if (u + 2 >= nG) { DP_ISSUE_NEXT() }   // u + 1 is the last activation
-                        DP_REDUCE_ITEM(gB, uB, u + 1)
-                        if (u + 3 < nG) DP_LOAD_ITEM(gB, uB)
-                    }
-                }
-                DP_ISSUE_NEXT()
-            }
+            // ---- the next iteration's polls and first weight rows go out before this wavefront goes to
+            // the barrier: the memory pipe stays busy while the workgroup gathers -------------------------
+            if (it + 1 < n_mine + 4) { DP_ISSUE_ITER(it + 1) }
         }
 
         // ---- the step is complete everywhere before the next one starts ---------------------------------
