@@ -214,18 +214,18 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         if (++g_i == I) { g_i = 0; ++g_j; }                                                           \
     }
 
-        // Loads of iteration `itn`: the polls first (loads return in order, so whatever is issued
-        // behind them does not delay them), then the router segments of the layer it starts and the
-        // gate / up rows of the first two activations of the layer whose experts it evaluates.  Under
-        // load a round trip to memory takes several microseconds: whatever an iteration would
-        // otherwise fetch and wait for at its start is requested here, from inside the previous
-        // iteration's stream.  The selection the gate / up rows depend on was made at the start of
+        // Loads of iteration `itn`, requested from inside the previous iteration's stream (under load a
+        // round trip to memory takes several microseconds, and an iteration that fetched and waited
+        // at its start would leave the memory pipe empty that long).  The polls go out before the
+        // previous iteration's down projection: what they ask for was published at least half an
+        // iteration earlier.  The router segments of the layer the iteration starts and the gate / up
+        // rows of the first two activations of the layer whose experts it evaluates go out last.  The selection the gate / up rows depend on was made at the start of
         // the previous iteration by one wavefront of this workgroup; its flag says whether it is
         // there.  Nobody waits for it: a wavefront that gets here first (an iteration with nothing
         // else to do) requests its rows behind the next barrier instead.
-#define DP_ISSUE_ITER(itn)                                                                            \
+#define DP_ISSUE_POLLS(itn)                                                                           \
     {                                                                                                 \
-        const int mR_ = (itn), mT_ = (itn) - 1, mG_ = (itn) - 2, mD_ = (itn) - 4;                     \
+        const int mT_ = (itn) - 1, mD_ = (itn) - 4;                                                   \
         int tid_ = threadIdx.x;                                                                       \
         asm volatile("" : "+v"(tid_));                                                                \
         if (mT_ >= 0 && mT_ < n_mine) {                                                               \
@@ -243,6 +243,12 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             }                                                                                         \
         }                                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                            \
+    }
+#define DP_ISSUE_LOADS(itn)                                                                           \
+    {                                                                                                 \
+        const int mR_ = (itn), mG_ = (itn) - 2;                                                       \
+        int tid_ = threadIdx.x;                                                                       \
+        asm volatile("" : "+v"(tid_));                                                                \
         if (mR_ < n_mine) {                                                                           \
             const float *w_router_ = static_cast<const float *>(table_ptr(a.layers, (group + NG * mR_) * 4)); \
             _Pragma("unroll") for (int r = 0; r < DP_MAX_R; ++r) {                                     \
@@ -271,7 +277,7 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
 
         int g_j = 0, g_i = 0;     // (expert slot, intermediate index) of the next activation to load
         bool g_ahead = false;     // the first gate / up rows of the coming iteration are already requested
-        if (n_mine > 0) DP_ISSUE_ITER(0)
+        if (n_mine > 0) DP_ISSUE_LOADS(0)
 
 #pragma unroll 1
         for (int it = 0; it < (n_mine > 0 ? n_mine + 4 : 0); ++it) {
@@ -436,6 +442,7 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             bool d_issued = false;
 #define DP_ISSUE_D01()                                                                                \
     if (!d_issued) {                                                                                  \
+        if (it + 1 < n_mine + 4) { DP_ISSUE_POLLS(it + 1) }                                           \
         if (nD > 0) {                                                                                 \
             DP_GRAB_ROW(rA)                                                                           \
             DP_GRAB_ROW(rB)                                                                           \
@@ -533,9 +540,9 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
                 }
             }
 
-            // ---- the next iteration's polls and first weight rows go out before this wavefront goes to
-            // the barrier: the memory pipe stays busy while the workgroup gathers -------------------------
-            if (it + 1 < n_mine + 4) { DP_ISSUE_ITER(it + 1) }
+            // ---- the next iteration's first weight rows go out before this wavefront goes to the
+            // barrier: the memory pipe stays busy while the workgroup gathers ------------------------------
+            if (it + 1 < n_mine + 4) { DP_ISSUE_LOADS(it + 1) }
         }
 
         // ---- the step is complete everywhere before the next one starts ---------------------------------
