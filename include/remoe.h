@@ -201,11 +201,18 @@ remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps,
  *                   REMOE_DECODE_CHAINED    a layer starts only after the previous layer has finished
  *                                           on every compute unit, as in a decoder whose layers feed
  *                                           each other (three grid-wide waits per layer-step);
- *                   REMOE_DECODE_PIPELINED  the layers of a step overlap: while layer l's gate/up rows
- *                                           stream, layer l+1's router logits are computed and layer
- *                                           l-2's down rows are read, so no wait sits between two
- *                                           HBM streams (needs top_k * inter <= 4 per wavefront:
- *                                           top_k * inter <= 32 * compute units).
+ *                   REMOE_DECODE_PIPELINED  the layers of a step overlap.  The compute units are split
+ *                                           into 8 groups (one per XCD); group x owns layers x, x + 8,
+ *                                           ... and runs them as a software pipeline: while one of its
+ *                                           layers' gate/up rows stream, the next layers' router logits
+ *                                           and top-k are computed and an earlier layer's down rows are
+ *                                           read, so no wait sits between two HBM streams.  With
+ *                                           W = 8 * compute units / groups wavefronts per group (256
+ *                                           on MI355X; a device whose compute-unit count is not a
+ *                                           multiple of 8 runs as a single group) it needs
+ *                                           n_experts * hidden / 256 <= min(2048, 4 W) and
+ *                                           W * ceil(ceil(top_k * inter / W) / 3) <= 2048;
+ *                                           other shapes are refused with REMOE_E_UNSUPPORTED.
  *
  *   desc            bf16 layers without shared expert; hidden in {512, 1024, 2048, 4096},
  *                   inter % 8 == 0, top_k * inter <= 6144

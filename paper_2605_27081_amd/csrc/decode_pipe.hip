@@ -15,21 +15,29 @@
 //     barrier.  Iteration i of a step works on the group's layers number
 //         R(i)    partial router logits                                   -> published, tagged
 //         T(i-1)  top-k / softmax from the logits published an iteration ago (one wavefront per
-//                 workgroup, in turn; the result is used from the next iteration on)
+//                 workgroup, in turn; the result is first used at the end of the iteration)
 //         G(i-2)  gate/up rows of the selected experts, SwiGLU            -> published, tagged
 //         D(i-4)  down projection from the activations published two iterations ago
+//     in the order R, T, G, D.  G's activations are split statically over the wavefronts of the
+//     group; D's output rows are split statically over the workgroups and handed out one at a time
+//     inside a workgroup (an LDS counter), so its wavefronts reach the next barrier together
+//     however unevenly memory served them.
 //
 // Exchanged values carry the number of the layer-step that produced them (partial logits: fp32 and a
 // 32-bit tag; three SwiGLU activations of one wavefront: 3 x bf16 and a 16-bit tag, one 8-byte word),
 // so a reader needs no barrier: it polls (agent-scope loads, which bypass the per-XCD L2 and its stale
 // copies) until the tags match, and in steady state they already do; a missing word is asked for
-// again by the wavefront that needs it.  The polls and the first weight rows of the next iteration
-// are issued before the last activation of the current one is reduced, so HBM keeps streaming across
-// iterations.  bf16 activations are what the batched path stores between its two GEMMs as well; they
-// let the gate/up and the down products run as packed bf16 dot instructions (exact products, fp32
-// accumulation) against x and h kept in bf16 in LDS.  Steps stay strictly sequential: a grid barrier
-// over all workgroups closes every step (the statistics of step t+1 need those of step t, and a
-// decoder would need the step's output before it has the next input).
+// again by the wavefront that needs it.  Everything an iteration needs at its start is requested from
+// inside the previous one (the polls before its down projection, the router segments and the first
+// gate / up rows behind it), so HBM keeps streaming across iterations.  The streaming loops are
+// branch-free with a fixed number of loads per unit of work: the compiler's wait counts then let one
+// register set be reduced while the other's loads stay in flight.  Weight pointers come out of the
+// launch's table through scalar loads (a vector load would sit in the same in-order queue as the
+// weight stream).  bf16 activations are what the batched path stores between its two GEMMs as well;
+// they let the gate/up and the down products run as packed bf16 dot instructions (exact products,
+// fp32 accumulation) against x and h kept in bf16 in LDS.  Steps stay strictly sequential: a grid
+// barrier over all workgroups closes every step (the statistics of step t+1 need those of step t, and
+// a decoder would need the step's output before it has the next input).
 //
 // One workgroup of 8 wavefronts per compute unit; every wait is bounded as in the chained kernel.
 #include "common.h"
