@@ -56,6 +56,11 @@ def lib() -> ctypes.CDLL:
         _lib.oracle_remoe_losses.restype = _c_int
         _lib.oracle_remoe_losses.argtypes = [_c_ptr, _c_ptr, _c_ptr, _c_i64, _c_i64, _c_int, _c_int, _c_ptr, _c_int,
                                              _c_int, _c_ptr]
+        _lib.oracle_remoe_loss_grad.restype = _c_int
+        _lib.oracle_remoe_loss_grad.argtypes = [_c_ptr, _c_ptr, _c_ptr, _c_i64, _c_i64, _c_int, _c_int, _c_ptr, _c_int,
+                                                _c_int, _c_ptr, _c_ptr]
+        _lib.oracle_gate_grad.restype = _c_int
+        _lib.oracle_gate_grad.argtypes = [_c_ptr, _c_ptr, _c_i64, _c_int, _c_int, _c_ptr, _c_i64, _c_ptr]
     return _lib
 
 
@@ -268,4 +273,39 @@ def remoe_losses(probs: torch.Tensor, probs_ref: torch.Tensor, idx: torch.Tensor
                                    _p(out))
     if rc != 0:
         raise ValueError(f"oracle_remoe_losses failed ({rc})")
+    return out
+
+
+def remoe_loss_grad(probs: torch.Tensor, probs_ref: torch.Tensor, idx: torch.Tensor, lags: Sequence[int], window: int,
+                    coef: Sequence[float]):
+    """d(sum_i coef[i] L_i)/d(logits) per sequence, L_i in the order Reuse, Trust, Smooth, Lag, WS
+    (Eq. 3, 6-12 through the softmax): fp64 [S, T, N]."""
+    probs, probs_ref, idx = _chk(probs, torch.float32), _chk(probs_ref, torch.float32), _chk(idx, torch.int32)
+    S, T, N = probs.shape
+    lg = torch.tensor(list(lags), dtype=torch.int32)
+    cf = torch.tensor(list(coef), dtype=torch.float64)
+    assert cf.numel() == 5
+    out = torch.zeros(S, T, N, dtype=torch.float64)
+    rc = lib().oracle_remoe_loss_grad(_p(probs), _p(probs_ref), _p(idx), S, T, N, idx.shape[2], _p(lg), len(lags), window,
+                                      _p(cf), _p(out))
+    if rc != 0:
+        raise ValueError(f"oracle_remoe_loss_grad failed ({rc})")
+    return out
+
+
+def gate_grad(dz: torch.Tensor, x: torch.Tensor, pick: Optional[torch.Tensor] = None):
+    """dL/dW_r = dz^T x (router without bias, Sec. 3.1): fp64 [N, H], or the picked (e, h) entries only."""
+    dz, x = _chk(dz, torch.float32), _chk(x.float(), torch.float32)
+    T, N = dz.shape
+    H = x.shape[1]
+    assert x.shape[0] == T
+    if pick is not None:
+        pick = _chk(pick, torch.int32)
+        out = torch.zeros(pick.shape[0], dtype=torch.float64)
+        rc = lib().oracle_gate_grad(_p(dz), _p(x), T, N, H, _p(pick), pick.shape[0], _p(out))
+    else:
+        out = torch.zeros(N, H, dtype=torch.float64)
+        rc = lib().oracle_gate_grad(_p(dz), _p(x), T, N, H, None, 0, _p(out))
+    if rc != 0:
+        raise ValueError(f"oracle_gate_grad failed ({rc})")
     return out
