@@ -368,6 +368,46 @@ remoe_status remoe_loss_forward(const float *probs, const float *probs_ref, cons
                                 const int32_t *lags, int32_t n_lags, int32_t window, double *out,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * remoe_loss_backward -- gradient of the weighted sum of the regularisers above with respect to the
+ * router logits (the backward pass of the gate-only fine-tuning step, Sec. 4.1 step 6; Eq. 3, 6):
+ *
+ *   L[s] = coef[0] L_Reuse + coef[1] L_Trust + coef[2] L_Smooth + coef[3] L_Lag + coef[4] L_WS,
+ *   dlogits[s, t, k] = dL[s] / dz[s, t, k]   with P_t = softmax(z_t):
+ *                      P_t[k] (g[k] - sum_j P_t[j] g[j]),  g = dL[s] / dP_t entry by entry.
+ *
+ * The previous routed set in the reuse mass and the snapshot router's distribution are constants
+ * (stop-gradient, Eq. 2 and Eq. 4); both arguments of every SymKL carry gradient (Sec. 4.4 says so
+ * for L_Smooth; taken for L_Lag as well).  Entries with P_t[k] = 0 get 0.  Computed in fp64 from
+ * the fp32 probabilities, stored as fp32.  Sequences are independent: a mean over sequences is a
+ * factor 1/S in coef.
+ *
+ *   probs, probs_ref, idx, lags, n_lags, window   as for remoe_loss_forward
+ *   coef          HOST array of 5 doubles (warm-up factor and the lambdas of Eq. 3, 6 folded in)
+ *   loss_values   DEVICE [S, 6] double: the output of remoe_loss_forward on the same inputs (rho is
+ *                 read from it)
+ *   dlogits       DEVICE [S, T, N_r] fp32, written
+ *   workspace     remoe_loss_backward_workspace_bytes(S, T, N_r, window) bytes, 8-byte aligned
+ *
+ * remoe_gate_grad -- the gate gradient of a router without bias (Sec. 3.1: z_t = W_r x_t):
+ *   dw[e, h] = sum_t dlogits[t, e] x[t, h]        (fp32 matrix cores, fp32 accumulation; the sum over
+ *   tokens is split into chunks whose partial results are added in a fixed order: results repeat
+ *   bit for bit)
+ *   dlogits [T, N_r] fp32 (all sequences flattened); x [T, H] of x_dtype (REMOE_F32 / REMOE_BF16);
+ *   dw [N_r, H] fp32, overwritten; workspace remoe_gate_grad_workspace_bytes(T, N_r, H) bytes,
+ *   256-byte aligned.  n_experts <= 128, hidden % 64 == 0.
+ */
+size_t remoe_loss_backward_workspace_bytes(int64_t n_seq, int64_t n_steps, int32_t n_experts, int32_t window);
+remoe_status remoe_loss_backward(const float *probs, const float *probs_ref, const int32_t *idx,
+                                 int64_t n_seq, int64_t n_steps, int32_t n_experts, int32_t top_k,
+                                 const int32_t *lags, int32_t n_lags, int32_t window, const double *coef,
+                                 const double *loss_values, float *dlogits,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+size_t remoe_gate_grad_workspace_bytes(int64_t n_tokens, int32_t n_experts, int32_t hidden);
+remoe_status remoe_gate_grad(const float *dlogits, const void *x, int32_t x_dtype, int64_t n_tokens,
+                             int32_t n_experts, int32_t hidden, float *dw,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,6 +28,10 @@ from .binding import (  # noqa: F401
     moe_route,
     PROF_KINDS,
     remoe_last_error,
+    remoe_gate_grad,
+    remoe_gate_grad_workspace_bytes,
+    remoe_loss_backward,
+    remoe_loss_backward_workspace_bytes,
     remoe_loss_forward,
     remoe_loss_workspace_bytes,
     remoe_profile_enable,

@@ -92,6 +92,15 @@ def load_library() -> ctypes.CDLL:
     lib.remoe_loss_workspace_bytes.argtypes = [I64]
     lib.remoe_loss_forward.restype = ctypes.c_int
     lib.remoe_loss_forward.argtypes = [P, P, P, I64, I64, I32, I32, ctypes.POINTER(I32), I32, I32, P, P, SZ, P]
+    lib.remoe_loss_backward_workspace_bytes.restype = SZ
+    lib.remoe_loss_backward_workspace_bytes.argtypes = [I64, I64, I32, I32]
+    lib.remoe_loss_backward.restype = ctypes.c_int
+    lib.remoe_loss_backward.argtypes = [P, P, P, I64, I64, I32, I32, ctypes.POINTER(I32), I32, I32,
+                                        ctypes.POINTER(ctypes.c_double), P, P, P, SZ, P]
+    lib.remoe_gate_grad_workspace_bytes.restype = SZ
+    lib.remoe_gate_grad_workspace_bytes.argtypes = [I64, I32, I32]
+    lib.remoe_gate_grad.restype = ctypes.c_int
+    lib.remoe_gate_grad.argtypes = [P, P, I32, I64, I32, I32, P, P, SZ, P]
     _lib = lib
     return lib
 
@@ -261,3 +270,32 @@ def remoe_loss_forward(probs: torch.Tensor, probs_ref: torch.Tensor, idx: torch.
     _check(load_library().remoe_loss_forward(_ptr(probs), _ptr(probs_ref), _ptr(idx), n_seq, n_steps, n_experts,
                                              idx.shape[2], lg, len(lags), window, _ptr(out), _ptr(workspace),
                                              workspace.numel() * workspace.element_size(), _stream()))
+
+
+def remoe_loss_backward_workspace_bytes(n_seq: int, n_steps: int, n_experts: int, window: int) -> int:
+    return int(load_library().remoe_loss_backward_workspace_bytes(n_seq, n_steps, n_experts, window))
+
+
+def remoe_loss_backward(probs: torch.Tensor, probs_ref: torch.Tensor, idx: torch.Tensor, lags, window: int, coef,
+                        loss_values: torch.Tensor, dlogits: torch.Tensor, workspace: torch.Tensor) -> None:
+    """coef: 5 host floats (Reuse, Trust, Smooth, Lag, WS); loss_values fp64 [S, 6] from remoe_loss_forward;
+    dlogits fp32 [S, T, N] (written)."""
+    n_seq, n_steps, n_experts = probs.shape
+    lg = (ctypes.c_int32 * max(len(lags), 1))(*lags)
+    cf = (ctypes.c_double * 5)(*[float(c) for c in coef])
+    _check(load_library().remoe_loss_backward(_ptr(probs), _ptr(probs_ref), _ptr(idx), n_seq, n_steps, n_experts,
+                                              idx.shape[2], lg, len(lags), window, cf, _ptr(loss_values), _ptr(dlogits),
+                                              _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def remoe_gate_grad_workspace_bytes(n_tokens: int, n_experts: int, hidden: int) -> int:
+    return int(load_library().remoe_gate_grad_workspace_bytes(n_tokens, n_experts, hidden))
+
+
+def remoe_gate_grad(dlogits: torch.Tensor, x: torch.Tensor, dw: torch.Tensor, workspace: torch.Tensor) -> None:
+    """dlogits fp32 [T, N]; x [T, H] fp32 or bf16; dw fp32 [N, H] (overwritten)."""
+    n_tokens, n_experts = dlogits.shape
+    hidden = x.shape[1]
+    code = REMOE_BF16 if x.dtype == torch.bfloat16 else REMOE_F32
+    _check(load_library().remoe_gate_grad(_ptr(dlogits), _ptr(x), code, n_tokens, n_experts, hidden, _ptr(dw),
+                                          _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))

@@ -534,5 +534,54 @@ remoe_status remoe_loss_forward(const float *probs, const float *probs_ref, cons
                                static_cast<hipStream_t>(stream));
 }
 
+size_t remoe_loss_backward_workspace_bytes(int64_t n_seq, int64_t n_steps, int32_t n_experts, int32_t window)
+{
+    if (n_seq < 0 || n_steps < 0 || n_experts < 1 || window < 1) return 0;
+    return loss_backward_workspace_bytes(n_seq, n_steps, n_experts, window);
+}
+
+remoe_status remoe_loss_backward(const float *probs, const float *probs_ref, const int32_t *idx, int64_t n_seq,
+                                 int64_t n_steps, int32_t n_experts, int32_t top_k, const int32_t *lags, int32_t n_lags,
+                                 int32_t window, const double *coef, const double *loss_values, float *dlogits,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    remoe_status st = validate_trace(idx, n_seq, n_steps, top_k, n_experts);
+    if (st != REMOE_OK) return st;
+    if (n_lags < 0 || n_lags > 8 || (n_lags > 0 && !lags)) return fail(REMOE_E_INVALID_ARG, "n_lags %d outside 0..8 or lags is NULL", n_lags);
+    for (int i = 0; i < n_lags; ++i)
+        if (lags[i] < 1) return fail(REMOE_E_INVALID_ARG, "lag %d must be positive", lags[i]);
+    if (window < 1) return fail(REMOE_E_INVALID_ARG, "window %d must be positive", window);
+    if (!coef) return fail(REMOE_E_INVALID_ARG, "coef is NULL");
+    for (int i = 0; i < 5; ++i)
+        if (!(coef[i] == coef[i]) || coef[i] - coef[i] != 0.0) return fail(REMOE_E_INVALID_ARG, "coef[%d] is not finite", i);
+    if (n_seq == 0 || n_steps == 0) return REMOE_OK;
+    if (!probs || !probs_ref || !loss_values || !dlogits) return fail(REMOE_E_INVALID_ARG, "a required pointer is NULL");
+    const size_t need = loss_backward_workspace_bytes(n_seq, n_steps, n_experts, window);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 7))
+        return fail(REMOE_E_WORKSPACE, "remoe_loss_backward needs an 8-byte aligned workspace of %zu bytes", need);
+    return launch_loss_backward(probs, probs_ref, idx, n_seq, n_steps, n_experts, top_k, lags, n_lags, window, coef,
+                                loss_values, dlogits, workspace, static_cast<hipStream_t>(stream));
+}
+
+size_t remoe_gate_grad_workspace_bytes(int64_t n_tokens, int32_t n_experts, int32_t hidden)
+{
+    if (n_tokens < 0 || n_experts < 1 || hidden < 1) return 0;
+    return gate_grad_workspace_bytes(n_tokens, n_experts, hidden);
+}
+
+remoe_status remoe_gate_grad(const float *dlogits, const void *x, int32_t x_dtype, int64_t n_tokens, int32_t n_experts,
+                             int32_t hidden, float *dw, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (n_tokens < 0 || n_experts < 1 || n_experts > 128 || hidden < 1)
+        return fail(REMOE_E_INVALID_ARG, "remoe_gate_grad: n_tokens %lld, n_experts %d (1..128), hidden %d", (long long)n_tokens,
+                    n_experts, hidden);
+    if (x_dtype != REMOE_F32 && x_dtype != REMOE_BF16) return fail(REMOE_E_INVALID_ARG, "x_dtype %d is neither REMOE_F32 nor REMOE_BF16", x_dtype);
+    if (!dw || (n_tokens > 0 && (!dlogits || !x))) return fail(REMOE_E_INVALID_ARG, "a required pointer is NULL");
+    const size_t need = gate_grad_workspace_bytes(n_tokens, n_experts, hidden);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))
+        return fail(REMOE_E_WORKSPACE, "remoe_gate_grad needs a 256-byte aligned workspace of %zu bytes", need);
+    return launch_gate_grad(dlogits, x, x_dtype, n_tokens, n_experts, hidden, dw, workspace, static_cast<hipStream_t>(stream));
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

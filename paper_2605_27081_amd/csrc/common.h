@@ -162,6 +162,15 @@ remoe_status launch_loss_forward(const float *probs, const float *probs_ref, con
                                  int N, int K, const int32_t *lags, int n_lags, int window, double *out, void *workspace,
                                  hipStream_t stream);
 
+// Gradient of the regularisers with respect to the router logits; gate gradient dz^T x.
+size_t loss_backward_workspace_bytes(int64_t S, int64_t T, int N, int window);
+remoe_status launch_loss_backward(const float *probs, const float *probs_ref, const int32_t *idx, int64_t S, int64_t T,
+                                  int N, int K, const int32_t *lags, int n_lags, int window, const double *coef,
+                                  const double *loss_values, float *dlogits, void *workspace, hipStream_t stream);
+size_t gate_grad_workspace_bytes(int64_t T, int N, int H);
+remoe_status launch_gate_grad(const float *dz, const void *x, int x_dtype, int64_t T, int N, int H, float *dw, void *workspace,
+                              hipStream_t stream);
+
 // Plain copy of known size (yardstick for hardware byte counters).
 remoe_status launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t stream);
 

@@ -37,9 +37,7 @@ constexpr int DC_SEG = DEC_SEG;
 constexpr int DC_MAX_KI = 6144;      // K * I floats of h staged in LDS (24 KB)
 constexpr int DC_MAX_CAPS = DEC_MAX_CAPS;
 constexpr int DC_MAX_GRID = DEC_MAX_GRID;
-constexpr int DC_FLAG_BYTES = DEC_FLAG_BYTES;
 constexpr int DC_MAX_LAYERS = DEC_MAX_LAYERS;
-constexpr int DC_ITEM_BATCH = 3;     // gate/up activations a wavefront has in flight
 constexpr int DC_MAX_DCH = 12;       // down-projection chunks per lane per output row (K * I <= 6144)
 
 struct DecodeArgs {
