@@ -156,14 +156,19 @@ struct GateArgs {
     float *dw;                          // [N, H]
 };
 
+// loads through pointers known to point to device memory (global, not flat, address space)
+__device__ __forceinline__ float load_global_f32(const void *p) { return *(const __attribute__((address_space(1))) float *)p; }
 template <class XT> __device__ __forceinline__ float x_as_float(const XT *p);
-template <> __device__ __forceinline__ float x_as_float<float>(const float *p) { return *p; }
-template <> __device__ __forceinline__ float x_as_float<bf16_t>(const bf16_t *p) { return __uint_as_float((uint32_t)*p << 16); }
+template <> __device__ __forceinline__ float x_as_float<float>(const float *p) { return load_global_f32(p); }
+template <> __device__ __forceinline__ float x_as_float<bf16_t>(const bf16_t *p)
+{
+    return __uint_as_float((uint32_t)(*(const __attribute__((address_space(1))) bf16_t *)p) << 16);
+}
 
 template <class XT, int NE>
 __global__ __launch_bounds__(GG_WAVES * 64) void gate_grad_partial_kernel(const GateArgs a)
 {
-    __shared__ float red[GG_WAVES - 1][NE * GG_NH * 16 * 64];   // accumulators of wavefronts 1..3
+    __shared__ float red[NE * GG_NH * 16 * 64];   // one wavefront's accumulators at a time
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 31, lh = lane >> 5;
     const int h0 = blockIdx.x * GG_COLS;
@@ -186,30 +191,82 @@ __global__ __launch_bounds__(GG_WAVES * 64) void gate_grad_partial_kernel(const 
     int64_t t_lo = wg_lo + wave * per_wave, t_hi = t_lo + per_wave;
     if (t_hi > wg_hi) t_hi = wg_hi;
 
-    for (int64_t tp = t_lo; tp < t_hi; tp += 2) {
-        const int64_t t = tp + lh;                       // k index of the instruction = which token of the pair
-        const bool ok = t < t_hi;
-        float av[NE], bv[GG_NH];
+    // GG_UN token pairs per pass.  The operand loads of the next pass are issued before the MFMAs of
+    // the current one (two register sets), so that a wavefront alone on its SIMD still overlaps load
+    // latency with matrix-core work.  Loads are unconditional (clamped indices) and masked by a
+    // multiplication: a conditional load is a branch, and behind every branch the compiler waits for
+    // all loads in flight.  (What a masked load reads is other tokens' or experts' data of the same call.)
+    constexpr int GG_UN = 2;
+    const int n_tok = (int)(t_hi > t_lo ? t_hi - t_lo : 0);
+    const int n_pairs = (n_tok + 1) >> 1;
+    const char *dz_w = reinterpret_cast<const char *>(a.dz + t_lo * N);
+    const char *x_w = reinterpret_cast<const char *>(x + t_lo * H + h0);
+    uint32_t dz_col[NE];
+    float col_live[NE];
 #pragma unroll
-        for (int e = 0; e < NE; ++e) av[e] = (ok && e * 32 + li < N) ? a.dz[t * N + e * 32 + li] : 0.f;
-#pragma unroll
-        for (int n = 0; n < GG_NH; ++n) bv[n] = ok ? x_as_float<XT>(x + t * H + h0 + n * 32 + li) : 0.f;
-#pragma unroll
-        for (int e = 0; e < NE; ++e)
-#pragma unroll
-            for (int n = 0; n < GG_NH; ++n) acc[e][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], bv[n], acc[e][n], 0, 0, 0);
+    for (int e = 0; e < NE; ++e) {
+        const int col = e * 32 + li;
+        dz_col[e] = (uint32_t)(col < N ? col : N - 1) * 4u;
+        col_live[e] = col < N ? 1.0f : 0.f;
     }
+#define GG_LOAD(av, bv, first_pair)                                                                      \
+    _Pragma("unroll") for (int u = 0; u < GG_UN; ++u) {                                                  \
+        const int t_ = 2 * ((first_pair) + u) + lh;      /* k index of the instruction = which token of the pair */ \
+        const int tc_ = t_ < n_tok ? t_ : n_tok - 1;                                                     \
+        _Pragma("unroll") for (int e = 0; e < NE; ++e)                                                   \
+            av[u][e] = load_global_f32(dz_w + (uint32_t)(tc_ * N) * 4u + dz_col[e]);                     \
+        _Pragma("unroll") for (int n = 0; n < GG_NH; ++n)                                                \
+            bv[u][n] = x_as_float<XT>(reinterpret_cast<const XT *>(x_w + (uint32_t)(tc_ * H + n * 32 + li) * (uint32_t)sizeof(XT))); \
+    }
+    // the masks are applied here, not where the values are requested: a use right behind a load is a wait
+#define GG_MFMA(av, bv, first_pair)                                                                      \
+    _Pragma("unroll") for (int u = 0; u < GG_UN; ++u) {                                                  \
+        const float live_ = (2 * ((first_pair) + u) + lh < n_tok) ? 1.0f : 0.f;                          \
+        _Pragma("unroll") for (int e = 0; e < NE; ++e)                                                   \
+            _Pragma("unroll") for (int n = 0; n < GG_NH; ++n)                                            \
+                acc[e][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][e] * col_live[e], bv[u][n] * live_, acc[e][n], 0, 0, 0); \
+    }
+    if (n_tok > 0) {
+        float avA[GG_UN][NE], bvA[GG_UN][GG_NH], avB[GG_UN][NE], bvB[GG_UN][GG_NH];
+        GG_LOAD(avA, bvA, 0)
+#pragma unroll 1
+        for (int i = 0; i < n_pairs; i += 2 * GG_UN) {
+            __builtin_amdgcn_sched_barrier(0);
+            GG_LOAD(avB, bvB, i + GG_UN)                 // past the end: clamped and masked to zero
+            __builtin_amdgcn_sched_barrier(0);
+            GG_MFMA(avA, bvA, i)
+            __builtin_amdgcn_sched_barrier(0);
+            GG_LOAD(avA, bvA, i + 2 * GG_UN)
+            __builtin_amdgcn_sched_barrier(0);
+            GG_MFMA(avB, bvB, i + GG_UN)
+        }
+    }
+#undef GG_LOAD
+#undef GG_MFMA
 
-    // add the four wavefronts' accumulators in wavefront order, then write the workgroup's tile
-    if (wave > 0) {
+    // add the four wavefronts' accumulators in wavefront order (one at a time through one LDS buffer:
+    // a small LDS footprint lets several workgroups share a compute unit and hide each other's load
+    // latency), then write the workgroup's tile
+    for (int w = 1; w < GG_WAVES; ++w) {
+        if (wave == w) {
 #pragma unroll
-        for (int e = 0; e < NE; ++e)
+            for (int e = 0; e < NE; ++e)
 #pragma unroll
-            for (int n = 0; n < GG_NH; ++n)
+                for (int n = 0; n < GG_NH; ++n)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) red[wave - 1][((e * GG_NH + n) * 16 + r) * 64 + lane] = acc[e][n][r];
+                    for (int r = 0; r < 16; ++r) red[((e * GG_NH + n) * 16 + r) * 64 + lane] = acc[e][n][r];
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+#pragma unroll
+                for (int n = 0; n < GG_NH; ++n)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[e][n][r] += red[((e * GG_NH + n) * 16 + r) * 64 + lane];
+        }
+        __syncthreads();
     }
-    __syncthreads();
     if (wave == 0) {
         float *out = a.partial + (int64_t)chunk * N * H;
 #pragma unroll
@@ -218,10 +275,8 @@ __global__ __launch_bounds__(GG_WAVES * 64) void gate_grad_partial_kernel(const 
             for (int n = 0; n < GG_NH; ++n)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float v = acc[e][n][r];
-                    for (int w = 0; w < GG_WAVES - 1; ++w) v += red[w][((e * GG_NH + n) * 16 + r) * 64 + lane];
                     const int row = e * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);     // expert
-                    if (row < N) out[(int64_t)row * H + h0 + n * 32 + li] = v;
+                    if (row < N) out[(int64_t)row * H + h0 + n * 32 + li] = acc[e][n][r];
                 }
     }
 }
