@@ -87,6 +87,8 @@ def _check_decode(desc, layers, x, caps, expert_bytes, out, renorm):
     (2, 33, 1024, 60, 128, 4, False, [12], [1, 1, 7, 24]),          # online: fed in pieces
     (4, 24, 2048, 128, 768, 8, True, [16, 32, 64], [10, 14]),       # the Qwen3-30B-A3B layer shape
     (1, 17, 512, 8, 64, 8, False, [2, 8, 9, 3], [17]),              # K = N, C < K, four capacities
+    (20, 9, 512, 32, 128, 4, True, [8], [4, 5]),                    # groups of compute units with 3 and with 2 layers
+    (64, 5, 512, 16, 64, 2, True, [4, 16], [5]),                    # the largest layer count
 ])
 def test_decode_matches_oracle(L, T, H, N, I, K, renorm, caps, pieces, order):
     _say(f"decode order={order} L={L} T={T} H={H} N={N} I={I} K={K} caps={caps} pieces={pieces}")
