@@ -234,8 +234,9 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             __builtin_amdgcn_sched_barrier(0);                                                      \
         }
     // k-steps of one slice: fragments of step ks+1 are read while the MFMAs of step ks run.  MID runs
-    // after the MFMAs of step 2, when every fragment of the stage has been requested: it waits for
-    // them, passes a barrier and may then refill the stage, a k-step before the slice ends.
+    // behind the MFMAs of step 1, as soon as every fragment of the stage has been requested: it waits
+    // for them (the matrix cores are still busy with step 1), passes a barrier and may then refill the
+    // stage, two k-steps before the slice ends, so a copy has a slice and a half of MFMA time to land.
 #define GM_COMPUTE(la, lb, MID, LAST)                                                                   \
     {                                                                                               \
         bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];                                                \
@@ -250,11 +251,11 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         __builtin_amdgcn_sched_barrier(0);                                                          \
         GM_READ_FRAGS(la, lb, 3, fa1, fb1)                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
-        GM_MFMA(fa0, fb0)                                                                           \
-        __builtin_amdgcn_sched_barrier(0);                                                          \
         MID                                                                                         \
         __builtin_amdgcn_sched_barrier(0);                                                          \
-        LAST(fa1, fb1)                                                                              \
+        LAST(fa0, fb0)                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        GM_MFMA(fa1, fb1)                                                                           \
     }
     // Workgroup barrier that orders LDS traffic only.  (__syncthreads would also wait for every
     // direct-to-LDS copy in flight.)
