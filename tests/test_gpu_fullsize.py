@@ -107,3 +107,59 @@ def test_qwen3_prefill_full_layers():
     assert cfg.expert_bytes == 9_437_184
     _check_layer(cfg, 0, 0.8, n_route=4096, n_out=64)
     _check_layer(cfg, 47, 0.8, n_route=2048, n_out=32)
+
+
+def test_qwen3_decode_full_stack():
+    """All 48 layers resident (54 GiB), launches of 128 steps as bench.py times them.  Every layer-step's
+    statistics are compared bit for bit on the complete traces; routing and layer outputs on the
+    layers the oracle is given (it evaluates their tokens one by one)."""
+    cfg = wl.get_config("qwen3_decode")
+    L, H, K, N = cfg.n_layers, cfg.hidden, cfg.top_k, cfg.n_experts
+    T = 256                                      # two launches of 128 steps
+    caps = list(cfg.capacities)
+    _say(f"full size {cfg.name}: {L} layers x {T} steps")
+    desc = remoe.LayerDesc.from_config(cfg)
+    x = wl.hidden_states(cfg, cfg.rhos[-1], device=DEV).reshape(cfg.seq_len, H)[:T].contiguous()
+    weights = [wl.layer_weights(cfg, l, device=DEV) for l in range(L)]
+    table = torch.tensor([[w["w_router"].data_ptr(), w["w_gate"].data_ptr(), w["w_up"].data_ptr(),
+                           w["w_down"].data_ptr()] for w in weights], dtype=torch.int64, device=DEV)
+    y = torch.full((T, L, H), float("nan"), dtype=torch.bfloat16, device=DEV)
+    idx = torch.full((L, T, K), -1, dtype=torch.int32, device=DEV)
+    gw = torch.full((L, T, K), float("nan"), dtype=torch.float32, device=DEV)
+    state = torch.zeros(L, N, dtype=torch.int32, device=DEV)
+    ov = torch.full((L, T), 255, dtype=torch.uint8, device=DEV)
+    miss = torch.full((len(caps), L, T), 255, dtype=torch.uint8, device=DEV)
+    sum_ov = torch.zeros(L, dtype=torch.int64, device=DEV)
+    tot = torch.zeros(len(caps), L, dtype=torch.int64, device=DEV)
+    nbytes = torch.zeros(len(caps), L, dtype=torch.int64, device=DEV)
+    ws = torch.zeros(remoe.remoe_decode_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    for pos in range(0, T, 128):
+        remoe.moe_decode(desc, table, x, pos, 128, y, idx, gw, caps, cfg.expert_bytes, state, ov, miss, sum_ov, tot,
+                         nbytes, ws, 0, remoe.REMOE_DECODE_PIPELINED)
+    torch.cuda.synchronize()
+    assert int(ws[128:132].view(torch.int32)[0]) == 0, "a wait inside the kernel timed out"
+    # ---- properties of every layer-step
+    assert torch.isfinite(y.float()).all()
+    assert (idx >= 0).all() and (idx < N).all()
+    srt = torch.sort(idx, 2).values
+    assert (srt[..., 1:] != srt[..., :-1]).all(), "a step selected an expert twice"
+    assert torch.allclose(gw.sum(2), torch.ones(L, T, device=DEV), atol=1e-5)
+    # ---- statistics, complete traces
+    tr = idx.cpu()
+    rov, rsum = oracle.trace_reuse(tr, N)
+    assert torch.equal(ov.cpu(), rov) and torch.equal(sum_ov.cpu(), rsum)
+    for c, cap in enumerate(caps):
+        rmiss, rtot, rb = oracle.lru_list(tr, N, cap, cfg.expert_bytes)
+        assert torch.equal(miss[c].cpu(), rmiss), f"LRU misses differ at capacity {cap}"
+        assert torch.equal(tot[c].cpu(), rtot) and torch.equal(nbytes[c].cpu(), rb)
+    # ---- routing and outputs of sampled layers (first, one of a group with uneven position, last)
+    xc = x.cpu()
+    steps = torch.tensor([0, 1, 63, 127, 128, 200, 255])
+    worst = 0.0
+    for l in (0, 13, 47):
+        wc = to_oracle_weights(weights[l])
+        orc = oracle.route(xc, wc["w_router"], K, cfg.renorm, want_probs=True)
+        _, exp_w = compare_routing(idx[l], gw[l], orc, cfg.renorm)
+        y_ref = oracle.experts_sparse(xc[steps], idx[l].cpu()[steps], exp_w[steps], wc)
+        worst = max(worst, check_output(y[steps.to(DEV), l], y_ref, cfg.dtype))
+    _say(f"  3 layers x {T} steps routed, {len(steps)} steps each evaluated: worst rel L2 {worst:.3e}")
