@@ -153,6 +153,7 @@ Workspace layout(const remoe_layer_desc *d, int64_t T, void *base_v)
     carve(base, off, w.pb.tile_row0, sizeof(int32_t) * w.max_tiles);
     carve(base, off, w.pb.tile_rows, sizeof(int32_t) * w.max_tiles);
     carve(base, off, w.pb.n_tiles, sizeof(int32_t));
+    carve(base, off, w.pb.gemm_ctr, sizeof(uint32_t) * GEMM_CTR_SETS * 8);
     carve(base, off, w.pb.pair_slot, sizeof(int32_t) * pairs);
     carve(base, off, w.pb.slot_token, sizeof(int32_t) * pairs);
     carve(base, off, w.pb.slot_w, sizeof(float) * pairs);
@@ -302,6 +303,7 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
     g.tile_expert = ws.pb.tile_expert; g.tile_row0 = ws.pb.tile_row0; g.tile_rows = ws.pb.tile_rows;
     g.n_tiles = ws.pb.n_tiles; g.max_tiles = ws.max_tiles;
     g.c = ws.hbuf; g.ldc = I; g.c_row_offset = 0;
+    g.tile_ctr = ws.pb.gemm_ctr;
     {
         ProfScope prof(REMOE_PROF_GATE_UP, stream);
         st = gemm(0, g);
@@ -310,6 +312,7 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
     g.a = ws.hbuf; g.lda = I; g.a_rows = T * K; g.row_gather = nullptr;
     g.b0 = w_down; g.b1 = nullptr; g.k_dim = I; g.n_out = H;
     g.row_scale = ws.pb.slot_w; g.c = ws.rows; g.ldc = H;
+    g.tile_ctr = ws.pb.gemm_ctr + 8;
     {
         ProfScope prof(REMOE_PROF_DOWN, stream);
         st = gemm(1, g);
@@ -321,6 +324,7 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
         s.a = x; s.lda = H; s.a_rows = T; s.b0 = ws_gate; s.b1 = ws_up; s.k_dim = H; s.n_out = Is;
         s.dense_rows = T; s.max_tiles = (int)ceil_div(T, gemm_tile_m());
         s.c = ws.hsbuf; s.ldc = Is;
+        s.tile_ctr = ws.pb.gemm_ctr + 16;
         {
             ProfScope prof(REMOE_PROF_SHARED_GATE_UP, stream);
             st = gemm(0, s);
@@ -328,6 +332,7 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
         if (st != REMOE_OK) return st;
         s.a = ws.hsbuf; s.lda = Is; s.a_rows = T; s.b0 = ws_down; s.b1 = nullptr; s.k_dim = Is; s.n_out = H;
         s.c = ws.rows; s.ldc = H; s.c_row_offset = T * K;
+        s.tile_ctr = ws.pb.gemm_ctr + 24;
         {
             ProfScope prof(REMOE_PROF_SHARED_DOWN, stream);
             st = gemm(1, s);

@@ -81,7 +81,9 @@ struct PermuteBuffers {
     int32_t *pair_slot;    // [T*K]        (token, j) -> slot
     int32_t *slot_token;   // [T*K]        slot -> token
     float *slot_w;         // [T*K]        slot -> gate weight
+    uint32_t *gemm_ctr;    // [GEMM_CTR_SETS * 8] tile counters of the layer's GEMM launches, zeroed by the permute step
 };
+constexpr int GEMM_CTR_SETS = 4;
 int permute_tokens_per_block();
 remoe_status launch_permute(const int32_t *idx, const float *w, int64_t T, int K, int N,
                             int tile_m, int max_tiles, const PermuteBuffers &pb, hipStream_t stream);
@@ -103,6 +105,7 @@ struct GroupedGemmArgs {
     void *c;                  // output [rows, ldc]
     int64_t ldc;
     int64_t c_row_offset;     // added to the output row index
+    uint32_t *tile_ctr;       // bf16 kernel: 8 tile counters (one per XCD), zero when the launch starts
 };
 int gemm_tile_m();
 remoe_status launch_grouped_gemm_bf16(int mode, const GroupedGemmArgs &g, hipStream_t stream);

@@ -72,7 +72,25 @@ struct KArgs {
     bf16_t *c;
     int64_t ldc;
     int64_t c_row_offset;
+    uint32_t *tile_ctr;          // [8] next unclaimed tile of each XCD's range, zero at launch
 };
+
+// Claims the next logical tile for a workgroup of XCD `home`: first from that XCD's own contiguous
+// range, and once that is used up from the ranges of the other XCDs, so that compute units that run
+// ahead (the XCDs do not all stream at the same speed) take over work instead of idling at the end
+// of the launch.  Returns -1 when every range is exhausted.
+__device__ __forceinline__ int claim_tile(uint32_t *ctr, int home, int chunk, int nblk)
+{
+    for (int k = 0; k < 8; ++k) {
+        const int x = (home + k) & 7;
+        const int lo = x * chunk;
+        const int n = (nblk - lo < chunk) ? nblk - lo : chunk;
+        if (n <= 0) continue;
+        const uint32_t i = __hip_atomic_fetch_add(&ctr[x], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (i < (uint32_t)n) return lo + (int)i;
+    }
+    return -1;
+}
 
 // WM x WN wavefronts, each owning TM x TN MFMA tiles of 32 x 32.
 template <int MODE, int WM, int WN, int TM, int TN>
@@ -92,22 +110,27 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     __shared__ float lds_scale[2][BM];         // mode 1: gate weight of each tile row (this tile / next tile)
     static_assert(BM == BN, "the epilogue stages its bands in the second A stage and the second B stage alike");
 
-    // Persistent workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs, so workgroup b is
-    // slot b / 8 of XCD b % 8.  XCD x owns the contiguous range [x * chunk, (x + 1) * chunk) of
-    // logical tiles (n-tile fastest) and its slots walk that range together: slot c takes tiles
-    // c, c + n_slots, ...  At any time the workgroups of one XCD therefore work on neighbouring
-    // tiles, which share A rows and expert weights through that XCD's L2.
+    // Persistent workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs, so workgroup b runs
+    // on XCD b % 8.  XCD x owns the contiguous range [x * chunk, (x + 1) * chunk) of logical tiles
+    // (n-tile fastest) and its workgroups claim the tiles of that range one after the other from a
+    // counter: at any time the workgroups of one XCD therefore work on neighbouring tiles, which share
+    // A rows and expert weights through that XCD's L2.  Tile numbers are claimed three tiles ahead of
+    // their use (the descriptor and the row indices of a tile are each fetched a tile ahead).
+    __shared__ int lds_claim[4];
     const int ntn = (p.n_out + BN_OUT - 1) / BN_OUT;
     const int n_mt = p.tile_expert ? *p.n_tiles : (p.dense_rows + BM - 1) / BM;
     const int nblk = n_mt * ntn;
     const int chunk = (nblk + 7) >> 3;
-    const int n_slots = gridDim.x >> 3;
-    const int tile0 = (blockIdx.x & 7) * chunk;                          // first logical tile of this XCD
-    const int q_end = (nblk - tile0 < chunk) ? nblk - tile0 : chunk;     // its tile count (may be <= 0)
-    int q = blockIdx.x >> 3;
-    if (q >= q_end) return;
-
+    const int home = blockIdx.x & 7;
     const int tid = threadIdx.x;
+    if (tid == 0) {
+        for (int j = 0; j < 3; ++j) lds_claim[j] = claim_tile(p.tile_ctr, home, chunk, nblk);
+    }
+    __syncthreads();
+    const int q0 = lds_claim[0];
+    int q_nx = lds_claim[1], q_nn = lds_claim[2];      // the next tile and the one after it (-1: none)
+    if (q0 < 0) return;
+
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lh = lane >> 5;
@@ -135,7 +158,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 
 #define GM_TILE_INFO(qq, E, R0, RS, NT)                                                             \
     {                                                                                               \
-        const int logical_ = tile0 + (qq);                                                          \
+        const int logical_ = (qq);                                                                  \
         const int mt_ = logical_ / ntn;                                                             \
         NT = logical_ - mt_ * ntn;                                                                  \
         if (p.tile_expert) {                                                                        \
@@ -332,24 +355,29 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     GM_LDS_BARRIER();                                                                               \
     GM_EPI_STORE(mi, st, e_row0, e_rows, e_nt)
 
-    GM_TILE_INFO(q, expert, row0, rows, nt)
+    GM_TILE_INFO(q0, expert, row0, rows, nt)
     GM_TILE_ROWS(row0, rows, a_row)
     GM_LOAD_SCALE(row0, rows, scale_reg)
     GM_TILE_OFFSETS()
     GM_FILL_SCALE(0)
     GM_COPY_SLICE(lds_a0, lds_b0, 0)
     // descriptor of this workgroup's next tile
-    bool has_next = q + n_slots < q_end;
+    bool has_next = q_nx >= 0;
     int nx_expert = 0, nx_row0 = 0, nx_rows = 1, nx_nt = 0;
-    if (has_next) GM_TILE_INFO(q + n_slots, nx_expert, nx_row0, nx_rows, nx_nt)
+    if (has_next) GM_TILE_INFO(q_nx, nx_expert, nx_row0, nx_rows, nx_nt)
 
     for (;;) {
         // Fetched under the main loop: the next tile's row indices and gate weights (its descriptor
         // arrived a tile ago) and the descriptor of the tile after it.
         int a_row_nx[A_CH];
         float scale_nx = 1.0f;
-        const bool has_nn = q + 2 * n_slots < q_end;
+        const bool has_nn = q_nn >= 0;
         int nn_expert = 0, nn_row0 = 0, nn_rows = 1, nn_nt = 0;
+        // the claim for the tile three ahead goes out now (this XCD's own counter) and is looked at
+        // when the main loop is over: nobody waits for the atomic's round trip
+        uint32_t claim_raw = 0;
+        if (threadIdx.x == 0 && has_nn)
+            claim_raw = __hip_atomic_fetch_add(&p.tile_ctr[home], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         {
             int tid_early = threadIdx.x;
             asm volatile("" : "+v"(tid_early));   // (index arithmetic redone here rather than kept in registers)
@@ -363,7 +391,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 #pragma unroll
                 for (int i = 0; i < A_CH; ++i) a_row_nx[i] = 0;
             }
-            if (has_nn) GM_TILE_INFO(q + 2 * n_slots, nn_expert, nn_row0, nn_rows, nn_nt)
+            if (has_nn) GM_TILE_INFO(q_nn, nn_expert, nn_row0, nn_rows, nn_nt)
         }
 
         floatx16_t acc[TM][TN];
@@ -392,6 +420,17 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             }
         }
 
+        // the claim made at the top of this tile: inside this XCD's range, or else one from another's
+        if (threadIdx.x == 0) {
+            int q3 = -1;
+            if (has_nn) {
+                const int lo = home * chunk;
+                const int n_home = (nblk - lo < chunk) ? nblk - lo : chunk;
+                q3 = (claim_raw < (uint32_t)(n_home > 0 ? n_home : 0)) ? lo + (int)claim_raw
+                                                                        : claim_tile(p.tile_ctr, home, chunk, nblk);
+            }
+            lds_claim[3] = q3;
+        }
         // Both stages are idle now.  The finished tile is written out band by band while the next
         // tile's row indices, offsets and first slice are fetched in between.
         // (Thread-index arithmetic of this phase is redone per tile from a value the optimiser
@@ -426,9 +465,9 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         if (TM > 3) { GM_EPI_BAND(3, lds_b1, e_row0, e_rows, e_nt, e_par) }
         static_assert(TM <= 4, "the epilogue is written out for up to four bands");
         if (!has_next) break;
-        q += n_slots;
         has_next = has_nn;
         nx_expert = nn_expert; nx_row0 = nn_row0; nx_rows = nn_rows; nx_nt = nn_nt;
+        q_nn = lds_claim[3];       // written before the epilogue's barriers
     }
 }
 
@@ -468,6 +507,8 @@ remoe_status launch_grouped_gemm_bf16(int mode, const GroupedGemmArgs &g, hipStr
     p.c = static_cast<bf16_t *>(g.c);
     p.ldc = g.ldc;
     p.c_row_offset = g.c_row_offset;
+    p.tile_ctr = g.tile_ctr;
+    if (!p.tile_ctr) return fail(REMOE_E_INVALID_ARG, "grouped_gemm_bf16 needs tile counters");
     // persistent launch: one workgroup per compute unit (a multiple of 8, one share per XCD), fewer
     // when the upper bound of tiles is smaller
     int dev = 0, n_cu = 0;

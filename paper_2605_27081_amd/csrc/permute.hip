@@ -55,10 +55,11 @@ __global__ __launch_bounds__(128) void permute_scan(const int32_t *__restrict__ 
                                                     int32_t *__restrict__ tile_expert,
                                                     int32_t *__restrict__ tile_row0,
                                                     int32_t *__restrict__ tile_rows,
-                                                    int32_t *__restrict__ n_tiles)
+                                                    int32_t *__restrict__ n_tiles, uint32_t *__restrict__ gemm_ctr)
 {
     __shared__ int32_t cnt[128], off[129], tstart[129];
     const int e = threadIdx.x;
+    if (e < GEMM_CTR_SETS * 8) gemm_ctr[e] = 0u;   // tile counters of the GEMM launches that follow
     int run = 0;
     if (e < N) {
 #pragma unroll 8
@@ -133,7 +134,7 @@ remoe_status launch_permute(const int32_t *idx, const float *w, int64_t T, int K
                        pb.pair_slot);
     hipLaunchKernelGGL(permute_scan, dim3(1), dim3(128), 0, stream, blk_hist, n_blk, N, tile_m,
                        max_tiles, blk_off, pb.offsets, pb.tile_expert, pb.tile_row0, pb.tile_rows,
-                       pb.n_tiles);
+                       pb.n_tiles, pb.gemm_ctr);
     const int64_t n_pairs = T * K;
     hipLaunchKernelGGL(permute_place, dim3((unsigned)ceil_div(n_pairs, 256)), dim3(256), 0, stream, idx,
                        w, n_pairs, K, N, blk_off, pb.offsets, pb.pair_slot, pb.slot_token, pb.slot_w);
