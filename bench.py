@@ -78,7 +78,7 @@ def counter_traffic(kernel, field):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures ONE GPU; run with --gpus 1 (no sharding or collectives exist here)",
+        print("bench.py: this library measures ONE GPU; run with --gpus 1 (no sharding or collectives exist here)",
               file=sys.stderr)
         return 2
 
