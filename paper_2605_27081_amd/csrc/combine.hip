@@ -31,7 +31,7 @@ template <> struct Vec<bf16_t> {
     static constexpr int N = 8;
     __device__ static __forceinline__ void load(const bf16_t *p, float *o)
     {
-        const uint4 v = *reinterpret_cast<const uint4 *>(p);
+        const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));   // every row is read once
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -41,12 +41,12 @@ template <> struct Vec<bf16_t> {
     }
     __device__ static __forceinline__ void store(bf16_t *p, const float *o)
     {
-        uint4 v;
+        u32x4_t v;
         v.x = pack_bf16x2(o[0], o[1]);
         v.y = pack_bf16x2(o[2], o[3]);
         v.z = pack_bf16x2(o[4], o[5]);
         v.w = pack_bf16x2(o[6], o[7]);
-        *reinterpret_cast<uint4 *>(p) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(p));
     }
 };
 

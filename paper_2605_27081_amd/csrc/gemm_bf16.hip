@@ -18,13 +18,16 @@
 // (global_load_lds_dwordx4, no staging registers): the copy of slice k+1 into the other LDS stage is
 // issued before the MFMAs of slice k and has that whole MFMA phase to land (one barrier per slice);
 // MFMA fragments are double-buffered in registers so LDS latency hides behind matrix-core work.
+// The MFMAs take the B rows as their first operand, so the accumulators hold the tile transposed:
+// a lane owns one output row and four adjacent columns per register group, which the epilogue packs
+// into 8-byte pieces of a row without exchanging values between lanes.
 //
 // Rows of A are gathered through slot -> token, so no permuted copy of x is ever materialised.
 // The tile list (expert, first slot, valid rows) comes from the permute step and lives in device
 // memory; the launch covers an upper bound of tiles and surplus workgroups return at once.
-// Workgroup ids are dealt round-robin to the 8 XCDs, so id b works on logical tile
-// (b % 8) * chunk + b / 8: every XCD walks one contiguous range (n-tile fastest), which keeps an
-// expert's weights and the current A rows hot in that XCD's L2.
+// Workgroup ids are dealt round-robin to the 8 XCDs; every XCD hands out one contiguous range of
+// logical tiles (n-tile fastest) to its workgroups in arrival order, which keeps an expert's weights
+// and the current A rows hot in that XCD's L2.
 #include "common.h"
 
 namespace remoe {
@@ -32,6 +35,7 @@ namespace remoe {
 namespace {
 
 constexpr int GM_BK = 64;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;   // four bf16 of one output row
 
 // LDS tile layout: rows of 8 chunks (16 bytes each).  Chunk c of row r lives in row slot
 // r ^ ((r >> 3) & 1) at chunk position c ^ (r & 7).  A fragment read has lane i on row base+i with
@@ -56,6 +60,15 @@ __device__ __forceinline__ void copy16_to_lds(const char *base, uint32_t off, co
     (void)off;
     (void)lds_base;
 #endif
+}
+
+// Entry idx of a list that no kernel writes while this one runs (the tile list of the permute step),
+// fetched through the constant address space: a scalar load, which neither occupies the vector
+// memory queue nor has to wait for the stores queued in it.
+__device__ __forceinline__ int list_entry(const int32_t *list, int idx)
+{
+    typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
+    return *(const_i32_ptr)(uintptr_t)(list + idx);
 }
 
 struct KArgs {
@@ -156,21 +169,23 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     const char *a_base, *b_base0, *b_base1;
     int par = 0;
 
+    // (the tile list holds rows already limited to the tile height, so nothing here consumes a loaded
+    // value: the loads are waited for where the descriptor is first used, a tile later)
 #define GM_TILE_INFO(qq, E, R0, RS, NT)                                                             \
     {                                                                                               \
-        const int logical_ = (qq);                                                                  \
+        const int logical_ = __builtin_amdgcn_readfirstlane(qq);                                    \
         const int mt_ = logical_ / ntn;                                                             \
         NT = logical_ - mt_ * ntn;                                                                  \
         if (p.tile_expert) {                                                                        \
-            E = p.tile_expert[mt_];                                                                 \
-            R0 = p.tile_row0[mt_];                                                                  \
-            RS = p.tile_rows[mt_];                                                                  \
+            E = list_entry(p.tile_expert, mt_);                                                     \
+            R0 = list_entry(p.tile_row0, mt_);                                                      \
+            RS = list_entry(p.tile_rows, mt_);                                                      \
         } else {                                                                                    \
             E = 0;                                                                                  \
             R0 = mt_ * BM;                                                                          \
             RS = p.dense_rows - R0;                                                                 \
+            if (RS > BM) RS = BM;                                                                   \
         }                                                                                           \
-        if (RS > BM) RS = BM;                                                                       \
     }
     // rows of A this thread copies (through slot -> token when gathered) for the tile at first slot R0
     // with RS valid rows; fetched a tile ahead, used by GM_TILE_OFFSETS
@@ -237,7 +252,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 #define GM_MFMA(fa, fb)                                                                             \
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
         _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                            \
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[mi][ni], 0, 0, 0);
     // copy instruction c of a slice (0 .. A_CH-1: A rows, then B rows)
 #define GM_COPY_ONE(la, lb, k0, c)                                                                  \
     if ((c) < A_CH)                                                                                 \
@@ -251,7 +266,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 #define GM_MFMA_COPIES(fa, fb, la, lb, k0, on)                                                      \
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
         _Pragma("unroll") for (int ni = 0; ni < TN; ++ni) {                                          \
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0); \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[mi][ni], 0, 0, 0); \
             __builtin_amdgcn_sched_barrier(0);                                                      \
             if (mi * TN + ni < COPIES && (on)) { GM_COPY_ONE(la, lb, k0, mi * TN + ni) }            \
             __builtin_amdgcn_sched_barrier(0);                                                      \
@@ -291,69 +306,73 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     else __builtin_amdgcn_s_waitcnt(0x0F70);                /* vmcnt(0) */                          \
     GM_LDS_BARRIER();
 
-    // Epilogue of one 32-row band per wavefront row (mi).  A lane holds column li of 16 rows per
-    // accumulator, which would make 2-byte stores.  Instead each band of the workgroup tile (both wm
-    // halves, all BN_OUT columns) is staged in LDS as bf16 and written out as 16-byte chunks, so
-    // every output row leaves as one contiguous run of full cache lines.  Neighbouring lanes first
-    // swap one value (lanes 2j and 2j+1 own adjacent columns) so that each lane packs two adjacent
-    // columns of one row into a dword.  A 64-byte segment s of band row r is stored at segment
-    // s ^ f(r), f = (r&1)|((r>>2)&1)<<1: the four rows one write instruction touches (r, r+1, r+4,
-    // r+5) then fall on different banks.  Bands alternate between the second A stage and the second
-    // B stage (idle after the last slice), so one barrier per band suffices and the first stage is
-    // free to receive the next tile's first slice meanwhile.
+    // Epilogue of one 32-row band per wavefront row (mi).  The MFMAs take the B rows as their first
+    // operand, so an accumulator holds the transposed 32 x 32 tile: a lane owns ONE row of A (li) and,
+    // per group of four registers g, the four adjacent output columns 8 g + 4 lh + (0..3).  Four
+    // registers therefore pack into 8 contiguous bytes of one output row, and in mode 1 the row's
+    // gate weight is one factor per lane.  Each band of the workgroup tile (both wm halves, all
+    // BN_OUT columns) is staged in LDS as bf16 and written out as 16-byte chunks, so every output row
+    // leaves as one contiguous run of full cache lines.  The 16-byte chunk c of band row R is stored
+    // at chunk position c ^ (R & 7): the eight rows li..li+7 that write the same logical chunk then
+    // fall on different banks.  Bands alternate between the second A stage and the second B stage
+    // (idle after the last slice), so one barrier per band suffices and the first stage is free to
+    // receive the next tile's first slice meanwhile.
     constexpr int ROWB = BN_OUT * 2;        // bytes per staged row
     constexpr int CPR = BN_OUT / 8;         // 16-byte chunks per staged row
     static_assert(BM <= THREADS, "one thread per tile row fetches the row's gate weight");
-    // accumulators of band mi -> staging array st (u32x4_t[], indexed in dwords)
+    static_assert(CPR % 8 == 0, "the chunk swizzle permutes groups of eight chunks");
+    // accumulators of band mi -> staging array st (u32x4_t[], indexed in bytes)
 #define GM_EPI_STAGE(mi, st, e_par)                                                                 \
     {                                                                                               \
-        uint32_t *reg = reinterpret_cast<uint32_t *>(st);                                           \
-        _Pragma("unroll") for (int rp = 0; rp < 8; ++rp) {                                           \
-            const int r0 = 2 * rp;                                                                  \
-            const int rr0 = (r0 >> 2) * 8 + lh * 4 + (r0 & 3);   /* band row of acc[..][r0]; r0 + 1 is the next row */ \
-            const int row = odd ? rr0 + 1 : rr0;                                                    \
-            const int f = (row & 1) | (((row >> 2) & 1) << 1);                                      \
-            float sc0 = 1.0f, sc1 = 1.0f;                                                           \
-            if (MODE == 1) {                                                                        \
-                sc0 = lds_scale[e_par][(wm * TM + (mi)) * 32 + rr0];                                \
-                sc1 = lds_scale[e_par][(wm * TM + (mi)) * 32 + rr0 + 1];                            \
-            }                                                                                       \
-            _Pragma("unroll") for (int ni = 0; ni < ((MODE == 0) ? 1 : TN); ++ni) {                  \
-                float va, vb;                                                                       \
-                if (MODE == 0) {                                                                    \
-                    const float g0 = acc[mi][0][r0], u0 = acc[mi][1][r0];                           \
-                    const float g1 = acc[mi][0][r0 + 1], u1 = acc[mi][1][r0 + 1];                   \
-                    va = g0 * u0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0));   /* silu(g) * u; the 1-ulp reciprocal is far inside bf16 rounding */ \
-                    vb = g1 * u1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1));                       \
-                } else {                                                                            \
-                    va = acc[mi][ni][r0] * sc0;                                                     \
-                    vb = acc[mi][ni][r0 + 1] * sc1;                                                 \
+        char *reg = reinterpret_cast<char *>(st) + (wm * 32 + li) * ROWB + lh * 8;                  \
+        float sc = 1.0f;                                                                            \
+        if (MODE == 1) sc = lds_scale[e_par][(wm * TM + (mi)) * 32 + li];                           \
+        _Pragma("unroll") for (int ni = 0; ni < ((MODE == 0) ? 1 : TN); ++ni) {                      \
+            const int seg = (MODE == 0) ? wn : wn * TN + ni;                                        \
+            _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                          \
+                float v[4];                                                                         \
+                _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                      \
+                    if (MODE == 0) {                                                                \
+                        const float gt = acc[mi][0][4 * g + e], up = acc[mi][1][4 * g + e];         \
+                        v[e] = gt * up * __builtin_amdgcn_rcpf(1.0f + __expf(-gt));   /* silu(g) * u; the 1-ulp reciprocal is far inside bf16 rounding */ \
+                    } else {                                                                        \
+                        v[e] = acc[mi][ni][4 * g + e] * sc;                                         \
+                    }                                                                               \
                 }                                                                                   \
-                const float recv = swap_with_neighbour(odd ? va : vb);                              \
-                const uint32_t packed = odd ? pack_bf16x2(recv, vb) : pack_bf16x2(va, recv);        \
-                const int seg = (MODE == 0) ? wn : wn * TN + ni;                                    \
-                reg[((wm * 32 + row) * ROWB + ((seg ^ f) << 6) + ((li & ~1) << 1)) >> 2] = packed;  \
+                u32x2_t pk;                                                                         \
+                pk.x = pack_bf16x2(v[0], v[1]);                                                     \
+                pk.y = pack_bf16x2(v[2], v[3]);                                                     \
+                *reinterpret_cast<u32x2_t *>(reg + (((seg * 4 + g) ^ (li & 7)) << 4)) = pk;         \
             }                                                                                       \
         }                                                                                           \
     }
     // staging array st -> global memory, 16 bytes per lane (non-temporal: the output is not read again by
-    // this kernel and should not push operand lines out of the L2)
-#define GM_EPI_STORE(mi, st, e_row0, e_rows, e_nt)                                                  \
-    _Pragma("unroll") for (int j = 0; j < 64 * CPR / THREADS; ++j) {                                 \
-        const int q2 = tid + THREADS * j;                                                           \
-        const int R = q2 / CPR, ch = q2 % CPR;     /* band row over both wm halves, chunk in the row */ \
-        const int row = R & 31;                                                                     \
-        const int f = (row & 1) | (((row >> 2) & 1) << 1);                                          \
-        const u32x4_t v = st[(R * ROWB + ((((ch >> 2) ^ f) << 6) + ((ch & 3) << 4))) >> 4];         \
-        const int m = ((R >> 5) * TM + (mi)) * 32 + row;                                            \
-        const int col = (e_nt) * BN_OUT + ch * 8;                                                   \
-        if (m < (e_rows) && col < p.n_out)                                                          \
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(p.c + (p.c_row_offset + (e_row0) + m) * p.ldc + col)); \
+    // this kernel and should not push operand lines out of the L2).  e_base is the wave-uniform address
+    // of the tile's first output element; offsets inside a tile fit 32 bits (checked by the launcher).
+#define GM_EPI_STORE(mi, st, e_base, e_rows, e_cols)                                                \
+    {                                                                                               \
+        constexpr int NJ = 64 * CPR / THREADS;                                                      \
+        const int R0 = tid / CPR, ch = tid % CPR;   /* band row over both wm halves, chunk in the row */ \
+        u32x4_t v[NJ];                                                                              \
+        _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                             \
+            const int R = R0 + j * (THREADS / CPR);                                                 \
+            v[j] = *reinterpret_cast<const u32x4_t *>(reinterpret_cast<const char *>(st) + R * ROWB + ((ch ^ (R & 7)) << 4)); \
+        }                                                                                           \
+        static_assert(NJ == 2 || NJ == 4, "the pin below is written for two or four chunks per thread"); \
+        /* all reads are issued before the first masked store (they would otherwise sink into its branch) */ \
+        if (NJ == 4) asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[NJ - 2]), "+v"(v[NJ - 1]));   \
+        else asm volatile("" : "+v"(v[0]), "+v"(v[1]));                                             \
+        _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                             \
+            const int R = R0 + j * (THREADS / CPR);                                                 \
+            const int m = ((R >> 5) * TM + (mi)) * 32 + (R & 31);                                   \
+            if (m < (e_rows) && ch * 8 < (e_cols))                                                  \
+                __builtin_nontemporal_store(v[j], reinterpret_cast<u32x4_t *>((e_base) + ((uint32_t)m * ldc_bytes + (uint32_t)ch * 16u))); \
+        }                                                                                           \
     }
-#define GM_EPI_BAND(mi, st, e_row0, e_rows, e_nt, e_par)                                            \
+#define GM_EPI_BAND(mi, st, e_base, e_rows, e_cols, e_par)                                          \
     GM_EPI_STAGE(mi, st, e_par)                                                                     \
     GM_LDS_BARRIER();                                                                               \
-    GM_EPI_STORE(mi, st, e_row0, e_rows, e_nt)
+    GM_EPI_STORE(mi, st, e_base, e_rows, e_cols)
 
     GM_TILE_INFO(q0, expert, row0, rows, nt)
     GM_TILE_ROWS(row0, rows, a_row)
@@ -366,33 +385,17 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     int nx_expert = 0, nx_row0 = 0, nx_rows = 1, nx_nt = 0;
     if (has_next) GM_TILE_INFO(q_nx, nx_expert, nx_row0, nx_rows, nx_nt)
 
+    uint32_t claim_raw = 0;      // ticket of the claim in flight (lane 0 only; read only when one was made)
     for (;;) {
         // Fetched under the main loop: the next tile's row indices and gate weights (its descriptor
-        // arrived a tile ago) and the descriptor of the tile after it.
+        // arrived a tile ago) and the descriptor of the tile after it.  The descriptor goes out now
+        // (scalar loads); the vector loads and the claim go out behind the first wait below, so that
+        // the wait for slice 0 is not also a wait for their round trip.
         int a_row_nx[A_CH];
         float scale_nx = 1.0f;
         const bool has_nn = q_nn >= 0;
         int nn_expert = 0, nn_row0 = 0, nn_rows = 1, nn_nt = 0;
-        // the claim for the tile three ahead goes out now (this XCD's own counter) and is looked at
-        // when the main loop is over: nobody waits for the atomic's round trip
-        uint32_t claim_raw = 0;
-        if (threadIdx.x == 0 && has_nn)
-            claim_raw = __hip_atomic_fetch_add(&p.tile_ctr[home], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        {
-            int tid_early = threadIdx.x;
-            asm volatile("" : "+v"(tid_early));   // (index arithmetic redone here rather than kept in registers)
-            const int tid = tid_early;
-            const int lane = tid & 63, wave = tid >> 6;
-            const int land_rs = lane >> 3;
-            if (has_next) {
-                GM_TILE_ROWS(nx_row0, nx_rows, a_row_nx)
-                GM_LOAD_SCALE(nx_row0, nx_rows, scale_nx)
-            } else {
-#pragma unroll
-                for (int i = 0; i < A_CH; ++i) a_row_nx[i] = 0;
-            }
-            if (has_nn) GM_TILE_INFO(q_nn, nn_expert, nn_row0, nn_rows, nn_nt)
-        }
+        if (has_nn) GM_TILE_INFO(q_nn, nn_expert, nn_row0, nn_rows, nn_nt)
 
         floatx16_t acc[TM][TN];
 #pragma unroll
@@ -407,6 +410,30 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         // been read (inside GM_COMPUTE), so a copy has about one and a half slices of MFMA time to land.
         if (nk > 1) { GM_COPY_SLICE(lds_a1, lds_b1, GM_BK) }
         GM_WAIT_SLICE(nk > 1)
+        // the claim for the tile three ahead (this XCD's own counter) is looked at when the main loop
+        // is over: nobody waits for the atomic's round trip
+        // (the counter's address is handed over in a vector register: for an atomic with a wave-uniform
+        // address the compiler emits a wave-wide reduction that waits for the result on the spot)
+        if (threadIdx.x == 0 && has_nn) {
+            typedef uint32_t __attribute__((address_space(1))) *global_u32_ptr;
+            uintptr_t ctr_addr = reinterpret_cast<uintptr_t>(p.tile_ctr + home);
+            asm volatile("" : "+v"(ctr_addr));
+            claim_raw = __hip_atomic_fetch_add((global_u32_ptr)ctr_addr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        {
+            int tid_early = threadIdx.x;
+            asm volatile("" : "+v"(tid_early));   // (index arithmetic redone here rather than kept in registers)
+            const int tid = tid_early;
+            const int lane = tid & 63, wave = tid >> 6;
+            const int land_rs = lane >> 3;
+            if (has_next) {
+                GM_TILE_ROWS(nx_row0, nx_rows, a_row_nx)
+                GM_LOAD_SCALE(nx_row0, nx_rows, scale_nx)
+            } else {
+#pragma unroll
+                for (int i = 0; i < A_CH; ++i) a_row_nx[i] = 0;
+            }
+        }
 #define GM_LAST_REFILL0(fa, fb) GM_MFMA_COPIES(fa, fb, lds_a0, lds_b0, (kt + 2) * GM_BK, refill0)
 #define GM_LAST_REFILL1(fa, fb) GM_MFMA_COPIES(fa, fb, lds_a1, lds_b1, (kt + 3) * GM_BK, refill1)
         for (int kt = 0; kt < nk; kt += 2) {
@@ -420,6 +447,10 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             }
         }
 
+        // Every copy has landed; the loads and the claim issued under the loop have too.  Saying so on
+        // every path keeps the compiler from waiting for them again at the top of the next tile, where
+        // the wait would be for this tile's stores.
+        __builtin_amdgcn_s_waitcnt(0x0F70);   /* vmcnt(0) */
         // the claim made at the top of this tile: inside this XCD's range, or else one from another's
         if (threadIdx.x == 0) {
             int q3 = -1;
@@ -443,8 +474,10 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         const int li = lane & 31, lh = lane >> 5;
         const int land_rs = lane >> 3, land_cp = lane & 7;
         const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-        const bool odd = li & 1;
-        const int e_row0 = row0, e_rows = rows, e_nt = nt, e_par = par;
+        const int e_rows = rows, e_par = par;
+        const int e_cols = p.n_out - nt * BN_OUT;      // valid columns of this n-tile (the store masks the rest)
+        char *const e_base = reinterpret_cast<char *>(p.c + (p.c_row_offset + row0) * p.ldc + nt * BN_OUT);
+        const uint32_t ldc_bytes = (uint32_t)p.ldc * 2u;
         if (has_next) {
             expert = nx_expert; row0 = nx_row0; rows = nx_rows; nt = nx_nt;
             par ^= 1;
@@ -459,10 +492,10 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             GM_COPY_SLICE(lds_a0, lds_b0, 0)
         }
         GM_LDS_BARRIER();
-        GM_EPI_STORE(0, lds_a1, e_row0, e_rows, e_nt)
-        if (TM > 1) { GM_EPI_BAND(1, lds_b1, e_row0, e_rows, e_nt, e_par) }
-        if (TM > 2) { GM_EPI_BAND(2, lds_a1, e_row0, e_rows, e_nt, e_par) }
-        if (TM > 3) { GM_EPI_BAND(3, lds_b1, e_row0, e_rows, e_nt, e_par) }
+        GM_EPI_STORE(0, lds_a1, e_base, e_rows, e_cols)
+        if (TM > 1) { GM_EPI_BAND(1, lds_b1, e_base, e_rows, e_cols, e_par) }
+        if (TM > 2) { GM_EPI_BAND(2, lds_a1, e_base, e_rows, e_cols, e_par) }
+        if (TM > 3) { GM_EPI_BAND(3, lds_b1, e_base, e_rows, e_cols, e_par) }
         static_assert(TM <= 4, "the epilogue is written out for up to four bands");
         if (!has_next) break;
         has_next = has_nn;
@@ -489,6 +522,9 @@ remoe_status launch_grouped_gemm_bf16(int mode, const GroupedGemmArgs &g, hipStr
         return fail(REMOE_E_UNSUPPORTED, "gathered GEMM operand spans 4 GiB or more (%lld rows)", (long long)g.a_rows);
     if ((int64_t)g.n_out * g.k_dim * 2 >= (int64_t)1 << 32)
         return fail(REMOE_E_UNSUPPORTED, "one expert matrix spans 4 GiB or more");
+    if (g.ldc * 2 * CFG_BM >= (int64_t)1 << 32 || g.n_out % 8 != 0)
+        return fail(REMOE_E_UNSUPPORTED, "bf16 GEMM output needs n %% 8 == 0 and a row pitch below 8 Mi elements (n=%d ldc=%lld)",
+                    g.n_out, (long long)g.ldc);
     if (g.max_tiles <= 0) return REMOE_OK;
     KArgs p;
     p.a = static_cast<const bf16_t *>(g.a);
