@@ -168,6 +168,9 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     int a_row[A_CH];
     const char *a_base, *b_base0, *b_base1;
     int par = 0;
+    floatx16_t zero16;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) zero16[r] = 0.f;
 
     // (the tile list holds rows already limited to the tile height, so nothing here consumes a loaded
     // value: the loads are waited for where the descriptor is first used, a tile later)
@@ -253,6 +256,11 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
         _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                            \
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[mi][ni], 0, 0, 0);
+    // the first k-step of a tile starts the accumulators from the constant zero (no registers to clear)
+#define GM_MFMA_FIRST(fa, fb)                                                                       \
+    _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
+        _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                            \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], zero16, 0, 0, 0);
     // copy instruction c of a slice (0 .. A_CH-1: A rows, then B rows)
 #define GM_COPY_ONE(la, lb, k0, c)                                                                  \
     if ((c) < A_CH)                                                                                 \
@@ -275,13 +283,13 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // behind the MFMAs of step 1, as soon as every fragment of the stage has been requested: it waits
     // for them (the matrix cores are still busy with step 1), passes a barrier and may then refill the
     // stage, two k-steps before the slice ends, so a copy has a slice and a half of MFMA time to land.
-#define GM_COMPUTE(la, lb, MID, LAST)                                                                   \
+#define GM_COMPUTE(la, lb, STEP0, MID, LAST)                                                            \
     {                                                                                               \
         bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];                                                \
         GM_READ_FRAGS(la, lb, 0, fa0, fb0)                                                           \
         GM_READ_FRAGS(la, lb, 1, fa1, fb1)                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
-        GM_MFMA(fa0, fb0)                                                                           \
+        STEP0(fa0, fb0)                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                          \
         GM_READ_FRAGS(la, lb, 2, fa0, fb0)                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
@@ -347,7 +355,9 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         }                                                                                           \
     }
     // staging array st -> global memory, 16 bytes per lane (non-temporal: the output is not read again by
-    // this kernel and should not push operand lines out of the L2).  e_base is the wave-uniform address
+    // this kernel and should not push operand lines out of the L2; the last band of the down projection
+    // is stored the ordinary way, which is acknowledged sooner: the next tile's first wait on the vector
+    // memory counter also waits for these stores).  e_base is the wave-uniform address
     // of the tile's first output element; offsets inside a tile fit 32 bits (checked by the launcher).
 #define GM_EPI_STORE(mi, st, e_base, e_rows, e_cols)                                                \
     {                                                                                               \
@@ -365,8 +375,11 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                             \
             const int R = R0 + j * (THREADS / CPR);                                                 \
             const int m = ((R >> 5) * TM + (mi)) * 32 + (R & 31);                                   \
-            if (m < (e_rows) && ch * 8 < (e_cols))                                                  \
-                __builtin_nontemporal_store(v[j], reinterpret_cast<u32x4_t *>((e_base) + ((uint32_t)m * ldc_bytes + (uint32_t)ch * 16u))); \
+            if (m < (e_rows) && ch * 8 < (e_cols)) {                                                \
+                u32x4_t *dst_ = reinterpret_cast<u32x4_t *>((e_base) + ((uint32_t)m * ldc_bytes + (uint32_t)ch * 16u)); \
+                if (MODE == 1 && (mi) == TM - 1) *dst_ = v[j];                                      \
+                else __builtin_nontemporal_store(v[j], dst_);                                       \
+            }                                                                                       \
         }                                                                                           \
     }
 #define GM_EPI_BAND(mi, st, e_base, e_rows, e_cols, e_par)                                          \
@@ -397,13 +410,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         int nn_expert = 0, nn_row0 = 0, nn_rows = 1, nn_nt = 0;
         if (has_nn) GM_TILE_INFO(q_nn, nn_expert, nn_row0, nn_rows, nn_nt)
 
-        floatx16_t acc[TM][TN];
-#pragma unroll
-        for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+        floatx16_t acc[TM][TN];   // first written by the MFMAs of slice 0, k-step 0
 
         // Main loop.  Slice 0 is already on its way into stage 0; even slices use stage 0, odd ones
         // stage 1.  A stage is refilled with the slice after next as soon as all its fragments have
@@ -434,15 +441,17 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
                 for (int i = 0; i < A_CH; ++i) a_row_nx[i] = 0;
             }
         }
+#define GM_STEP0_EVEN(fa, fb)                                                                       \
+    if (kt == 0) { GM_MFMA_FIRST(fa, fb) } else { GM_MFMA(fa, fb) }
 #define GM_LAST_REFILL0(fa, fb) GM_MFMA_COPIES(fa, fb, lds_a0, lds_b0, (kt + 2) * GM_BK, refill0)
 #define GM_LAST_REFILL1(fa, fb) GM_MFMA_COPIES(fa, fb, lds_a1, lds_b1, (kt + 3) * GM_BK, refill1)
         for (int kt = 0; kt < nk; kt += 2) {
             const bool refill0 = kt + 2 < nk;
-            GM_COMPUTE(lds_a0, lds_b0, GM_LDS_BARRIER();, GM_LAST_REFILL0)
+            GM_COMPUTE(lds_a0, lds_b0, GM_STEP0_EVEN, GM_LDS_BARRIER();, GM_LAST_REFILL0)
             if (kt + 1 < nk) {
                 const bool refill1 = kt + 3 < nk;
                 GM_WAIT_SLICE(refill0)
-                GM_COMPUTE(lds_a1, lds_b1, GM_LDS_BARRIER();, GM_LAST_REFILL1)
+                GM_COMPUTE(lds_a1, lds_b1, GM_MFMA, GM_LDS_BARRIER();, GM_LAST_REFILL1)
                 if (refill0) { GM_WAIT_SLICE(refill1) }
             }
         }
