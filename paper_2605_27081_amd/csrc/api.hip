@@ -296,7 +296,7 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
         st = launch_permute(out_idx, out_w, T, K, N, gemm_tile_m(), ws.max_tiles, ws.pb, stream);
     }
     if (st != REMOE_OK) return st;
-    // 3. routed experts: gate/up + SwiGLU, then down projection scaled by the gate weight
+    // 3. routed experts: gate/up + SwiGLU, then the down projection (the fp32 kernel also applies the gate weight)
     GroupedGemmArgs g{};
     g.a = x; g.lda = H; g.a_rows = T; g.row_gather = ws.pb.slot_token;
     g.b0 = w_gate; g.b1 = w_up; g.k_dim = H; g.n_out = I;
@@ -311,7 +311,8 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
     if (st != REMOE_OK) return st;
     g.a = ws.hbuf; g.lda = I; g.a_rows = T * K; g.row_gather = nullptr;
     g.b0 = w_down; g.b1 = nullptr; g.k_dim = I; g.n_out = H;
-    g.row_scale = ws.pb.slot_w; g.c = ws.rows; g.ldc = H;
+    g.row_scale = f32 ? ws.pb.slot_w : nullptr;   // bf16: the combine step applies the gate weights
+    g.c = ws.rows; g.ldc = H;
     g.tile_ctr = ws.pb.gemm_ctr + 8;
     {
         ProfScope prof(REMOE_PROF_DOWN, stream);
@@ -341,7 +342,7 @@ remoe_status moe_forward(const remoe_layer_desc *desc, const void *x, int64_t n_
     }
     // 5. combine the K (+1) rows of every token
     ProfScope prof(REMOE_PROF_COMBINE, stream);
-    return launch_combine(desc->dtype, ws.rows, ws.pb.pair_slot, T, K, H, T * K, Is > 0, x,
+    return launch_combine(desc->dtype, ws.rows, ws.pb.pair_slot, f32 ? nullptr : out_w, T, K, H, T * K, Is > 0, x,
                           desc->shared_gate ? ws_scale : nullptr, y, stream);
 }
 

@@ -1,8 +1,10 @@
 // Weighted combine: y[t] = sum_{j<K} out_j(t) + s_t * shared(t), summed in fp32.
 //
-// The down-projection kernels have already multiplied each (token, expert) row by its gate weight
-// P_t[e] (Sec. 3.1), so the routed part is a plain sum of the token's K rows, found through the
-// pair -> slot map of the permute step and taken in routing order (descending logit).  The shared
+// The routed part is the sum of the token's K rows, each weighted by its gate weight P_t[e]
+// (Sec. 3.1), found through the pair -> slot map of the permute step and taken in routing order
+// (descending logit).  The weights come from pair_w in (token, j) order; where pair_w is NULL the
+// down-projection kernel has already applied them (the fp32 path) and the rows are summed as they
+// are.  The shared
 // expert's row (always active, outside P_t) is added last, scaled by s_t = sigmoid(ws_scale . x[t])
 // when the layer gates its shared expert.  One workgroup per token; the sum order is fixed, so the
 // result is deterministic.
@@ -52,8 +54,8 @@ template <> struct Vec<bf16_t> {
 
 template <typename ET>
 __global__ __launch_bounds__(256) void combine_kernel(const ET *__restrict__ rows,
-                                                      const int32_t *__restrict__ pair_slot, int K,
-                                                      int H, int64_t shared_row0, int has_shared,
+                                                      const int32_t *__restrict__ pair_slot,
+                                                      const float *__restrict__ pair_w, int K, int H, int64_t shared_row0, int has_shared,
                                                       const ET *__restrict__ x,
                                                       const float *__restrict__ ws_scale,
                                                       ET *__restrict__ y)
@@ -81,6 +83,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const ET *__restrict__ row
     int slot[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) slot[j] = (j < K) ? pair_slot[t * K + j] : 0;
+    float wj[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) wj[j] = (j < K && pair_w) ? pair_w[t * K + j] : 1.0f;
     for (int c = tid; c < H / V; c += 256) {
         float acc[V];
 #pragma unroll
@@ -91,7 +96,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const ET *__restrict__ row
                 float v[V];
                 Vec<ET>::load(rows + (int64_t)slot[j] * H + c * V, v);
 #pragma unroll
-                for (int i = 0; i < V; ++i) acc[i] += v[i];
+                for (int i = 0; i < V; ++i) acc[i] = fmaf(wj[j], v[i], acc[i]);
             }
         }
         if (has_shared) {
@@ -106,7 +111,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const ET *__restrict__ row
 
 }  // namespace
 
-remoe_status launch_combine(int dtype, const void *rows, const int32_t *pair_slot, int64_t T, int K,
+remoe_status launch_combine(int dtype, const void *rows, const int32_t *pair_slot, const float *pair_w, int64_t T, int K,
                             int H, int64_t shared_row0, int has_shared, const void *x,
                             const float *ws_scale, void *y, hipStream_t stream)
 {
@@ -114,11 +119,11 @@ remoe_status launch_combine(int dtype, const void *rows, const int32_t *pair_slo
     const dim3 grid((unsigned)T), block(256);
     if (dtype == REMOE_F32)
         hipLaunchKernelGGL(combine_kernel<float>, grid, block, 0, stream, static_cast<const float *>(rows),
-                           pair_slot, K, H, shared_row0, has_shared, static_cast<const float *>(x),
+                           pair_slot, pair_w, K, H, shared_row0, has_shared, static_cast<const float *>(x),
                            ws_scale, static_cast<float *>(y));
     else
         hipLaunchKernelGGL(combine_kernel<bf16_t>, grid, block, 0, stream,
-                           static_cast<const bf16_t *>(rows), pair_slot, K, H, shared_row0, has_shared,
+                           static_cast<const bf16_t *>(rows), pair_slot, pair_w, K, H, shared_row0, has_shared,
                            static_cast<const bf16_t *>(x), ws_scale, static_cast<bf16_t *>(y));
     return check_hip(hipGetLastError(), "combine launch");
 }

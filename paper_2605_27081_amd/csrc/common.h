@@ -112,7 +112,7 @@ remoe_status launch_grouped_gemm_bf16(int mode, const GroupedGemmArgs &g, hipStr
 remoe_status launch_grouped_gemm_f32(int mode, const GroupedGemmArgs &g, hipStream_t stream);
 
 // y[t] = sum_j rows[pair_slot[t*K+j]] + s_t * rows[shared_row0 + t]
-remoe_status launch_combine(int dtype, const void *rows, const int32_t *pair_slot, int64_t T, int K,
+remoe_status launch_combine(int dtype, const void *rows, const int32_t *pair_slot, const float *pair_w, int64_t T, int K,
                             int H, int64_t shared_row0, int has_shared, const void *x,
                             const float *ws_scale, void *y, hipStream_t stream);
 

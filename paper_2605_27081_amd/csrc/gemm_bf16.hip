@@ -3,7 +3,8 @@
 // The selected experts "execute as in the base model" (Sec. 4.1, step 5); with SwiGLU experts that
 // is, per expert e and for the rows (token, j) routed to it,
 //   mode 0:  h   = silu(X_e W_gate[e]^T) * (X_e W_up[e]^T)          -> [slots, I]   bf16
-//   mode 1:  out = (h_e W_down[e]^T) * gate weight of the row       -> [slots, H]   bf16
+//   mode 1:  out = h_e W_down[e]^T                                  -> [slots, H]   bf16
+// (the gate weight P_t[e] of a row is applied by the combine step, which reads it anyway).
 // Both are C[m, n] = sum_k A[row(m), k] * B_e[n, k] with the reduction dimension contiguous in both
 // operands, which is exactly the per-lane operand layout of the 32x32x16 MFMA (8 consecutive k per
 // lane), so LDS fragments are single 16-byte reads.
@@ -81,7 +82,6 @@ struct KArgs {
     int n_out;
     const int32_t *tile_expert, *tile_row0, *tile_rows, *n_tiles;
     int dense_rows;
-    const float *row_scale;
     bf16_t *c;
     int64_t ldc;
     int64_t c_row_offset;
@@ -120,7 +120,6 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // the fragment reads of the other (no wait for the copy before those reads)
     __shared__ u32x4_t lds_a0[BM * 8], lds_a1[BM * 8];
     __shared__ u32x4_t lds_b0[BN * 8], lds_b1[BN * 8];
-    __shared__ float lds_scale[2][BM];         // mode 1: gate weight of each tile row (this tile / next tile)
     static_assert(BM == BN, "the epilogue stages its bands in the second A stage and the second B stage alike");
 
     // Persistent workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs, so workgroup b runs
@@ -167,7 +166,6 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     uint32_t a_off[A_CH], b_off[B_CH];
     int a_row[A_CH];
     const char *a_base, *b_base0, *b_base1;
-    int par = 0;
     floatx16_t zero16;
 #pragma unroll
     for (int r = 0; r < 16; ++r) zero16[r] = 0.f;
@@ -218,13 +216,6 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         if (brow_ >= p.n_out) brow_ = p.n_out - 1;   /* ragged last n-tile: loads stay in bounds, stores are masked */ \
         b_off[i] = (uint32_t)(((int64_t)brow_ * p.k_dim + c_ * 8) * 2);                             \
     }
-    // mode 1: the gate weight of tile row tid (threads below BM), fetched early and parked in LDS later
-    float scale_reg = 1.0f;
-#define GM_LOAD_SCALE(R0, RS, OUT)                                                                  \
-    if (MODE == 1) OUT = (p.row_scale && tid < (RS)) ? p.row_scale[(R0) + tid] : 1.0f;
-#define GM_FILL_SCALE(buf)                                                                          \
-    if (MODE == 1 && tid < BM) lds_scale[buf][tid] = scale_reg;
-
     // mode 0: row-slot groups below BN/2 rows hold gate rows, the others up rows (a group never straddles)
 #define GM_COPY_SLICE(la, lb, k0)                                                                   \
     {                                                                                               \
@@ -317,8 +308,8 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // Epilogue of one 32-row band per wavefront row (mi).  The MFMAs take the B rows as their first
     // operand, so an accumulator holds the transposed 32 x 32 tile: a lane owns ONE row of A (li) and,
     // per group of four registers g, the four adjacent output columns 8 g + 4 lh + (0..3).  Four
-    // registers therefore pack into 8 contiguous bytes of one output row, and in mode 1 the row's
-    // gate weight is one factor per lane.  Each band of the workgroup tile (both wm halves, all
+    // registers therefore pack into 8 contiguous bytes of one output row.  Each band of the workgroup
+    // tile (both wm halves, all
     // BN_OUT columns) is staged in LDS as bf16 and written out as 16-byte chunks, so every output row
     // leaves as one contiguous run of full cache lines.  The 16-byte chunk c of band row R is stored
     // at chunk position c ^ (R & 7): the eight rows li..li+7 that write the same logical chunk then
@@ -327,14 +318,11 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // receive the next tile's first slice meanwhile.
     constexpr int ROWB = BN_OUT * 2;        // bytes per staged row
     constexpr int CPR = BN_OUT / 8;         // 16-byte chunks per staged row
-    static_assert(BM <= THREADS, "one thread per tile row fetches the row's gate weight");
     static_assert(CPR % 8 == 0, "the chunk swizzle permutes groups of eight chunks");
     // accumulators of band mi -> staging array st (u32x4_t[], indexed in bytes)
-#define GM_EPI_STAGE(mi, st, e_par)                                                                 \
+#define GM_EPI_STAGE(mi, st)                                                                        \
     {                                                                                               \
         char *reg = reinterpret_cast<char *>(st) + (wm * 32 + li) * ROWB + lh * 8;                  \
-        float sc = 1.0f;                                                                            \
-        if (MODE == 1) sc = lds_scale[e_par][(wm * TM + (mi)) * 32 + li];                           \
         _Pragma("unroll") for (int ni = 0; ni < ((MODE == 0) ? 1 : TN); ++ni) {                      \
             const int seg = (MODE == 0) ? wn : wn * TN + ni;                                        \
             _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                          \
@@ -344,7 +332,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
                         const float gt = acc[mi][0][4 * g + e], up = acc[mi][1][4 * g + e];         \
                         v[e] = gt * up * __builtin_amdgcn_rcpf(1.0f + __expf(-gt));   /* silu(g) * u; the 1-ulp reciprocal is far inside bf16 rounding */ \
                     } else {                                                                        \
-                        v[e] = acc[mi][ni][4 * g + e] * sc;                                         \
+                        v[e] = acc[mi][ni][4 * g + e];                                              \
                     }                                                                               \
                 }                                                                                   \
                 u32x2_t pk;                                                                         \
@@ -382,16 +370,14 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             }                                                                                       \
         }                                                                                           \
     }
-#define GM_EPI_BAND(mi, st, e_base, e_rows, e_cols, e_par)                                          \
-    GM_EPI_STAGE(mi, st, e_par)                                                                     \
+#define GM_EPI_BAND(mi, st, e_base, e_rows, e_cols)                                                 \
+    GM_EPI_STAGE(mi, st)                                                                            \
     GM_LDS_BARRIER();                                                                               \
     GM_EPI_STORE(mi, st, e_base, e_rows, e_cols)
 
     GM_TILE_INFO(q0, expert, row0, rows, nt)
     GM_TILE_ROWS(row0, rows, a_row)
-    GM_LOAD_SCALE(row0, rows, scale_reg)
     GM_TILE_OFFSETS()
-    GM_FILL_SCALE(0)
     GM_COPY_SLICE(lds_a0, lds_b0, 0)
     // descriptor of this workgroup's next tile
     bool has_next = q_nx >= 0;
@@ -400,12 +386,11 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 
     uint32_t claim_raw = 0;      // ticket of the claim in flight (lane 0 only; read only when one was made)
     for (;;) {
-        // Fetched under the main loop: the next tile's row indices and gate weights (its descriptor
+        // Fetched under the main loop: the next tile's row indices (its descriptor
         // arrived a tile ago) and the descriptor of the tile after it.  The descriptor goes out now
         // (scalar loads); the vector loads and the claim go out behind the first wait below, so that
         // the wait for slice 0 is not also a wait for their round trip.
         int a_row_nx[A_CH];
-        float scale_nx = 1.0f;
         const bool has_nn = q_nn >= 0;
         int nn_expert = 0, nn_row0 = 0, nn_rows = 1, nn_nt = 0;
         if (has_nn) GM_TILE_INFO(q_nn, nn_expert, nn_row0, nn_rows, nn_nt)
@@ -435,7 +420,6 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             const int land_rs = lane >> 3;
             if (has_next) {
                 GM_TILE_ROWS(nx_row0, nx_rows, a_row_nx)
-                GM_LOAD_SCALE(nx_row0, nx_rows, scale_nx)
             } else {
 #pragma unroll
                 for (int i = 0; i < A_CH; ++i) a_row_nx[i] = 0;
@@ -483,28 +467,25 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         const int li = lane & 31, lh = lane >> 5;
         const int land_rs = lane >> 3, land_cp = lane & 7;
         const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-        const int e_rows = rows, e_par = par;
+        const int e_rows = rows;
         const int e_cols = p.n_out - nt * BN_OUT;      // valid columns of this n-tile (the store masks the rest)
         char *const e_base = reinterpret_cast<char *>(p.c + (p.c_row_offset + row0) * p.ldc + nt * BN_OUT);
         const uint32_t ldc_bytes = (uint32_t)p.ldc * 2u;
         if (has_next) {
             expert = nx_expert; row0 = nx_row0; rows = nx_rows; nt = nx_nt;
-            par ^= 1;
 #pragma unroll
             for (int i = 0; i < A_CH; ++i) a_row[i] = a_row_nx[i];
-            scale_reg = scale_nx;
         }
-        GM_EPI_STAGE(0, lds_a1, e_par)
+        GM_EPI_STAGE(0, lds_a1)
         if (has_next) {
             GM_TILE_OFFSETS()
-            GM_FILL_SCALE(par)
             GM_COPY_SLICE(lds_a0, lds_b0, 0)
         }
         GM_LDS_BARRIER();
         GM_EPI_STORE(0, lds_a1, e_base, e_rows, e_cols)
-        if (TM > 1) { GM_EPI_BAND(1, lds_b1, e_base, e_rows, e_cols, e_par) }
-        if (TM > 2) { GM_EPI_BAND(2, lds_a1, e_base, e_rows, e_cols, e_par) }
-        if (TM > 3) { GM_EPI_BAND(3, lds_b1, e_base, e_rows, e_cols, e_par) }
+        if (TM > 1) { GM_EPI_BAND(1, lds_b1, e_base, e_rows, e_cols) }
+        if (TM > 2) { GM_EPI_BAND(2, lds_a1, e_base, e_rows, e_cols) }
+        if (TM > 3) { GM_EPI_BAND(3, lds_b1, e_base, e_rows, e_cols) }
         static_assert(TM <= 4, "the epilogue is written out for up to four bands");
         if (!has_next) break;
         has_next = has_nn;
@@ -534,6 +515,7 @@ remoe_status launch_grouped_gemm_bf16(int mode, const GroupedGemmArgs &g, hipStr
     if (g.ldc * 2 * CFG_BM >= (int64_t)1 << 32 || g.n_out % 8 != 0)
         return fail(REMOE_E_UNSUPPORTED, "bf16 GEMM output needs n %% 8 == 0 and a row pitch below 8 Mi elements (n=%d ldc=%lld)",
                     g.n_out, (long long)g.ldc);
+    if (g.row_scale) return fail(REMOE_E_INVALID_ARG, "the bf16 GEMM applies no row factors (the combine step does)");
     if (g.max_tiles <= 0) return REMOE_OK;
     KArgs p;
     p.a = static_cast<const bf16_t *>(g.a);
@@ -548,7 +530,6 @@ remoe_status launch_grouped_gemm_bf16(int mode, const GroupedGemmArgs &g, hipStr
     p.tile_rows = g.tile_rows;
     p.n_tiles = g.n_tiles;
     p.dense_rows = (int)g.dense_rows;
-    p.row_scale = g.row_scale;
     p.c = static_cast<bf16_t *>(g.c);
     p.ldc = g.ldc;
     p.c_row_offset = g.c_row_offset;
