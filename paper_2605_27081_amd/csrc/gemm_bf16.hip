@@ -313,9 +313,9 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // BN_OUT columns) is staged in LDS as bf16 and written out as 16-byte chunks, so every output row
     // leaves as one contiguous run of full cache lines.  The 16-byte chunk c of band row R is stored
     // at chunk position c ^ (R & 7): the eight rows li..li+7 that write the same logical chunk then
-    // fall on different banks.  Bands alternate between the second A stage and the second B stage
-    // (idle after the last slice), so one barrier per band suffices and the first stage is free to
-    // receive the next tile's first slice meanwhile.
+    // fall on different banks.  Bands 0 and 2 are staged in the second A stage,
+    // bands 1 and 3 in the second B stage (both idle after the last slice), two bands per barrier,
+    // and the first stage is free to receive the next tile's first slice meanwhile.
     constexpr int ROWB = BN_OUT * 2;        // bytes per staged row
     constexpr int CPR = BN_OUT / 8;         // 16-byte chunks per staged row
     static_assert(CPR % 8 == 0, "the chunk swizzle permutes groups of eight chunks");
@@ -476,17 +476,22 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 #pragma unroll
             for (int i = 0; i < A_CH; ++i) a_row[i] = a_row_nx[i];
         }
+        static_assert(TM == 4, "the epilogue is written out for four bands");
         GM_EPI_STAGE(0, lds_a1)
         if (has_next) {
             GM_TILE_OFFSETS()
             GM_COPY_SLICE(lds_a0, lds_b0, 0)
         }
+        GM_EPI_STAGE(1, lds_b1)
         GM_LDS_BARRIER();
         GM_EPI_STORE(0, lds_a1, e_base, e_rows, e_cols)
-        if (TM > 1) { GM_EPI_BAND(1, lds_b1, e_base, e_rows, e_cols) }
-        if (TM > 2) { GM_EPI_BAND(2, lds_a1, e_base, e_rows, e_cols) }
-        if (TM > 3) { GM_EPI_BAND(3, lds_b1, e_base, e_rows, e_cols) }
-        static_assert(TM <= 4, "the epilogue is written out for up to four bands");
+        GM_EPI_STORE(1, lds_b1, e_base, e_rows, e_cols)
+        GM_LDS_BARRIER();      // everyone has read bands 0 and 1
+        GM_EPI_STAGE(2, lds_a1)
+        GM_EPI_STAGE(3, lds_b1)
+        GM_LDS_BARRIER();
+        GM_EPI_STORE(2, lds_a1, e_base, e_rows, e_cols)
+        GM_EPI_STORE(3, lds_b1, e_base, e_rows, e_cols)
         if (!has_next) break;
         has_next = has_nn;
         nx_expert = nn_expert; nx_row0 = nn_row0; nx_rows = nn_rows; nx_nt = nn_nt;
