@@ -27,8 +27,8 @@
 // The tile list (expert, first slot, valid rows) comes from the permute step and lives in device
 // memory; the launch covers an upper bound of tiles and surplus workgroups return at once.
 // Workgroup ids are dealt round-robin to the 8 XCDs; every XCD hands out one contiguous range of
-// logical tiles (n-tile fastest) to its workgroups in arrival order, which keeps an expert's weights
-// and the current A rows hot in that XCD's L2.
+// logical tiles to its workgroups in arrival order, which keeps an expert's weights and the current
+// A rows hot in that XCD's L2.
 #include "common.h"
 
 namespace remoe {
@@ -36,6 +36,12 @@ namespace remoe {
 namespace {
 
 constexpr int GM_BK = 64;
+// Order of the logical tiles: MT_GROUP row tiles walk the column tiles together, row tile fastest, so
+// that workgroups that start one after the other share a weight tile and meet the same row tile
+// again MT_GROUP tiles later.  Measured on the Qwen3-shaped layer (65,536 tokens): 4 for gate/up and
+// 5 for the down projection (2.85 -> 2.82 ms and 1.82 -> 1.65 ms against column tile fastest; 7 is as
+// good as 5, the even sizes 6 and 8 are 2 % and 5 % slower).
+constexpr int MT_GROUP0 = 4, MT_GROUP1 = 5;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;   // four bf16 of one output row
 
 // LDS tile layout: rows of 8 chunks (16 bytes each).  Chunk c of row r lives in row slot
@@ -111,6 +117,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 {
     static_assert(MODE == 1 || TN == 2, "mode 0 pairs one gate tile with one up tile per wavefront");
     constexpr int THREADS = WM * WN * 64;
+    constexpr int MT_GROUP = (MODE == 0) ? MT_GROUP0 : MT_GROUP1;
     constexpr int BM = WM * TM * 32;           // rows of A per workgroup
     constexpr int BN = WN * TN * 32;           // rows of B per workgroup
     constexpr int BN_OUT = (MODE == 0) ? BN / 2 : BN;
@@ -124,7 +131,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 
     // Persistent workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs, so workgroup b runs
     // on XCD b % 8.  XCD x owns the contiguous range [x * chunk, (x + 1) * chunk) of logical tiles
-    // (n-tile fastest) and its workgroups claim the tiles of that range one after the other from a
+    // (in the grouped order described at MT_GROUP0) and its workgroups claim the tiles of that range one after the other from a
     // counter: at any time the workgroups of one XCD therefore work on neighbouring tiles, which share
     // A rows and expert weights through that XCD's L2.  Tile numbers are claimed three tiles ahead of
     // their use (the descriptor and the row indices of a tile are each fetched a tile ahead).
@@ -175,8 +182,16 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 #define GM_TILE_INFO(qq, E, R0, RS, NT)                                                             \
     {                                                                                               \
         const int logical_ = __builtin_amdgcn_readfirstlane(qq);                                    \
-        const int mt_ = logical_ / ntn;                                                             \
-        NT = logical_ - mt_ * ntn;                                                                  \
+        const int blk_ = logical_ / (MT_GROUP * ntn), r_ = logical_ - blk_ * (MT_GROUP * ntn);      \
+        int mt_ = blk_ * MT_GROUP;                                                                  \
+        if (mt_ + MT_GROUP <= n_mt) {  /* a full group of row tiles: row tile fastest inside it */   \
+            NT = r_ / MT_GROUP;                                                                     \
+            mt_ += r_ - NT * MT_GROUP;                                                              \
+        } else {                       /* the last, partial group */                                \
+            const int left_ = n_mt - mt_;                                                           \
+            NT = r_ / left_;                                                                        \
+            mt_ += r_ - NT * left_;                                                                 \
+        }                                                                                           \
         if (p.tile_expert) {                                                                        \
             E = list_entry(p.tile_expert, mt_);                                                     \
             R0 = list_entry(p.tile_row0, mt_);                                                      \
