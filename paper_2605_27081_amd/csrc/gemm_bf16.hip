@@ -274,15 +274,19 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     else                                                                                            \
         copy16_to_lds(((MODE == 0 && NWAVES * ((c) - A_CH) * 8 >= BN / 2) ? b_base1 : b_base0) + (k0) * 2, \
                       b_off[(c) >= A_CH ? (c) - A_CH : 0], &lb[(wave_u + NWAVES * ((c) - A_CH)) * 64]);
-    // the MFMAs of one k-step with the copy instructions of a slice dealt out between them, so that
-    // the wavefront never queues several copies at once (a full address queue stalls the wavefront,
-    // MFMAs included)
-#define GM_MFMA_COPIES(fa, fb, la, lb, k0, on)                                                      \
+    // the MFMAs of one k-step with copy instructions of a slice dealt out between them, one behind
+    // every COPY_EVERY-th MFMA starting with copy c0, so that the wavefront never queues several
+    // copies at once (a full address queue stalls the wavefront, MFMAs included).  The compute
+    // unit's memory path takes a slice's 64 copies of 1 KB at 64 bytes per cycle, as long as the
+    // MFMAs of two k-steps: the copies are therefore spread over the last two k-steps of a slice.
+    constexpr int COPY_EVERY = 2;
+    static_assert(COPIES * COPY_EVERY == 2 * TM * TN, "a slice's copies are dealt out over the MFMAs of two k-steps");
+#define GM_MFMA_COPIES(fa, fb, la, lb, k0, on, c0)                                                  \
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
         _Pragma("unroll") for (int ni = 0; ni < TN; ++ni) {                                          \
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[mi][ni], 0, 0, 0); \
             __builtin_amdgcn_sched_barrier(0);                                                      \
-            if (mi * TN + ni < COPIES && (on)) { GM_COPY_ONE(la, lb, k0, mi * TN + ni) }            \
+            if ((mi * TN + ni) % COPY_EVERY == 0 && (on)) { GM_COPY_ONE(la, lb, k0, (c0) + (mi * TN + ni) / COPY_EVERY) } \
             __builtin_amdgcn_sched_barrier(0);                                                      \
         }
     // k-steps of one slice: fragments of step ks+1 are read while the MFMAs of step ks run.  MID runs
@@ -305,9 +309,9 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         __builtin_amdgcn_sched_barrier(0);                                                          \
         MID                                                                                         \
         __builtin_amdgcn_sched_barrier(0);                                                          \
-        LAST(fa0, fb0)                                                                              \
+        LAST(fa0, fb0, 0)                                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
-        GM_MFMA(fa1, fb1)                                                                           \
+        LAST(fa1, fb1, TM * TN / COPY_EVERY)                                                        \
     }
     // Workgroup barrier that orders LDS traffic only.  (__syncthreads would also wait for every
     // direct-to-LDS copy in flight.)
@@ -442,8 +446,8 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         }
 #define GM_STEP0_EVEN(fa, fb)                                                                       \
     if (kt == 0) { GM_MFMA_FIRST(fa, fb) } else { GM_MFMA(fa, fb) }
-#define GM_LAST_REFILL0(fa, fb) GM_MFMA_COPIES(fa, fb, lds_a0, lds_b0, (kt + 2) * GM_BK, refill0)
-#define GM_LAST_REFILL1(fa, fb) GM_MFMA_COPIES(fa, fb, lds_a1, lds_b1, (kt + 3) * GM_BK, refill1)
+#define GM_LAST_REFILL0(fa, fb, c0) GM_MFMA_COPIES(fa, fb, lds_a0, lds_b0, (kt + 2) * GM_BK, refill0, c0)
+#define GM_LAST_REFILL1(fa, fb, c0) GM_MFMA_COPIES(fa, fb, lds_a1, lds_b1, (kt + 3) * GM_BK, refill1, c0)
         for (int kt = 0; kt < nk; kt += 2) {
             const bool refill0 = kt + 2 < nk;
             GM_COMPUTE(lds_a0, lds_b0, GM_STEP0_EVEN, GM_LDS_BARRIER();, GM_LAST_REFILL0)
