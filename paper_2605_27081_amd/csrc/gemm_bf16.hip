@@ -253,20 +253,34 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     const int b_tile0 = (MODE == 0) ? wn * 32 * 8 : wn * TN * 32 * 8;            // + ni * B_TILE_STEP
     constexpr int B_TILE_STEP = (MODE == 0) ? (BN / 2) * 8 : 32 * 8;
 
+    // The j-th fragment read of a k-step, in the order in which the MFMAs (row tile slowest) first need
+    // them: B 0, A 0, the other B fragments, the other A fragments.  All eight wavefronts ask the LDS
+    // for their fragments at the same moment behind a barrier; the first MFMA can go once two reads
+    // are back, not five.
+#define GM_READ_ONE(la, lb, ks, fa, fb, j)                                                          \
+    if ((j) == 0) fb[0] = *reinterpret_cast<const bf16x8_t *>(&lb[b_tile0 + fr_idx[ks]]);           \
+    else if ((j) == 1) fa[0] = *reinterpret_cast<const bf16x8_t *>(&la[a_tile0 + fr_idx[ks]]);      \
+    else if ((j) < 1 + TN) fb[((j) < 1 + TN && (j) >= 2) ? (j) - 1 : 0] =                           \
+        *reinterpret_cast<const bf16x8_t *>(&lb[b_tile0 + fr_idx[ks] + ((j) - 1) * B_TILE_STEP]);   \
+    else fa[((j) >= 1 + TN) ? (j) - TN : 0] =                                                       \
+        *reinterpret_cast<const bf16x8_t *>(&la[a_tile0 + fr_idx[ks] + ((j) - TN) * 256]);
 #define GM_READ_FRAGS(la, lb, ks, fa, fb)                                                           \
-    _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
-        fa[mi] = *reinterpret_cast<const bf16x8_t *>(&la[a_tile0 + fr_idx[ks] + mi * 256]);          \
-    _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                                \
-        fb[ni] = *reinterpret_cast<const bf16x8_t *>(&lb[b_tile0 + fr_idx[ks] + ni * B_TILE_STEP]);
+    _Pragma("unroll") for (int j_ = 0; j_ < TM + TN; ++j_) { GM_READ_ONE(la, lb, ks, fa, fb, j_) }
 #define GM_MFMA(fa, fb)                                                                             \
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
         _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                            \
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[mi][ni], 0, 0, 0);
-    // the first k-step of a tile starts the accumulators from the constant zero (no registers to clear)
-#define GM_MFMA_FIRST(fa, fb)                                                                       \
+    // the MFMAs of a k-step with the fragment reads of the next k-step dealt out behind the first of them
+    // (issued in one block behind the barrier they would stand in the LDS queue in front of the other
+    // wavefronts' first fragments); ZERO: start the accumulators from the constant zero
+#define GM_MFMA_READS(fa, fb, ZERO, la, lb, ks, fa_nx, fb_nx)                                       \
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
-        _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                            \
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], zero16, 0, 0, 0);
+        _Pragma("unroll") for (int ni = 0; ni < TN; ++ni) {                                          \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], (ZERO) ? zero16 : acc[mi][ni], 0, 0, 0); \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+            if (mi * TN + ni < TM + TN) { GM_READ_ONE(la, lb, ks, fa_nx, fb_nx, mi * TN + ni) }     \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+        }
     // copy instruction c of a slice (0 .. A_CH-1: A rows, then B rows)
 #define GM_COPY_ONE(la, lb, k0, c)                                                                  \
     if ((c) < A_CH)                                                                                 \
@@ -297,9 +311,8 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     {                                                                                               \
         bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];                                                \
         GM_READ_FRAGS(la, lb, 0, fa0, fb0)                                                           \
-        GM_READ_FRAGS(la, lb, 1, fa1, fb1)                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
-        STEP0(fa0, fb0)                                                                             \
+        STEP0(fa0, fb0, la, lb, fa1, fb1)                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
         GM_READ_FRAGS(la, lb, 2, fa0, fb0)                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
@@ -444,8 +457,9 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
                 for (int i = 0; i < A_CH; ++i) a_row_nx[i] = 0;
             }
         }
-#define GM_STEP0_EVEN(fa, fb)                                                                       \
-    if (kt == 0) { GM_MFMA_FIRST(fa, fb) } else { GM_MFMA(fa, fb) }
+#define GM_STEP0_EVEN(fa, fb, la, lb, fa_nx, fb_nx)                                                 \
+    if (kt == 0) { GM_MFMA_READS(fa, fb, 1, la, lb, 1, fa_nx, fb_nx) } else { GM_MFMA_READS(fa, fb, 0, la, lb, 1, fa_nx, fb_nx) }
+#define GM_STEP0_ODD(fa, fb, la, lb, fa_nx, fb_nx) GM_MFMA_READS(fa, fb, 0, la, lb, 1, fa_nx, fb_nx)
 #define GM_LAST_REFILL0(fa, fb, c0) GM_MFMA_COPIES(fa, fb, lds_a0, lds_b0, (kt + 2) * GM_BK, refill0, c0)
 #define GM_LAST_REFILL1(fa, fb, c0) GM_MFMA_COPIES(fa, fb, lds_a1, lds_b1, (kt + 3) * GM_BK, refill1, c0)
         for (int kt = 0; kt < nk; kt += 2) {
@@ -454,7 +468,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             if (kt + 1 < nk) {
                 const bool refill1 = kt + 3 < nk;
                 GM_WAIT_SLICE(refill0)
-                GM_COMPUTE(lds_a1, lds_b1, GM_MFMA, GM_LDS_BARRIER();, GM_LAST_REFILL1)
+                GM_COMPUTE(lds_a1, lds_b1, GM_STEP0_ODD, GM_LDS_BARRIER();, GM_LAST_REFILL1)
                 if (refill0) { GM_WAIT_SLICE(refill1) }
             }
         }
