@@ -281,6 +281,16 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             if (mi * TN + ni < TM + TN) { GM_READ_ONE(la, lb, ks, fa_nx, fb_nx, mi * TN + ni) }     \
             __builtin_amdgcn_sched_barrier(0);                                                      \
         }
+    // the same with the reads of two k-steps (ks_a first, ks_b two MFMAs behind it)
+#define GM_MFMA_READS2(fa, fb, la, lb, ks_a, fa_a, fb_a, ks_b, fa_b, fb_b)                          \
+    _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
+        _Pragma("unroll") for (int ni = 0; ni < TN; ++ni) {                                          \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[mi][ni], 0, 0, 0); \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+            if (mi * TN + ni < TM + TN) { GM_READ_ONE(la, lb, ks_a, fa_a, fb_a, mi * TN + ni) }     \
+            if (mi * TN + ni >= TM * TN - (TM + TN)) { GM_READ_ONE(la, lb, ks_b, fa_b, fb_b, mi * TN + ni - (TM * TN - (TM + TN))) } \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+        }
     // copy instruction c of a slice (0 .. A_CH-1: A rows, then B rows)
 #define GM_COPY_ONE(la, lb, k0, c)                                                                  \
     if ((c) < A_CH)                                                                                 \
@@ -303,28 +313,25 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             if ((mi * TN + ni) % COPY_EVERY == 0 && (on)) { GM_COPY_ONE(la, lb, k0, (c0) + (mi * TN + ni) / COPY_EVERY) } \
             __builtin_amdgcn_sched_barrier(0);                                                      \
         }
-    // k-steps of one slice: fragments of step ks+1 are read while the MFMAs of step ks run.  MID runs
-    // behind the MFMAs of step 1, as soon as every fragment of the stage has been requested: it waits
-    // for them (the matrix cores are still busy with step 1), passes a barrier and may then refill the
-    // stage, two k-steps before the slice ends, so a copy has a slice and a half of MFMA time to land.
+    // k-steps of one slice, three fragment buffers: the fragments of step 1 are read under the MFMAs of
+    // step 0, those of steps 2 and 3 under the MFMAs of step 1 (step 3 into the buffer step 0 has
+    // left).  MID runs behind the MFMAs of step 1, when every fragment of the stage has been requested
+    // a while ago: it waits for the last of them, passes a barrier and may then refill the stage, two
+    // k-steps before the slice ends, so a copy has a slice and a half of MFMA time to land.
 #define GM_COMPUTE(la, lb, STEP0, MID, LAST)                                                            \
     {                                                                                               \
-        bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];                                                \
+        bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN], fa2[TM], fb2[TN];                              \
         GM_READ_FRAGS(la, lb, 0, fa0, fb0)                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
         STEP0(fa0, fb0, la, lb, fa1, fb1)                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
-        GM_READ_FRAGS(la, lb, 2, fa0, fb0)                                                           \
-        __builtin_amdgcn_sched_barrier(0);                                                          \
-        GM_MFMA(fa1, fb1)                                                                           \
-        __builtin_amdgcn_sched_barrier(0);                                                          \
-        GM_READ_FRAGS(la, lb, 3, fa1, fb1)                                                           \
+        GM_MFMA_READS2(fa1, fb1, la, lb, 2, fa2, fb2, 3, fa0, fb0)                                  \
         __builtin_amdgcn_sched_barrier(0);                                                          \
         MID                                                                                         \
         __builtin_amdgcn_sched_barrier(0);                                                          \
-        LAST(fa0, fb0, 0)                                                                           \
+        LAST(fa2, fb2, 0)                                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
-        LAST(fa1, fb1, TM * TN / COPY_EVERY)                                                        \
+        LAST(fa0, fb0, TM * TN / COPY_EVERY)                                                        \
     }
     // Workgroup barrier that orders LDS traffic only.  (__syncthreads would also wait for every
     // direct-to-LDS copy in flight.)
