@@ -16,9 +16,11 @@
 // the same (m, n) in two accumulators and applies SwiGLU in registers.  LDS rows are 8 chunks of
 // 16 bytes in an XOR-swizzled layout (lds_slot) that keeps the row-per-lane fragment reads and the
 // global->LDS copies free of bank conflicts.  Slices move global -> LDS directly
-// (global_load_lds_dwordx4, no staging registers): the copy of slice k+1 into the other LDS stage is
-// issued before the MFMAs of slice k and has that whole MFMA phase to land (one barrier per slice);
-// MFMA fragments are double-buffered in registers so LDS latency hides behind matrix-core work.
+// (global_load_lds_dwordx4, no staging registers) into two stages: a stage is refilled with the slice
+// after next as soon as all its fragments have been read, the copy instructions dealt out between
+// the MFMAs of the slice's last two k-steps, and has about a slice and a half of MFMA time to land
+// (two barriers per slice).  MFMA fragments go through three register buffers, read one to two
+// k-steps ahead, so LDS latency hides behind matrix-core work.
 // The MFMAs take the B rows as their first operand, so the accumulators hold the tile transposed:
 // a lane owns one output row and four adjacent columns per register group, which the epilogue packs
 // into 8-byte pieces of a row without exchanging values between lanes.
