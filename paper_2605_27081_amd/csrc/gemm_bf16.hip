@@ -283,14 +283,15 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
             if (mi * TN + ni < TM + TN) { GM_READ_ONE(la, lb, ks, fa_nx, fb_nx, mi * TN + ni) }     \
             __builtin_amdgcn_sched_barrier(0);                                                      \
         }
-    // the same with the reads of two k-steps (ks_a first, ks_b two MFMAs behind it)
+    // the same with the reads of two k-steps, two reads behind each of the first MFMAs (all of them are
+    // then on their way two MFMAs before the barrier that waits for them)
 #define GM_MFMA_READS2(fa, fb, la, lb, ks_a, fa_a, fb_a, ks_b, fa_b, fb_b)                          \
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
         _Pragma("unroll") for (int ni = 0; ni < TN; ++ni) {                                          \
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[mi][ni], 0, 0, 0); \
             __builtin_amdgcn_sched_barrier(0);                                                      \
             if (mi * TN + ni < TM + TN) { GM_READ_ONE(la, lb, ks_a, fa_a, fb_a, mi * TN + ni) }     \
-            if (mi * TN + ni >= TM * TN - (TM + TN)) { GM_READ_ONE(la, lb, ks_b, fa_b, fb_b, mi * TN + ni - (TM * TN - (TM + TN))) } \
+            if (mi * TN + ni < TM + TN) { GM_READ_ONE(la, lb, ks_b, fa_b, fb_b, mi * TN + ni) }     \
             __builtin_amdgcn_sched_barrier(0);                                                      \
         }
     // copy instruction c of a slice (0 .. A_CH-1: A rows, then B rows)
