@@ -275,12 +275,19 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // the MFMAs of a k-step with the fragment reads of the next k-step dealt out behind the first of them
     // (issued in one block behind the barrier they would stand in the LDS queue in front of the other
     // wavefronts' first fragments); ZERO: start the accumulators from the constant zero
+    // Only the first FRONT reads of the k-step's own fragments go out in front of its MFMAs (what the
+    // first two MFMAs need); the rest follow behind the first MFMAs, then the next k-step's.
+    constexpr int FRONT = 1 + TN;
+    static_assert(TM * TN >= FRONT - 1 + TM + TN, "a k-step has enough MFMAs to deal the reads out behind");
 #define GM_MFMA_READS(fa, fb, ZERO, la, lb, ks, fa_nx, fb_nx)                                       \
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                \
         _Pragma("unroll") for (int ni = 0; ni < TN; ++ni) {                                          \
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], (ZERO) ? zero16 : acc[mi][ni], 0, 0, 0); \
             __builtin_amdgcn_sched_barrier(0);                                                      \
-            if (mi * TN + ni < TM + TN) { GM_READ_ONE(la, lb, ks, fa_nx, fb_nx, mi * TN + ni) }     \
+            if (mi * TN + ni < TM + TN - FRONT) { GM_READ_ONE(la, lb, (ks) - 1, fa, fb, FRONT + mi * TN + ni) } \
+            if (mi * TN + ni >= FRONT - 1 && mi * TN + ni < FRONT - 1 + TM + TN) {                  \
+                GM_READ_ONE(la, lb, ks, fa_nx, fb_nx, mi * TN + ni - (FRONT - 1))                   \
+            }                                                                                       \
             __builtin_amdgcn_sched_barrier(0);                                                      \
         }
     // the same with the reads of two k-steps, two reads behind each of the first MFMAs (all of them are
@@ -324,7 +331,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 #define GM_COMPUTE(la, lb, STEP0, MID, LAST)                                                            \
     {                                                                                               \
         bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN], fa2[TM], fb2[TN];                              \
-        GM_READ_FRAGS(la, lb, 0, fa0, fb0)                                                           \
+        _Pragma("unroll") for (int j_ = 0; j_ < FRONT; ++j_) { GM_READ_ONE(la, lb, 0, fa0, fb0, j_) } \
         __builtin_amdgcn_sched_barrier(0);                                                          \
         STEP0(fa0, fb0, la, lb, fa1, fb1)                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
