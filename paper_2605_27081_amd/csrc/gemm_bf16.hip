@@ -396,33 +396,37 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
     // is stored the ordinary way, which is acknowledged sooner: the next tile's first wait on the vector
     // memory counter also waits for these stores).  e_base is the wave-uniform address
     // of the tile's first output element; offsets inside a tile fit 32 bits (checked by the launcher).
-#define GM_EPI_STORE(mi, st, e_base, e_rows, e_cols)                                                \
+#define GM_EPI_STORE2(mi_a, st_a, mi_b, st_b, e_base, e_rows, e_cols)                               \
     {                                                                                               \
         constexpr int NJ = 64 * CPR / THREADS;                                                      \
         const int R0 = tid / CPR, ch = tid % CPR;   /* band row over both wm halves, chunk in the row */ \
-        u32x4_t v[NJ];                                                                              \
+        u32x4_t v[2][NJ];                                                                           \
         _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                             \
             const int R = R0 + j * (THREADS / CPR);                                                 \
-            v[j] = *reinterpret_cast<const u32x4_t *>(reinterpret_cast<const char *>(st) + R * ROWB + ((ch ^ (R & 7)) << 4)); \
+            v[0][j] = *reinterpret_cast<const u32x4_t *>(reinterpret_cast<const char *>(st_a) + R * ROWB + ((ch ^ (R & 7)) << 4)); \
+            v[1][j] = *reinterpret_cast<const u32x4_t *>(reinterpret_cast<const char *>(st_b) + R * ROWB + ((ch ^ (R & 7)) << 4)); \
         }                                                                                           \
         static_assert(NJ == 2 || NJ == 4, "the pin below is written for two or four chunks per thread"); \
-        /* all reads are issued before the first masked store (they would otherwise sink into its branch) */ \
-        if (NJ == 4) asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[NJ - 2]), "+v"(v[NJ - 1]));   \
-        else asm volatile("" : "+v"(v[0]), "+v"(v[1]));                                             \
-        _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                             \
-            const int R = R0 + j * (THREADS / CPR);                                                 \
-            const int m = ((R >> 5) * TM + (mi)) * 32 + (R & 31);                                   \
-            if (m < (e_rows) && ch * 8 < (e_cols)) {                                                \
-                u32x4_t *dst_ = reinterpret_cast<u32x4_t *>((e_base) + ((uint32_t)m * ldc_bytes + (uint32_t)ch * 16u)); \
-                if (MODE == 1 && (mi) == TM - 1) *dst_ = v[j];                                      \
-                else __builtin_nontemporal_store(v[j], dst_);                                       \
+        /* Every LDS read of both bands is issued before the first store (a read would otherwise sink  \
+           into its store's branch, behind stores that can stand in a full queue).  The staging areas   \
+           are the landing zone of the next tile's second slice, whose copies a wavefront issues once   \
+           its own stores are out: by then every other wavefront's reads, a dozen instructions behind   \
+           the barrier, are long done, and the copied data is an L2 round trip further away. */         \
+        if (NJ == 4) asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[0][NJ - 2]), "+v"(v[0][NJ - 1]), \
+                                       "+v"(v[1][0]), "+v"(v[1][1]), "+v"(v[1][NJ - 2]), "+v"(v[1][NJ - 1])); \
+        else asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]));         \
+        _Pragma("unroll") for (int b = 0; b < 2; ++b)                                                \
+            _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                         \
+                const int mi_ = b ? (mi_b) : (mi_a);                                                \
+                const int R = R0 + j * (THREADS / CPR);                                             \
+                const int m = ((R >> 5) * TM + mi_) * 32 + (R & 31);                                \
+                if (m < (e_rows) && ch * 8 < (e_cols)) {                                            \
+                    u32x4_t *dst_ = reinterpret_cast<u32x4_t *>((e_base) + ((uint32_t)m * ldc_bytes + (uint32_t)ch * 16u)); \
+                    if (MODE == 1 && mi_ == TM - 1) *dst_ = v[b][j];                                \
+                    else __builtin_nontemporal_store(v[b][j], dst_);                                \
+                }                                                                                   \
             }                                                                                       \
-        }                                                                                           \
     }
-#define GM_EPI_BAND(mi, st, e_base, e_rows, e_cols)                                                 \
-    GM_EPI_STAGE(mi, st)                                                                            \
-    GM_LDS_BARRIER();                                                                               \
-    GM_EPI_STORE(mi, st, e_base, e_rows, e_cols)
 
     GM_TILE_INFO(q0, expert, row0, rows, nt)
     GM_TILE_ROWS(row0, rows, a_row)
@@ -534,14 +538,12 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
         }
         GM_EPI_STAGE(1, lds_b1)
         GM_LDS_BARRIER();
-        GM_EPI_STORE(0, lds_a1, e_base, e_rows, e_cols)
-        GM_EPI_STORE(1, lds_b1, e_base, e_rows, e_cols)
+        GM_EPI_STORE2(0, lds_a1, 1, lds_b1, e_base, e_rows, e_cols)
         GM_LDS_BARRIER();      // everyone has read bands 0 and 1
         GM_EPI_STAGE(2, lds_a1)
         GM_EPI_STAGE(3, lds_b1)
         GM_LDS_BARRIER();
-        GM_EPI_STORE(2, lds_a1, e_base, e_rows, e_cols)
-        GM_EPI_STORE(3, lds_b1, e_base, e_rows, e_cols)
+        GM_EPI_STORE2(2, lds_a1, 3, lds_b1, e_base, e_rows, e_cols)
         if (!has_next) break;
         has_next = has_nn;
         nx_expert = nn_expert; nx_row0 = nn_row0; nx_rows = nn_rows; nx_nt = nn_nt;
