@@ -179,6 +179,27 @@ __device__ __forceinline__ void logits_bf16(const bf16_t *__restrict__ x, int64_
         const int cur = kt & 1;
         if (kt + 1 < nk) { RT_LOAD_BF16((kt + 1) * RT_BK) }
         const u32x4_t *st = base + cur * STAGE_U4;
+        if (NT == 4) {
+            // 128 experts: wavefront w takes expert tile w for all four token tiles, so a k-step reads
+            // 4 token fragments + 3 weight pieces from LDS (7 KB) instead of 1 + 12 (13 KB); the sums
+            // are the same, element by element and in the same order
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                bf16x8_t a8[NT], w8[3];
+#pragma unroll
+                for (int m = 0; m < NT; ++m)
+                    a8[m] = *reinterpret_cast<const bf16x8_t *>(&st[swz_bf16(m * 32 + li, 2 * ks + lh)]);
+#pragma unroll
+                for (int pc = 0; pc < 3; ++pc)
+                    w8[pc] = *reinterpret_cast<const bf16x8_t *>(
+                        &st[A_U4 + pc * P_U4 + swz_bf16(wave * 32 + li, 2 * ks + lh)]);
+#pragma unroll
+                for (int pc = 0; pc < 3; ++pc)
+#pragma unroll
+                    for (int m = 0; m < NT; ++m)
+                        acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a8[m], w8[pc], acc[m], 0, 0, 0);
+            }
+        } else
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             // this lane's eight k values of the step: 16 ks + 8 lh + {0..7} = chunk 2 ks + lh
@@ -265,8 +286,10 @@ __global__ __launch_bounds__(256) void route_kernel(const XT *__restrict__ x, in
     for (int n = 0; n < NT; ++n)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int row = wave * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-            Ls[LL::at(row, n * 32 + li)] = acc[n][r];
+            // (bf16 hidden states, 128 experts: accumulator n is token tile n of expert tile `wave`)
+            const bool by_expert = sizeof(XT) == 2 && NT == 4;
+            const int row = (by_expert ? n : wave) * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+            Ls[LL::at(row, (by_expert ? wave : n) * 32 + li)] = acc[n][r];
         }
     __syncthreads();
 
