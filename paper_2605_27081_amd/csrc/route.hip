@@ -39,14 +39,16 @@ __device__ __forceinline__ int swz_f32(int r, int c)
 // 256-byte period.  Returns the offset in 16-byte units.
 __device__ __forceinline__ int swz_bf16(int r, int c) { return r * 4 + (c ^ ((r >> 2) & 3)); }
 
-// round-to-nearest-even bf16 pieces of an fp32 value: w = hi + mid + lo up to 2^-24 relative
-__device__ __forceinline__ void split3(float w, uint32_t &hi, uint32_t &mid, uint32_t &lo)
+// round-to-nearest-even bf16 pieces of two neighbouring fp32 weights: w = hi + mid + lo up to 2^-24
+// relative, each piece packed the way the LDS tiles hold it (first weight in the low half); three
+// packed conversions (v_cvt_pk_bf16_f32) for the pair
+__device__ __forceinline__ void split3_pair(float w0, float w1, uint32_t &hi, uint32_t &mid, uint32_t &lo)
 {
-    hi = f32_to_bf16(w);
-    const float r1 = w - bf16_to_f32((bf16_t)hi);
-    mid = f32_to_bf16(r1);
-    const float r2 = r1 - bf16_to_f32((bf16_t)mid);
-    lo = f32_to_bf16(r2);
+    hi = pack_bf16x2(w0, w1);
+    const float r0 = w0 - __uint_as_float(hi << 16), r1 = w1 - __uint_as_float(hi & 0xFFFF0000u);
+    mid = pack_bf16x2(r0, r1);
+    const float q0 = r0 - __uint_as_float(mid << 16), q1 = r1 - __uint_as_float(mid & 0xFFFF0000u);
+    lo = pack_bf16x2(q0, q1);
 }
 
 // Logit rows in LDS: experts [0, NE/2) then 4 floats of padding, experts [NE/2, NE), 4 more.  With a
@@ -163,12 +165,13 @@ __device__ __forceinline__ void logits_bf16(const bf16_t *__restrict__ x, int64_
     }                                                                                          \
     _Pragma("unroll") for (int i = 0; i < NT; ++i) {                                            \
         const int q_ = tid + 256 * i, r_ = q_ >> 3, c_ = q_ & 7;                               \
-        uint32_t h_[4], m_[4], l_[4];                                                          \
-        _Pragma("unroll") for (int e = 0; e < 4; ++e) split3(wv[i][e], h_[e], m_[e], l_[e]);     \
+        uint32_t h_[2], m_[2], l_[2];                                                          \
+        split3_pair(wv[i][0], wv[i][1], h_[0], m_[0], l_[0]);                                  \
+        split3_pair(wv[i][2], wv[i][3], h_[1], m_[1], l_[1]);                                  \
         uint2 *dst_ = reinterpret_cast<uint2 *>((st) + A_U4 + swz_bf16(r_, c_ >> 1)) + (c_ & 1); \
-        dst_[0] = make_uint2(h_[0] | (h_[1] << 16), h_[2] | (h_[3] << 16));                     \
-        dst_[2 * P_U4] = make_uint2(m_[0] | (m_[1] << 16), m_[2] | (m_[3] << 16));              \
-        dst_[4 * P_U4] = make_uint2(l_[0] | (l_[1] << 16), l_[2] | (l_[3] << 16));              \
+        dst_[0] = make_uint2(h_[0], h_[1]);                                                    \
+        dst_[2 * P_U4] = make_uint2(m_[0], m_[1]);                                              \
+        dst_[4 * P_U4] = make_uint2(l_[0], l_[1]);                                              \
     }
 
     const int nk = H / RT_BK;
