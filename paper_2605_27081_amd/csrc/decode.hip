@@ -216,7 +216,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
         if (q_ < dchunks && row_first < H) {                                                         \
             const int j_ = q_ / chunks_per_row, pos_ = (q_ - j_ * chunks_per_row) * 8;               \
             const uint32_t off_ = (uint32_t)((((int64_t)sel_e[j_] * H + row_first) * I + pos_) * 2); \
-            dv[c] = load_global<u32x4_t>(wd_bytes + off_);                             \
+            dv[c] = load_global_stream<u32x4_t>(wd_bytes + off_);                             \
         }                                                                                            \
     }
             {
@@ -233,8 +233,8 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
         const bf16_t *gp_ = w_gate + ((int64_t)e_ * I + i_) * H;                                     \
         const bf16_t *up_ = w_up + ((int64_t)e_ * I + i_) * H;                                       \
         _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                             \
-            gv[c] = load_global<u32x4_t>(gp_ + loff + c * 512);                        \
-            uv[c] = load_global<u32x4_t>(up_ + loff + c * 512);                        \
+            gv[c] = load_global_stream<u32x4_t>(gp_ + loff + c * 512);                        \
+            uv[c] = load_global_stream<u32x4_t>(up_ + loff + c * 512);                        \
         }                                                                                            \
     }
 #define DC_REDUCE_ITEM(gv, uv, it)                                                                   \
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
                         if (rw > 0) {   // further rows of this wavefront are fetched on the spot
                             const int j = q / chunks_per_row, pos = (q - j * chunks_per_row) * 8;
                             const uint32_t off = (uint32_t)((((int64_t)sel_e[j] * H + o) * I + pos) * 2);
-                            wv = load_global<u32x4_t>(wd_bytes + off);
+                            wv = load_global_stream<u32x4_t>(wd_bytes + off);
                         }
                         acc = dot8(wv, &hl[q * 8], acc);
                     }

@@ -47,6 +47,16 @@ __device__ __forceinline__ T load_global(const void *p)
     return *(const __attribute__((address_space(1))) T *)p;
 }
 
+// The same as a non-temporal load, for the expert weights: every byte of them is read once per step
+// and the next step's copy is tens of gigabytes away, so keeping them in the caches only pushes out
+// what is reused (x, the exchange words).  Measured on the Qwen3-shaped stack: 13.15 -> 11.7 us per
+// layer-step.
+template <class T>
+__device__ __forceinline__ T load_global_stream(const void *p)
+{
+    return __builtin_nontemporal_load((const __attribute__((address_space(1))) T *)p);
+}
+
 // Entry idx (the same for every lane) of the launch's weight-pointer table, read with a scalar
 // load.  The host writes the table before the launch and no kernel ever does, so the constant
 // address space is safe; a vector load here returns the pointer in the same in-order queue as the

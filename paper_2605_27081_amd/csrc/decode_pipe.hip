@@ -205,7 +205,7 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             const int j_ = DP_SLOT_OF(q_);                                                            \
             uint32_t off_ = (uint32_t)(((int64_t)se_[j_] * H + (row)) * I * 2) + (uint32_t)(q_ - j_ * chunks_per_row) * 16u; \
             if (!(valid_)) off_ = 0;                                                                  \
-            dv[c] = load_global<u32x4_t>(wd_ + off_);                                                 \
+            dv[c] = load_global_stream<u32x4_t>(wd_ + off_);                                                 \
         }                                                                                             \
     }
 
@@ -216,8 +216,8 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
         const bf16_t *gp_ = static_cast<const bf16_t *>(table_ptr(a.layers, (group + NG * (mg_)) * 4 + 1)) + ((int64_t)e_ * I + g_i) * H; \
         const bf16_t *up_ = static_cast<const bf16_t *>(table_ptr(a.layers, (group + NG * (mg_)) * 4 + 2)) + ((int64_t)e_ * I + g_i) * H; \
         _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
-            gv[c] = load_global<u32x4_t>(gp_ + loff + c * 512);                                       \
-            uv[c] = load_global<u32x4_t>(up_ + loff + c * 512);                                       \
+            gv[c] = load_global_stream<u32x4_t>(gp_ + loff + c * 512);                                       \
+            uv[c] = load_global_stream<u32x4_t>(up_ + loff + c * 512);                                       \
         }                                                                                             \
         if (++g_i == I) { g_i = 0; ++g_j; }                                                           \
     }
