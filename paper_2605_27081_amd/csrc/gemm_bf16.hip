@@ -133,10 +133,11 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_bf16_kernel(const K
 
     // Persistent workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs, so workgroup b runs
     // on XCD b % 8.  XCD x owns the contiguous range [x * chunk, (x + 1) * chunk) of logical tiles
-    // (in the grouped order described at MT_GROUP0) and its workgroups claim the tiles of that range one after the other from a
-    // counter: at any time the workgroups of one XCD therefore work on neighbouring tiles, which share
-    // A rows and expert weights through that XCD's L2.  Tile numbers are claimed three tiles ahead of
-    // their use (the descriptor and the row indices of a tile are each fetched a tile ahead).
+    // (in the grouped order described at MT_GROUP0) and its workgroups claim the tiles of that range
+    // one after the other from a counter: at any time the workgroups of one XCD therefore work on
+    // neighbouring tiles, which share A rows and expert weights through that XCD's L2.  Tile numbers
+    // are claimed three tiles ahead of their use (the descriptor and the row indices of a tile are
+    // each fetched a tile ahead).
     __shared__ int lds_claim[4];
     const int ntn = (p.n_out + BN_OUT - 1) / BN_OUT;
     const int n_mt = p.tile_expert ? *p.n_tiles : (p.dense_rows + BM - 1) / BM;
