@@ -48,7 +48,10 @@ __global__ __launch_bounds__(PM_TOKENS) void permute_count(const int32_t *__rest
     }
 }
 
-__global__ __launch_bounds__(128) void permute_scan(const int32_t *__restrict__ blk_hist, int n_blk,
+// One workgroup of PS_SEG x 128 threads: thread (seg, e) owns expert e's counts of one segment of the
+// token blocks, so the running sums over the blocks are PS_SEG times shorter chains of loads.
+constexpr int PS_SEG = 8;
+__global__ __launch_bounds__(PS_SEG * 128) void permute_scan(const int32_t *__restrict__ blk_hist, int n_blk,
                                                     int N, int tile_m, int max_tiles,
                                                     int32_t *__restrict__ blk_off,
                                                     int32_t *__restrict__ offsets,
@@ -57,21 +60,31 @@ __global__ __launch_bounds__(128) void permute_scan(const int32_t *__restrict__ 
                                                     int32_t *__restrict__ tile_rows,
                                                     int32_t *__restrict__ n_tiles, uint32_t *__restrict__ gemm_ctr)
 {
-    __shared__ int32_t cnt[128], off[129], tstart[129];
-    const int e = threadIdx.x;
-    if (e < GEMM_CTR_SETS * 8) gemm_ctr[e] = 0u;   // tile counters of the GEMM launches that follow
-    int run = 0;
+    __shared__ int32_t cnt[128], off[129], tstart[129], seg_sum[PS_SEG][128];
+    const int e = threadIdx.x & 127, seg = threadIdx.x >> 7;
+    if (threadIdx.x < GEMM_CTR_SETS * 8) gemm_ctr[threadIdx.x] = 0u;   // tile counters of the GEMM launches that follow
+    const int per_seg = (n_blk + PS_SEG - 1) / PS_SEG;
+    const int b0 = seg * per_seg, b1 = (b0 + per_seg < n_blk) ? b0 + per_seg : n_blk;
+    int sum = 0;
     if (e < N) {
 #pragma unroll 8
-        for (int b = 0; b < n_blk; ++b) {
+        for (int b = b0; b < b1; ++b) sum += blk_hist[(int64_t)b * N + e];
+    }
+    seg_sum[seg][e] = sum;
+    __syncthreads();
+    int run = 0;
+    for (int q = 0; q < seg; ++q) run += seg_sum[q][e];
+    if (e < N) {
+#pragma unroll 8
+        for (int b = b0; b < b1; ++b) {
             const int c = blk_hist[(int64_t)b * N + e];
             blk_off[(int64_t)b * N + e] = run;
             run += c;
         }
     }
-    cnt[e] = (e < N) ? run : 0;
+    if (seg == PS_SEG - 1) cnt[e] = (e < N) ? run : 0;   // the last segment ends with the expert's total
     __syncthreads();
-    if (e == 0) {
+    if (threadIdx.x == 0) {
         int o = 0, ts = 0;
         for (int q = 0; q < N; ++q) {
             off[q] = o;
@@ -84,9 +97,9 @@ __global__ __launch_bounds__(128) void permute_scan(const int32_t *__restrict__ 
         *n_tiles = ts < max_tiles ? ts : max_tiles;
     }
     __syncthreads();
-    if (e <= N) offsets[e] = off[e];
-    if (e == 0 && N == 128) offsets[128] = off[128];
-    if (e < N) {
+    if (seg == 0 && e <= N) offsets[e] = off[e];
+    if (threadIdx.x == 0 && N == 128) offsets[128] = off[128];
+    if (seg == 0 && e < N) {
         const int nt = tstart[e + 1] - tstart[e];
         for (int i = 0; i < nt; ++i) {
             const int ti = tstart[e] + i;
@@ -132,7 +145,7 @@ remoe_status launch_permute(const int32_t *idx, const float *w, int64_t T, int K
     int32_t *blk_off = pb.blk_hist + (int64_t)n_blk * N;
     hipLaunchKernelGGL(permute_count, dim3(n_blk), dim3(PM_TOKENS), 0, stream, idx, T, K, N, blk_hist,
                        pb.pair_slot);
-    hipLaunchKernelGGL(permute_scan, dim3(1), dim3(128), 0, stream, blk_hist, n_blk, N, tile_m,
+    hipLaunchKernelGGL(permute_scan, dim3(1), dim3(PS_SEG * 128), 0, stream, blk_hist, n_blk, N, tile_m,
                        max_tiles, blk_off, pb.offsets, pb.tile_expert, pb.tile_row0, pb.tile_rows,
                        pb.n_tiles, pb.gemm_ctr);
     const int64_t n_pairs = T * K;
