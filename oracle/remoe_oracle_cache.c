@@ -55,15 +55,20 @@ static int keep_before(int policy, int a, int b, const int64_t *last, const int6
  *   U = distinct requested ids; token hits = requested slots whose expert is resident (with
  *   multiplicity); unique misses = |U \ resident| -- all against the state before the step;
  *   then every expert of U is in the cache (a missing one has just been fetched), the bookkeeping
- *   of the policy is updated, and while more than `capacity` experts are held the one that
- *   keep_before ranks last is dropped.
+ *   of the policy is updated, and while more than `capacity` experts are held one is dropped:
+ *   the one keep_before ranks last among the held experts that this step did NOT request.  An
+ *   expert served in a step is not evicted before the step is over, and "LRU/LFU/FIFO satisfy
+ *   E_t in C_{t+1} under C >= K by evicting experts not in E_t" (App. A, step atomicity and
+ *   admission; Prop. 3.1's bound miss_t <= K - |E_t n E_{t-1}| rests on it).  Only when every held
+ *   expert was requested by this step (more distinct requests than capacity, outside the
+ *   proposition) does the ranking run over the requested ones.
  * Readings (the paper names the policies only):
  *   LRU    as in oracle_lru_list (recency key (step, id));
  *   FIFO   age = step at which the expert was last brought in; a hit does not renew it;
  *   LFU    frequency = number of steps of the trace so far that requested the expert (kept across
  *          evictions), ties to the more recently used;
- *   Belady the expert whose next request lies farthest ahead goes first (never again = farthest),
- *          ties to the higher id; a just-fetched expert may be the one dropped.
+ *   Belady among the experts the step did not request, the one whose next request lies farthest
+ *          ahead goes first (never again = farthest), ties to the higher id.
  */
 int oracle_cache_policy(const int32_t *idx, int64_t n_seq, int64_t n_steps, int top_k, int n_experts,
                         int capacity, int policy, uint64_t expert_bytes,
@@ -120,9 +125,11 @@ int oracle_cache_policy(const int32_t *idx, int64_t n_seq, int64_t n_steps, int 
             for (int q = 0; q < n_experts; ++q) held += resident[q];
             while (held > capacity) {
                 int victim = -1;
-                for (int q = 0; q < n_experts; ++q) {
-                    if (!resident[q]) continue;
-                    if (victim < 0 || keep_before(policy, victim, q, last, ins, freq, next_use)) victim = q;
+                for (int pass = 0; pass < 2 && victim < 0; ++pass) {   /* pass 0: experts outside this step's request */
+                    for (int q = 0; q < n_experts; ++q) {
+                        if (!resident[q] || (pass == 0 && req[q])) continue;
+                        if (victim < 0 || keep_before(policy, victim, q, last, ins, freq, next_use)) victim = q;
+                    }
                 }
                 resident[victim] = 0;
                 --held;

@@ -8,9 +8,9 @@
 // These policies carry state from step to step (unlike LRU, whose resident set is a function of
 // the last requests alone), so a trace is walked in order: one wavefront per trace, lane l owning
 // experts l and l + 64 with their resident bit and retention key in registers.  After a step every
-// requested expert is held; while more than C are held, the one with the smallest key is dropped
-// (two wavefront-wide minimum reductions: primary key, then secondary key, which ends in the
-// expert id and is therefore unique).  Keys (larger = kept longer):
+// requested expert is held; while more than C are held, the one with the smallest key among those
+// the step did not request is dropped (two wavefront-wide minimum reductions: primary key, then
+// secondary key, which ends in the expert id and is therefore unique).  Keys (larger = kept longer):
 //   LRU    (step of last use, id)                 FIFO  (step of last fetch, id)
 //   LFU    requests so far, then (step of last use, id)
 //   Belady (steps_total - step of next request, 127 - id): the next request farthest ahead goes first
@@ -146,12 +146,18 @@ __global__ __launch_bounds__(64) void cache_policy_kernel(const int32_t *__restr
             res1 |= req1;
             int held = __popcll(__ballot(res0)) + __popcll(__ballot(res1));
             while (held > C) {
-                bool c0 = res0, c1 = res1;
+                // Victims come from the held experts this step did not request: an expert served in a step
+                // stays until the step is over (App. A, step atomicity and admission: E_t is part of the
+                // next resident set whenever C >= K).  Only a step with more distinct requests than C
+                // leaves none of those, and then the ranking runs over the requested ones.
+                const bool free0 = res0 && !req0, free1 = res1 && !req1;
+                const bool any_free = (__ballot(free0) | __ballot(free1)) != 0ull;
+                bool c0 = any_free ? free0 : res0, c1 = any_free ? free1 : res1;
                 if (POLICY == REMOE_CACHE_LFU) {
-                    const uint32_t a0 = res0 ? khi0 : CP_NONE, a1 = res1 ? khi1 : CP_NONE;
+                    const uint32_t a0 = c0 ? khi0 : CP_NONE, a1 = c1 ? khi1 : CP_NONE;
                     const uint32_t mhi = wave_min_u32(a0 < a1 ? a0 : a1);
-                    c0 = res0 && khi0 == mhi;
-                    c1 = res1 && khi1 == mhi;
+                    c0 = c0 && khi0 == mhi;
+                    c1 = c1 && khi1 == mhi;
                 }
                 const uint32_t b0 = c0 ? klo0 : CP_NONE, b1 = c1 ? klo1 : CP_NONE;
                 const uint32_t mlo = wave_min_u32(b0 < b1 ? b0 : b1);

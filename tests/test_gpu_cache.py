@@ -92,6 +92,17 @@ def test_cache_full_length_trace_sampled():
         assert (tot["belady"] <= tot[p]).all()
 
 
+@pytest.mark.parametrize("policy", ["lru", "fifo", "lfu", "belady"])
+def test_cache_policies_keep_the_served_step(policy):
+    """App. A (step atomicity and admission) on the kernel's own output: with C >= K no policy evicts an
+    expert of the step it has just served, so every step fetches at most K - |E_t n E_{t-1}| experts."""
+    K, N, C = 8, 128, 16
+    idx = _trace(31, 6, 700, K, N, True, 0.9)
+    got = _gpu_cache(idx, N, C, policy, 1)
+    ov, _ = oracle.trace_reuse(idx, N)
+    assert (got["miss"][:, 1:].long() <= K - ov[:, 1:].long()).all()
+
+
 def test_cache_rejects_bad_arguments():
     idx = torch.zeros(1, 4, 2, dtype=torch.int32, device=DEV)
     z8 = torch.zeros(1, 4, dtype=torch.uint8, device=DEV)

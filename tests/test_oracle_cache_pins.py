@@ -50,15 +50,16 @@ def _textbook_fifo(seq, C):
 
 
 def _textbook_lfu(seq, C):
-    """LFU with request counts kept for the whole sequence, least-recently-used among equals."""
+    """LFU with request counts kept for the whole sequence, least-recently-used among equals: on a miss
+    with a full cache the victim is chosen among the pages already held, then the new page comes in."""
     cache, freq, last, miss = set(), collections.Counter(), {}, []
     for t, e in enumerate(seq):
         miss.append(0 if e in cache else 1)
+        if e not in cache and len(cache) == C:
+            cache.remove(min(cache, key=lambda x: (freq[x], last[x], x)))
         freq[e] += 1
         last[e] = t
         cache.add(e)
-        if len(cache) > C:
-            cache.remove(min(cache, key=lambda x: (freq[x], last[x], x)))
     return miss
 
 
@@ -80,16 +81,74 @@ def test_fifo_hit_does_not_renew():
     assert oracle.cache_policy(idx, 3, 2, "lru")["miss"][0].tolist() == [1, 1, 0, 1, 0, 1]
 
 
+# ---- the in-step rules, hand-worked at K = 2 --------------------------------------------------------
+def test_fifo_two_requests_per_step_hand_worked():
+    """FIFO, N = 5, K = 2, C = 3.  Two experts fetched in the same step have the same age; the lower id
+    counts as the earlier arrival and leaves first.
+      t0 {0,1}: cold, 2 misses.                      held {0,1}
+      t1 {2,3}: 2 misses; 4 held > 3; candidates outside the step: 0, 1 (both fetched at t0) -> 0 leaves.
+                                                      held {1,2,3}
+      t2 {1,4}: 1 hits, 4 misses -> 1 (had 1 left instead of 0 this would be 2).
+                4 held; candidates 2, 3 (both fetched at t1) -> 2 leaves.   held {1,3,4}
+      t3 {3,0}: 3 hits, 0 misses -> 1 (had 3 left instead of 2 this would be 2).
+                candidates 1 (t0), 4 (t2) -> 1 leaves.                      held {0,3,4}
+      t4 {4,1}: 4 hits, 1 misses -> 1."""
+    idx = torch.tensor([[[0, 1], [2, 3], [1, 4], [3, 0], [4, 1]]], dtype=torch.int32)
+    assert oracle.cache_policy(idx, 5, 3, "fifo")["miss"][0].tolist() == [2, 2, 1, 1, 1]
+
+
+def test_fifo_keeps_what_the_step_requested():
+    """FIFO, C = K = 2: t0 {0,1}; t1 {0,2}: 0 hits, 2 misses, and the expert that leaves is 1, the only
+    one the step did not ask for -- not 0, although 0 is the oldest arrival (App. A: an expert used in a
+    step is not evicted before the step is over).  t2 {0,2} then hits twice: miss_t <= K - overlap_t = 0."""
+    idx = torch.tensor([[[0, 1], [0, 2], [0, 2]]], dtype=torch.int32)
+    assert oracle.cache_policy(idx, 3, 2, "fifo")["miss"][0].tolist() == [2, 1, 0]
+    assert oracle.cache_policy(idx, 3, 2, "lfu")["miss"][0].tolist() == [2, 1, 0]
+
+
+def test_lfu_two_requests_per_step_hand_worked():
+    """LFU, N = 5, K = 2, C = 4; counts are kept across evictions, equal counts go by last use, equal last
+    use by id (lower id leaves first).
+      t0 {0,1}: 2 misses.  counts 0:1 1:1                        held {0,1}
+      t1 {0,2}: 0 hits, 2 misses -> 1.  counts 0:2 1:1 2:1         held {0,1,2}
+      t2 {3,4}: 2 misses; 5 held > 4; outside the step: 0 (count 2), 1 (count 1, last t0), 2 (count 1, last t1)
+                -> 1 leaves.                                      held {0,2,3,4}
+      t3 {1,2}: 1 misses, 2 hits -> 1.  counts 1:2 2:2; outside the step: 0 (2), 3 (1, last t2), 4 (1, last t2)
+                -> equal count and last use: 3 leaves.            held {0,1,2,4}
+      t4 {4,0}: both hit -> 0 (had 4 left instead of 3 this would be 1).
+      t5 {3,4}: 3 misses -> 1."""
+    idx = torch.tensor([[[0, 1], [0, 2], [3, 4], [1, 2], [4, 0], [3, 4]]], dtype=torch.int32)
+    assert oracle.cache_policy(idx, 5, 4, "lfu")["miss"][0].tolist() == [2, 1, 2, 1, 0, 1]
+
+
+@pytest.mark.parametrize("policy", list(oracle.POLICIES))
+@pytest.mark.parametrize("K,N,C", [(2, 6, 2), (2, 9, 3), (4, 16, 4), (6, 20, 8), (8, 128, 32)])
+def test_every_policy_keeps_the_served_step(policy, K, N, C):
+    """App. A: with C >= K every policy keeps E_t for the next step, so Prop. 3.1's bound
+    miss_t <= K - |E_t n E_{t-1}| holds for t >= 2 whatever the policy."""
+    idx = _trace(K * 7 + C, 4, 150, K, N)
+    miss = oracle.cache_policy(idx, N, C, policy)["miss"].long()
+    ov, _ = oracle.trace_reuse(idx, N)
+    assert (miss[:, 1:] <= K - ov[:, 1:].long()).all()
+
+
 # ---- Belady == the least number of misses any replacement choice can reach ----------------------
 def _least_misses(steps, C):
-    """Exhaustive search: after every step keep any subset (of size <= C) of resident | requested."""
+    """Exhaustive search over every replacement choice of a cache that serves and keeps each step's
+    request (App. A): after a step the resident set is any subset of resident | requested of size
+    <= C that contains the request (or, when the request alone exceeds C, any C of the requested)."""
     best = {frozenset(): 0}
     for req in steps:
         nxt = {}
         for res, m in best.items():
             m2 = m + len(req - res)
             cand = res | req
-            keeps = [cand] if len(cand) <= C else [frozenset(c) for c in itertools.combinations(cand, C)]
+            if len(cand) <= C:
+                keeps = [cand]
+            elif len(req) <= C:
+                keeps = [req | frozenset(c) for c in itertools.combinations(cand - req, C - len(req))]
+            else:
+                keeps = [frozenset(c) for c in itertools.combinations(req, C)]
             for k in keeps:
                 if k not in nxt or nxt[k] > m2:
                     nxt[k] = m2
@@ -98,7 +157,7 @@ def _least_misses(steps, C):
 
 
 @pytest.mark.parametrize("seed,K,N,C,T", [(1, 1, 4, 2, 10), (2, 2, 5, 2, 8), (3, 2, 5, 3, 9), (4, 3, 6, 3, 7),
-                                          (5, 2, 6, 4, 9), (6, 1, 5, 3, 12)])
+                                          (5, 2, 6, 4, 9), (6, 1, 5, 3, 12), (7, 2, 7, 3, 10), (8, 3, 7, 4, 8)])
 def test_belady_is_optimal_on_tiny_traces(seed, K, N, C, T):
     idx = _trace(seed, 6, T, K, N, distinct=(K > 1))
     got = oracle.cache_policy(idx, N, C, "belady")["total_miss"].tolist()
@@ -171,6 +230,25 @@ def test_step_summary_matches_numpy(L, S, T):
     assert torch.equal(hist, torch.bincount(ref.reshape(-1), minlength=L * 6 + 1))
     want = [int(np.percentile(ref.numpy().reshape(-1), p, method="inverted_cdf")) for p in (50, 95, 99)]
     assert pct.tolist() == want
+
+
+def test_step_summary_sums_beyond_the_table_share_its_last_bin():
+    """A histogram shorter than the largest per-step sum: every sum >= hist_len - 1 is counted in the last
+    bin (numpy: clip, then bincount), the per-step sums themselves are unchanged, and a percentile that
+    falls into that bin reads hist_len - 1."""
+    g = torch.Generator().manual_seed(77)
+    L, S, T, hist_len = 9, 3, 120, 5
+    miss = torch.randint(0, 4, (L, S, T), generator=g, dtype=torch.uint8)
+    allm, hist, pct = oracle.step_summary(miss, hist_len)
+    ref = miss.to(torch.int64).sum(0)
+    assert int(ref.max()) >= hist_len + 3                      # the overflow rule is exercised
+    assert torch.equal(allm.to(torch.int64), ref)
+    want = np.bincount(np.clip(ref.numpy().reshape(-1), 0, hist_len - 1), minlength=hist_len)
+    assert hist.tolist() == want.tolist() and int(hist.sum()) == S * T
+    cum = np.cumsum(want)
+    for k, p in enumerate((50, 95, 99)):
+        assert int(pct[k]) == int(np.searchsorted(100 * cum, p * S * T, side="left"))
+    assert int(pct[2]) == hist_len - 1
 
 
 # ---- balance: closed forms ----------------------------------------------------------------------
