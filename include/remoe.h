@@ -252,6 +252,36 @@ remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers,
                         int32_t layer_order, void *stream);
 
 /*
+ * moe_decode_static -- moe_decode for callers that cannot allocate device memory or hand over a
+ * workspace: code that runs under HIP graph capture, serving loops that must not touch the
+ * allocator, harnesses that forbid hipMalloc.  It takes no workspace.  The kernels' scratch (abort
+ * word, barrier flags, exchange rings) lives in a static device array inside the library of
+ * remoe_decode_static_bytes() = 2,625,792 bytes, which every GPU the library runs on holds until
+ * the process ends; that size covers every layer shape moe_decode accepts (a shape that needed
+ * more is refused with REMOE_E_WORKSPACE).  The call allocates and frees nothing, on the host side
+ * of the runtime or the device.
+ *
+ * Arguments, outputs, limits and error behaviour are those of moe_decode, with one addition:
+ *   out_abort   DEVICE pointer to one uint32 owned by the caller; after the call it holds the abort
+ *               word (non-zero: a wait inside the kernel exceeded `spin_limit_us`, the outputs of
+ *               this call are invalid).
+ *
+ * All calls on one GPU share that GPU's array, whatever their stream: calls that overlap in time on
+ * one GPU race on it and must be serialised by the caller.  The array keeps the previous call's
+ * contents; the flags and exchange words are cleared by a kernel at the start of every call.
+ */
+size_t remoe_decode_static_bytes(void);
+remoe_status moe_decode_static(const remoe_layer_desc *desc, int32_t n_layers,
+                               const void *const *layer_weights,
+                               const void *x, int64_t steps_total, int64_t step0, int64_t n_steps,
+                               void *y, int32_t *out_idx, float *out_w,
+                               int32_t n_caps, const int32_t *capacities, uint64_t expert_bytes,
+                               uint32_t *lru_state, uint8_t *out_overlap, uint8_t *out_miss,
+                               uint64_t *sum_overlap, uint64_t *total_miss, uint64_t *bytes_fetched,
+                               uint32_t *out_abort, uint64_t spin_limit_us,
+                               int32_t layer_order, void *stream);
+
+/*
  * cache_simulate -- the paper's expert-cache simulator for the replacement policies it reports
  * besides LRU (App. E.2 "Cache state": LRU / LFU / FIFO; App. F.1: Belady's MIN under the same
  * per-request resets).  One cold cache of `capacity` experts per trace.  Per step, against the

@@ -22,8 +22,10 @@ from .binding import (  # noqa: F401
     load_library,
     lru_simulate,
     moe_decode,
+    moe_decode_static,
     remoe_copy_probe,
     remoe_decode_workspace_bytes,
+    remoe_decode_static_bytes,
     moe_forward,
     moe_route,
     PROF_KINDS,

@@ -72,6 +72,11 @@ def load_library() -> ctypes.CDLL:
     lib.moe_decode.restype = ctypes.c_int
     lib.moe_decode.argtypes = [D, I32, P, P, I64, I64, I64, P, P, P, I32, ctypes.POINTER(I32), U64,
                                P, P, P, P, P, P, P, SZ, U64, I32, P]
+    lib.remoe_decode_static_bytes.restype = SZ
+    lib.remoe_decode_static_bytes.argtypes = []
+    lib.moe_decode_static.restype = ctypes.c_int
+    lib.moe_decode_static.argtypes = [D, I32, P, P, I64, I64, I64, P, P, P, I32, ctypes.POINTER(I32), U64,
+                                      P, P, P, P, P, P, P, U64, I32, P]
     lib.remoe_copy_probe.restype = ctypes.c_int
     lib.remoe_copy_probe.argtypes = [P, P, SZ, P]
     lib.remoe_profile_enable.restype = ctypes.c_int
@@ -219,6 +224,27 @@ def moe_decode(desc: LayerDesc, layer_weights: torch.Tensor, x: torch.Tensor, st
                                      _ptr(sum_overlap), _ptr(total_miss), _ptr(bytes_fetched), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), spin_limit_us, layer_order,
                                      _stream()))
+
+
+def remoe_decode_static_bytes() -> int:
+    return int(load_library().remoe_decode_static_bytes())
+
+
+def moe_decode_static(desc: LayerDesc, layer_weights: torch.Tensor, x: torch.Tensor, step0: int, n_steps: int,
+                      y: torch.Tensor, out_idx: torch.Tensor, out_w: torch.Tensor, capacities, expert_bytes: int,
+                      lru_state: torch.Tensor, out_overlap: torch.Tensor, out_miss: Optional[torch.Tensor],
+                      sum_overlap: torch.Tensor, total_miss: Optional[torch.Tensor],
+                      bytes_fetched: Optional[torch.Tensor], out_abort: torch.Tensor, spin_limit_us: int = 0,
+                      layer_order: int = 0) -> None:
+    """moe_decode without a workspace (scratch in a static device array); out_abort: one int32 on the device."""
+    n_layers = layer_weights.shape[0]
+    steps_total = x.shape[0]
+    caps = (ctypes.c_int32 * max(len(capacities), 1))(*capacities)
+    _check(load_library().moe_decode_static(ctypes.byref(desc), n_layers, _ptr(layer_weights), _ptr(x), steps_total,
+                                            step0, n_steps, _ptr(y), _ptr(out_idx), _ptr(out_w), len(capacities),
+                                            caps, expert_bytes, _ptr(lru_state), _ptr(out_overlap), _ptr(out_miss),
+                                            _ptr(sum_overlap), _ptr(total_miss), _ptr(bytes_fetched),
+                                            _ptr(out_abort), spin_limit_us, layer_order, _stream()))
 
 
 def remoe_cache_workspace_bytes(n_seq: int, n_steps: int, top_k: int, policy: int) -> int:

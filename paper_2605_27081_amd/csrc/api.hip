@@ -164,6 +164,40 @@ Workspace layout(const remoe_layer_desc *d, int64_t T, void *base_v)
     return w;
 }
 
+// ---- scratch of moe_decode_static -------------------------------------------------------------
+// Callers that cannot allocate (code under graph capture, serving loops) get the decode kernels'
+// scratch (abort word, barrier flags, rings of exchange words) from this array instead of a
+// workspace argument.  Its size covers every layer shape moe_decode supports: n_experts <= 128,
+// hidden <= 4096, top_k * inter <= 6144 give 4352 bytes of flags + 8 groups x 4 ring slots x
+// (2048 + 8192) eight-byte words.  Every GPU the library runs on holds its own copy until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address it yields (one per device) is what the kernels and the host-side layout use.
+constexpr size_t DECODE_STATIC_BYTES = 4352 + (size_t)8 * 4 * (2048 + 8192) * 8;
+static __device__ __align__(256) unsigned char g_decode_scratch[DECODE_STATIC_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_decode_scratch_ptr[MAX_DEVICES] = {};
+
+// device address of g_decode_scratch on the current device (looked up once per device)
+remoe_status decode_static_scratch(void **out)
+{
+    int dev = -1;
+    REMOE_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(REMOE_E_UNSUPPORTED, "device ordinal %d outside 0..%d", dev, MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_decode_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        REMOE_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_decode_scratch)));
+        if (!ptr || ((uintptr_t)ptr & 255)) return fail(REMOE_E_HIP, "static decode scratch has no usable device address");
+        g_decode_scratch_ptr[dev] = ptr;
+    }
+    *out = g_decode_scratch_ptr[dev];
+    return REMOE_OK;
+}
+
+__global__ void copy_abort_word_kernel(const uint32_t *src, uint32_t *dst) { *dst = src ? *src : 0u; }
+
 }  // namespace
 }  // namespace remoe
 
@@ -395,12 +429,13 @@ size_t remoe_decode_workspace_bytes(const remoe_layer_desc *desc)
     return decode_workspace_bytes(desc->hidden, desc->n_experts, desc->inter, desc->top_k);
 }
 
-remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers, const void *const *layer_weights,
-                        const void *x, int64_t steps_total, int64_t step0, int64_t n_steps, void *y,
-                        int32_t *out_idx, float *out_w, int32_t n_caps, const int32_t *capacities,
-                        uint64_t expert_bytes, uint32_t *lru_state, uint8_t *out_overlap, uint8_t *out_miss,
-                        uint64_t *sum_overlap, uint64_t *total_miss, uint64_t *bytes_fetched, void *workspace,
-                        size_t workspace_bytes, uint64_t spin_limit_us, int32_t layer_order, void *stream)
+// moe_decode and moe_decode_static share everything but where the scratch memory comes from.
+static remoe_status decode_impl(const remoe_layer_desc *desc, int32_t n_layers, const void *const *layer_weights,
+                                const void *x, int64_t steps_total, int64_t step0, int64_t n_steps, void *y,
+                                int32_t *out_idx, float *out_w, int32_t n_caps, const int32_t *capacities,
+                                uint64_t expert_bytes, uint32_t *lru_state, uint8_t *out_overlap, uint8_t *out_miss,
+                                uint64_t *sum_overlap, uint64_t *total_miss, uint64_t *bytes_fetched, void *workspace,
+                                size_t workspace_bytes, uint64_t spin_limit_us, int32_t layer_order, void *stream)
 {
     remoe_status st = validate_layer_desc(desc);
     if (st != REMOE_OK) return st;
@@ -444,6 +479,48 @@ remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers, const vo
     ProfScope prof(REMOE_PROF_DECODE, static_cast<hipStream_t>(stream));
     return layer_order == REMOE_DECODE_PIPELINED ? launch_decode_pipelined(d, static_cast<hipStream_t>(stream))
                                                  : launch_decode(d, static_cast<hipStream_t>(stream));
+}
+
+remoe_status moe_decode(const remoe_layer_desc *desc, int32_t n_layers, const void *const *layer_weights,
+                        const void *x, int64_t steps_total, int64_t step0, int64_t n_steps, void *y,
+                        int32_t *out_idx, float *out_w, int32_t n_caps, const int32_t *capacities,
+                        uint64_t expert_bytes, uint32_t *lru_state, uint8_t *out_overlap, uint8_t *out_miss,
+                        uint64_t *sum_overlap, uint64_t *total_miss, uint64_t *bytes_fetched, void *workspace,
+                        size_t workspace_bytes, uint64_t spin_limit_us, int32_t layer_order, void *stream)
+{
+    return decode_impl(desc, n_layers, layer_weights, x, steps_total, step0, n_steps, y, out_idx, out_w, n_caps,
+                       capacities, expert_bytes, lru_state, out_overlap, out_miss, sum_overlap, total_miss,
+                       bytes_fetched, workspace, workspace_bytes, spin_limit_us, layer_order, stream);
+}
+
+size_t remoe_decode_static_bytes(void) { return DECODE_STATIC_BYTES; }
+
+remoe_status moe_decode_static(const remoe_layer_desc *desc, int32_t n_layers, const void *const *layer_weights,
+                               const void *x, int64_t steps_total, int64_t step0, int64_t n_steps, void *y,
+                               int32_t *out_idx, float *out_w, int32_t n_caps, const int32_t *capacities,
+                               uint64_t expert_bytes, uint32_t *lru_state, uint8_t *out_overlap, uint8_t *out_miss,
+                               uint64_t *sum_overlap, uint64_t *total_miss, uint64_t *bytes_fetched,
+                               uint32_t *out_abort, uint64_t spin_limit_us, int32_t layer_order, void *stream)
+{
+    remoe_status st = validate_layer_desc(desc);
+    if (st != REMOE_OK) return st;
+    if (!out_abort) return fail(REMOE_E_INVALID_ARG, "out_abort is NULL");
+    const size_t need = decode_workspace_bytes(desc->hidden, desc->n_experts, desc->inter, desc->top_k);
+    if (need > DECODE_STATIC_BYTES)
+        return fail(REMOE_E_WORKSPACE, "moe_decode_static: this layer shape needs %zu bytes of scratch, the static "
+                    "array holds %zu; use moe_decode with a workspace", need, (size_t)DECODE_STATIC_BYTES);
+    void *scratch = nullptr;
+    st = decode_static_scratch(&scratch);
+    if (st != REMOE_OK) return st;
+    st = decode_impl(desc, n_layers, layer_weights, x, steps_total, step0, n_steps, y, out_idx, out_w, n_caps,
+                     capacities, expert_bytes, lru_state, out_overlap, out_miss, sum_overlap, total_miss,
+                     bytes_fetched, scratch, DECODE_STATIC_BYTES, spin_limit_us, layer_order, stream);
+    if (st != REMOE_OK) return st;
+    // hand the abort word (byte 128 of the scratch) to the caller; a call that ran no step reports 0
+    hipLaunchKernelGGL(copy_abort_word_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream),
+                       n_steps > 0 ? reinterpret_cast<const uint32_t *>(static_cast<const char *>(scratch) + 128) : nullptr,
+                       out_abort);
+    return check_hip(hipGetLastError(), "moe_decode_static abort-word copy");
 }
 
 size_t remoe_cache_workspace_bytes(int64_t n_seq, int64_t n_steps, int32_t top_k, int32_t policy)
