@@ -1,4 +1,5 @@
-"""Compile the CPU oracle into oracle/liboracle.so (gcc, C99, OpenMP over tokens)."""
+"""Compile the CPU oracle into oracle/liboracle.so (gcc, C99, OpenMP over tokens); build_sanitized()
+links the same sources with a small driver under the address and undefined-behaviour sanitizers."""
 import os
 import subprocess
 import sys
@@ -15,6 +16,22 @@ def build(verbose: bool = False) -> str:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
     return LIB
+
+
+SAN_DRIVER = os.path.join(HERE, "sanitize_check.c")
+SAN_EXE = os.path.join(HERE, "sanitize_check")
+
+
+def build_sanitized(verbose: bool = False) -> str:
+    """The oracle's sources plus sanitize_check.c as one executable under AddressSanitizer and
+    UndefinedBehaviorSanitizer (runtimes linked statically, so nothing has to be preloaded)."""
+    cmd = ["gcc", "-std=c99", "-O1", "-g", "-fno-omit-frame-pointer", "-fopenmp", "-Wall", "-Wextra",
+           "-ffp-contract=off", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-static-libasan", "-static-libubsan", "-o", SAN_EXE, SAN_DRIVER, *SRCS, "-lm"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return SAN_EXE
 
 
 def ensure_built() -> str:

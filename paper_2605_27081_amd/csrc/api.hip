@@ -38,7 +38,9 @@ remoe_status check_hip(hipError_t e, const char *what)
 // ---- optional per-kernel timing (benchmarks only) --------------------------------------------
 // When enabled, every kernel group an entry point launches is bracketed by a pair of HIP events on
 // the caller's stream; remoe_profile_read sums the elapsed times per kind.  Off by default: the
-// entry points then record nothing.
+// entry points then record nothing.  The events come from a pool that remoe_profile_enable fills
+// (PROF_POOL pairs, created once); the entry points themselves never create one, and a scope that
+// finds the pool empty is simply not recorded.
 namespace {
 
 struct ProfRecord { int kind; hipEvent_t start, stop; };
@@ -46,6 +48,7 @@ std::mutex g_prof_mutex;
 bool g_prof_on = false;
 std::vector<ProfRecord> g_prof_used;
 std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_free;
+constexpr size_t PROF_POOL = 4096;      // event pairs; enough for a dozen profiled passes over 48 layers
 
 class ProfScope {
 public:
@@ -53,14 +56,9 @@ public:
     {
         std::lock_guard<std::mutex> lock(g_prof_mutex);
         if (!g_prof_on) return;
-        ProfRecord r{kind, nullptr, nullptr};
-        if (!g_prof_free.empty()) {
-            r.start = g_prof_free.back().first;
-            r.stop = g_prof_free.back().second;
-            g_prof_free.pop_back();
-        } else if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) {
-            return;
-        }
+        if (g_prof_free.empty()) return;      // pool used up: this scope goes unrecorded (nothing is created here)
+        ProfRecord r{kind, g_prof_free.back().first, g_prof_free.back().second};
+        g_prof_free.pop_back();
         if (hipEventRecord(r.start, stream_) != hipSuccess) return;
         rec_ = r;
         active_ = true;
@@ -213,6 +211,17 @@ const char *remoe_last_error(void) { return g_err; }
 remoe_status remoe_profile_enable(int32_t on)
 {
     std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (on) {
+        while (g_prof_free.size() + g_prof_used.size() < PROF_POOL) {
+            hipEvent_t a = nullptr, b = nullptr;
+            if (hipEventCreate(&a) != hipSuccess) return fail(REMOE_E_HIP, "hipEventCreate failed while filling the timing pool");
+            if (hipEventCreate(&b) != hipSuccess) {
+                (void)hipEventDestroy(a);
+                return fail(REMOE_E_HIP, "hipEventCreate failed while filling the timing pool");
+            }
+            g_prof_free.emplace_back(a, b);
+        }
+    }
     g_prof_on = on != 0;
     return REMOE_OK;
 }

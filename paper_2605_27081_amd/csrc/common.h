@@ -6,6 +6,7 @@
 #include <stdio.h>
 
 #include "remoe.h"
+#include "remoe_bench.h"
 
 namespace remoe {
 

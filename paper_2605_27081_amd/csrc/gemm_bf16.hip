@@ -57,13 +57,23 @@ __device__ __forceinline__ int lds_slot(int r, int c) { return ((r ^ ((r >> 3) &
 // base + off (wave-uniform 64-bit base, per-lane 32-bit byte offset), land at lds_base + 16 l
 // (lds_base wave-uniform, handed over in M0).  Written as assembly so that the compiler keeps no
 // books on these copies: its own bookkeeping makes every later LDS read wait for all of them,
-// which would undo the overlap.  Every wait for a copy in this file is therefore explicit.  Nothing
-// else in the kernel uses M0.
+// which would undo the overlap.  Every wait for a copy in this file is therefore explicit.
+// The compiler pads its own instructions with the wait states the hardware asks for but does not
+// look inside an assembly block, so the block must not depend on any:
+//   * the address goes in as a per-lane 64-bit value in vector registers (the compiler's own add of
+//     base and offset in front of the block).  With the base in a scalar register pair the copy
+//     would read a scalar register as a memory address, and a scalar register that a vector
+//     instruction has just written (a spilled base restored with v_readlane) may not be used that
+//     way for five wait states: whether that happened would depend on register allocation;
+//   * M0 is written inside the block and the one wait state the copy needs behind that write is
+//     part of the block.  Nothing else in this kernel touches M0 (the compiler reserves it and has
+//     no use for it here; a host-side test of the generated code checks that).
 __device__ __forceinline__ void copy16_to_lds(const char *base, uint32_t off, const void *lds_base)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     const uint32_t dst = (uint32_t)(uintptr_t)lds_base;   // the low 32 bits of a generic LDS pointer are the LDS offset
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(off), "s"(base) : "memory");
+    const char *src = base + off;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
 #else
     (void)base;
     (void)off;

@@ -48,16 +48,65 @@ def compare_routing(gpu_idx: torch.Tensor, gpu_w: torch.Tensor, orc: dict, renor
     return ties, exp_w
 
 
-def check_output(y_gpu: torch.Tensor, y_ref: torch.Tensor, dtype: str):
+BF16_COL_BLOCK = 256     # columns of one output tile of the down projection
+
+
+def check_output(y_gpu: torch.Tensor, y_ref: torch.Tensor, dtype: str, report: dict = None):
+    """fp32: max |diff| / max |ref| over the layer.  bf16: the relative L2 error over the layer, and the
+    same bound for every token (row) on its own and for every (row, 256-column block) cell, so that one
+    wrong row or one wrong 16-byte piece of a row cannot hide in the layer's norm.  Returns the layer
+    figure; `report` (if given) receives the worst row and the worst cell."""
     yg = y_gpu.cpu().double()
     diff = yg - y_ref
     if dtype == "f32":
         err = float(diff.abs().max() / y_ref.abs().max())
         assert err <= F32_MAX_REL, f"fp32 max relative error {err:.3e} > {F32_MAX_REL}"
-    else:
-        err = float(diff.norm() / y_ref.norm())
-        assert err <= BF16_REL_L2, f"bf16 relative L2 error {err:.3e} > {BF16_REL_L2}"
+        return err
+    err = float(diff.norm() / y_ref.norm())
+    assert err <= BF16_REL_L2, f"bf16 relative L2 error {err:.3e} > {BF16_REL_L2}"
+    if diff.dim() == 2 and diff.shape[0] > 0:
+        row_err = diff.norm(dim=1) / y_ref.norm(dim=1)
+        worst_row = int(row_err.argmax())
+        assert float(row_err[worst_row]) <= BF16_REL_L2, (
+            f"row {worst_row}: bf16 relative L2 error {float(row_err[worst_row]):.3e} > {BF16_REL_L2}")
+        H = diff.shape[1]
+        nb = (H + BF16_COL_BLOCK - 1) // BF16_COL_BLOCK
+        pad = nb * BF16_COL_BLOCK - H
+        d2 = torch.nn.functional.pad(diff, (0, pad)).reshape(-1, nb, BF16_COL_BLOCK)
+        r2 = torch.nn.functional.pad(y_ref, (0, pad)).reshape(-1, nb, BF16_COL_BLOCK)
+        cell = d2.norm(dim=2) / r2.norm(dim=2).clamp_min(1e-300)
+        worst_cell = float(cell.max())
+        assert worst_cell <= BF16_REL_L2, f"a (row, column-block) cell is off by {worst_cell:.3e} > {BF16_REL_L2}"
+        if report is not None:
+            report.update(worst_row=float(row_err[worst_row]), worst_cell=worst_cell)
     return err
+
+
+def slot_aimed_tokens(idx: torch.Tensor, n_experts: int, tile: int = 256, experts: int = 16, boundaries: int = 4):
+    """Tokens that sit where the grouped GEMM is most likely to go wrong, worked out on the host from the
+    expert ids alone: the (token, j) pairs are sorted by expert, stable in pair order (the slot order of
+    the sort step), and for `experts` evenly spaced experts the tokens of the first and last slot and of
+    the slots either side of up to `boundaries` tile boundaries (the first and the last ones) are taken.
+    Returns a sorted tensor of distinct token numbers."""
+    T, K = idx.shape
+    flat = idx.reshape(-1).long().cpu()
+    order = torch.sort(flat, stable=True).indices          # slot -> pair index
+    counts = torch.bincount(flat, minlength=n_experts)
+    offs = torch.cumsum(counts, 0) - counts
+    picked = []
+    busy = [e for e in range(n_experts) if int(counts[e]) > 0]
+    step = max(1, len(busy) // experts)
+    chosen = busy[::step][:experts]
+    if busy and busy[-1] not in chosen:
+        chosen.append(busy[-1])
+    for e in chosen:
+        lo, n = int(offs[e]), int(counts[e])
+        slots = {lo, lo + n - 1}
+        cuts = list(range(tile, n, tile))
+        for b in cuts[:boundaries // 2] + cuts[-(boundaries - boundaries // 2):]:
+            slots.update((lo + b - 1, lo + b))
+        picked += [int(order[s]) // K for s in slots]
+    return torch.tensor(sorted(set(picked)), dtype=torch.int64)
 
 
 def oracle_layer(x_cpu, weights_cpu, top_k, renorm, gpu_idx, gpu_w, tokens=None):

@@ -22,16 +22,22 @@ def lib():
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "remoe.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b([a-z_0-9]+)\s*\([^;{}]*\)\s*;", text)
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        if not header.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b([a-z_0-9]+)\s*\([^;{}]*\)\s*;", text)
     return sorted(set(names))
 
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert {"moe_route", "moe_forward", "trace_reuse", "lru_simulate", "remoe_workspace_bytes",
-            "remoe_last_error", "remoe_version"} <= set(names)
+            "remoe_last_error", "remoe_version", "moe_decode", "moe_decode_static", "remoe_profile_enable",
+            "remoe_copy_probe"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in remoe.h but not exported"
 

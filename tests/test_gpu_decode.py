@@ -120,18 +120,30 @@ def test_decode_orders_agree():
 
 @pytest.mark.parametrize("order", [remoe.REMOE_DECODE_CHAINED, remoe.REMOE_DECODE_PIPELINED], ids=["chained", "pipelined"])
 def test_decode_wait_limit_aborts_cleanly(order):
-    """A wait limit the barrier cannot meet makes the kernel give up: it must still exit (no hang)
-    and report it through the abort flag."""
+    """The smallest wait limit (1 us per wait) on a 16-layer stack.  Either every wait was met, and
+    then every output equals the unlimited run's bit for bit, or a wait ran out, and then the abort
+    word (byte 128 of the workspace) is 1, every workgroup has left the kernel (the stream
+    synchronises), and the next call on the same device runs normally and reproduces the unlimited
+    run."""
     L, T, H, N, I, K = 2, 4, 512, 16, 64, 4
-    layers = _layers(81, L, H, N, I, 0.05)
+    layers = _layers(81, L, H, N, I, 0.05) * 8
     x = wl.ar1_hidden_states(81, 1, T, H, 0.5, torch.bfloat16, DEV)[0].contiguous()
     desc = remoe.LayerDesc(H, N, I, K, 1, 0, 0, 1)
-    ok = _run_decode(desc, layers, x, [4], 1, [T], order=order)
-    assert ok["abort"] == 0
-    # the limit is per wait; 10 ns cannot cover one atomic round trip of 256 workgroups
-    # (spin_limit_us is in whole microseconds, so this uses the smallest value, 1 us, and many layers)
-    aborted = _run_decode(desc, layers * 8, x, [4], 1, [T], spin_limit_us=1, order=order)
-    assert aborted["abort"] in (0, 1)      # either it kept up or it gave up; it returned either way
+    keys = ("idx", "ov", "miss", "sum_ov", "tot", "bytes", "state")
+    ref = _run_decode(desc, layers, x, [4], 1, [T], order=order)
+    assert ref["abort"] == 0
+    lim = _run_decode(desc, layers, x, [4], 1, [T], spin_limit_us=1, order=order)   # returns after a synchronize
+    assert lim["abort"] in (0, 1)
+    _say(f"  1 us wait limit: abort word {lim['abort']}")
+    if lim["abort"] == 0:
+        for k in keys:
+            assert torch.equal(lim[k], ref[k]), k
+        assert torch.equal(lim["y"].view(torch.int16), ref["y"].view(torch.int16))
+    again = _run_decode(desc, layers, x, [4], 1, [T], order=order)
+    assert again["abort"] == 0
+    for k in keys:
+        assert torch.equal(again[k], ref[k]), k
+    assert torch.equal(again["y"].view(torch.int16), ref["y"].view(torch.int16))
 
 
 def test_decode_rejects_unsupported_layers():

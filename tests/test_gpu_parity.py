@@ -247,6 +247,38 @@ def test_layer_forward_matches_oracle(dtype, T, H, N, I, K, renorm, Is, gate):
     assert torch.equal(idx, idx2) and torch.equal(gw, gw2)
 
 
+def test_layer_forward_many_tiles_per_workgroup_every_token():
+    """65,536 tokens of a narrow layer: about 1,030 row tiles for 256 persistent workgroups, so every
+    workgroup runs the multi-tile path of the grouped GEMM (next tile's first slice fetched under the
+    epilogue, tiles claimed three ahead, ranges of other XCDs taken over at the end), and the layer
+    is small enough for the oracle to evaluate EVERY token.  The workspace starts as bf16 NaNs, so a
+    tile that was skipped shows; a tile claimed twice would not change the result, but a second run
+    must reproduce the first bit for bit."""
+    T, H, N, I, K = 65536, 128, 8, 64, 4
+    _say(f"forward many tiles: T={T} H={H} N={N} I={I} K={K}")
+    w = _gen_layer(58, H, N, I, 0, False, "bf16", std=0.05)
+    x = wl.ar1_hidden_states(58, 16, T // 16, H, 0.8, torch.bfloat16, DEV).reshape(T, H).contiguous()
+    desc = remoe.LayerDesc(H, N, I, K, 1, 0, 0, 1)
+    outs = []
+    for _ in range(2):
+        ws = torch.full((remoe.remoe_workspace_bytes(desc, T),), 0xFF, dtype=torch.uint8, device=DEV)
+        y = torch.full((T, H), float("nan"), dtype=torch.bfloat16, device=DEV)
+        idx = torch.full((T, K), -1, dtype=torch.int32, device=DEV)
+        gw = torch.full((T, K), float("nan"), dtype=torch.float32, device=DEV)
+        remoe.moe_forward(desc, x, w["w_router"], w["w_gate"], w["w_up"], w["w_down"], None, None, None, None,
+                          y, idx, gw, ws)
+        torch.cuda.synchronize()
+        outs.append((y, idx, gw))
+    y, idx, gw = outs[0]
+    assert torch.isfinite(y.float()).all()
+    assert torch.equal(y.view(torch.int16), outs[1][0].view(torch.int16))
+    assert torch.equal(idx, outs[1][1]) and torch.equal(gw, outs[1][2])
+    orc, ties, y_ref = oracle_layer(x.cpu(), to_oracle_weights(w), K, True, idx, gw)
+    rep = {}
+    err = check_output(y, y_ref, "bf16", rep)
+    _say(f"  all {T} tokens: rel L2 {err:.3e}, worst row {rep['worst_row']:.3e}, tie tokens {len(ties)}")
+
+
 def test_forward_routing_equals_moe_route():
     T, H, N, I, K = 400, 256, 64, 64, 6
     w = _gen_layer(61, H, N, I, 0, False, "bf16", std=0.05)

@@ -418,3 +418,20 @@ def test_generator_is_deterministic_and_chunk_invariant():
     xs = wl.ar1_hidden_states(7, 1, 20_000, 4, 0.8, torch.float64)[0]
     r1 = float((xs[1:] * xs[:-1]).mean())
     assert abs(r1 - 0.8) < 0.03 and abs(float(xs.var()) - 1) < 0.06
+
+
+# ---- the oracle's C code under the address and undefined-behaviour sanitizers --------------------
+def test_oracle_is_clean_under_sanitizers():
+    """Every oracle function on small inputs (one token, one expert, K = N_r, C < K, repeated ids, empty
+    traces, short histograms, long lags) in a build with -fsanitize=address,undefined: an access past
+    the end of an exactly sized buffer, a signed overflow or a misaligned access ends the run."""
+    import subprocess
+
+    from oracle import build as oracle_build
+
+    exe = oracle_build.build_sanitized()
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1",
+               OMP_NUM_THREADS="4")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    assert r.returncode == 0 and "sanitize_check ok" in r.stdout, r.stdout + r.stderr
+    assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr, r.stderr
