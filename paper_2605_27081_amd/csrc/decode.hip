@@ -1,28 +1,61 @@
-// M = 1 decode: the whole MoE layer for one token per step, weights streamed once from HBM.
+// M = 1 decode with the layers chained: the whole MoE layer for one token per step, weights streamed
+// once from HBM, a layer starting only when the previous one has finished on every compute unit.
 //
 // At one token per step the layer (Sec. 3.1 routing, Sec. 4.1 step 5 expert execution) is a chain
 // of matrix-vector products with about one flop per byte, so the matrix cores are useless and the
 // only roofline is HBM bandwidth: per layer-step the fp32 router matrix (N_r x H) and the three
-// matrices of the K selected experts are read exactly once.  One persistent kernel runs all layers
-// of all steps of a call: one workgroup of 8 wavefronts per compute unit, three phases per
-// layer-step separated by grid-wide barriers (an atomic counter in device memory):
-//   1. router   : every wavefront dots one 256-wide segment of one router row with x; partial
-//                 logits go to device memory;                                       -- barrier --
-//      top-k    : wavefront 0 of every workgroup sums the partials and runs the wavefront-shuffle
-//                 top-k / softmax (identical result everywhere, so no broadcast is needed);
-//   2. gate/up  : the K*I SwiGLU activations are dealt out in contiguous runs, each wavefront
-//                 streams the gate and up rows of its activations with 16-byte coalesced loads;
-//                 h goes to device memory in fp32;                                  -- barrier --
-//   3. down     : every wavefront owns output rows; for each it streams the K down-projection rows
-//                 (already prefetched into registers before the barrier, since the experts are
-//                 known) against h staged in LDS, weighted by the gate weights.     -- barrier --
-// Layers run strictly in order, as a real decoder would.  The routing-trace statistics the paper
-// optimises are updated online in the same kernel (one wavefront, right after the top-k): the
-// adjacent-step overlap |E_t ∩ E_{t-1}| (Eq. 1) and the LRU misses |E_t \ C_t| (App. E.2) for up to
-// four cache capacities at once, from one per-expert "last used" table per layer.
+// matrices of the K selected experts are read exactly once (the B = 1 regime of Sec. 3).  What
+// stands between a kernel and that roofline is the chain of dependencies inside a layer and from
+// one layer to the next, which a decoder cannot reorder:
 //
-// Every wait is bounded: a workgroup that waits longer than the limit raises an abort flag, every
-// other workgroup sees the flag at its next wait, and the whole grid drains.
+//     output of layer l-1 complete  ->  router logits of layer l  ->  top-k  ->  gate/up rows of the
+//     selected experts  ->  SwiGLU activations h complete  ->  down rows  ->  output of layer l
+//
+// Three of these arrows are exchanges between ALL compute units (every logit needs the whole input
+// row, the top-k needs every logit, every output row needs all of h).  One persistent kernel runs
+// all layers of all steps of a call, one workgroup per compute unit, and is organised so that HBM
+// keeps streaming across those exchanges wherever the data dependencies allow it:
+//
+//   * A workgroup has 8 streaming wavefronts and one exchange wavefront.  Vector-memory loads
+//     return to a wavefront in the order it issued them, so a wavefront with 30 KB of weights on
+//     their way cannot see an exchange word before all of them have arrived.  The exchange
+//     wavefront never loads weights: it polls the words the other workgroups publish (agent-scope
+//     loads, which bypass the per-XCD L2), hands the result over through LDS, and meets its
+//     workgroup's streaming wavefronts at LDS-only workgroup barriers (a full barrier would also
+//     wait for every weight load in flight).
+//   * Exchanged values carry the number of the layer-step that produced them as a tag (a partial
+//     logit: fp32 + 32-bit tag; up to three bf16 values of one wavefront + a 16-bit tag in one
+//     8-byte word), so a reader needs no separate flag: it polls until the tags match.  Every
+//     value is published once per XCD (eight copies, one store instruction), and a workgroup polls
+//     its own XCD's copy: 32 readers per copy instead of 256 on the same few memory channels.
+//   * As soon as the selection of a layer is known, a streaming wavefront requests everything it
+//     will need for the rest of the layer: the gate and up rows of its three activations (two
+//     register sets, the third activation's rows requested when the first is reduced), its row of
+//     the down projection from all K experts, and before them its router segment of the NEXT
+//     layer (the only data of the next layer that does not depend on this layer's output).  The
+//     loops are straight-line code with a fixed number of loads, so the compiler's wait counts let
+//     one set be reduced while the later requests stay in flight; the down rows are already on
+//     their way while h is being exchanged.
+//   * A layer ends with every wavefront publishing its output value(s); the exchange wavefronts
+//     gather them all (in a decoder they are the next layer's input row) before the router
+//     products of the next layer are formed from the prefetched router segments.  The same gather
+//     closes a step, so there is no separate grid barrier anywhere.
+//
+// The top-k / softmax of a layer is computed by the exchange wavefront of every workgroup (same
+// result everywhere: K rounds of wavefront maximum, ties to the lower id).  The routing-trace
+// statistics the paper optimises are updated online by the exchange wavefront of the last
+// workgroup right after its top-k: the adjacent-step overlap |E_t n E_{t-1}| (Eq. 1) and the LRU
+// misses |E_t \ C_t| (App. E.2) for up to four cache capacities from one per-expert "last used"
+// table per layer.
+//
+// SwiGLU activations cross workgroups as bf16 (what the batched path stores between its two GEMMs as
+// well), gate/up and down products are packed bf16 dot instructions with fp32 accumulation, the same
+// arithmetic in the same order as the layer-overlapped kernel (decode_pipe.hip), so both orders
+// give the same bits.
+//
+// Every wait is bounded: an exchange wavefront that waits longer than the limit raises the abort
+// word, every other one sees it in its next poll, and each workgroup leaves together at its next
+// barrier.
 #include "common.h"
 #include "decode_common.h"
 #include "topk.h"
@@ -31,16 +64,15 @@ namespace remoe {
 
 namespace {
 
-constexpr int DC_THREADS = DEC_THREADS;
-constexpr int DC_WAVES = DC_THREADS / 64;
-constexpr int DC_SEG = DEC_SEG;
-constexpr int DC_MAX_KI = 6144;      // K * I floats of h staged in LDS (24 KB)
-constexpr int DC_MAX_CAPS = DEC_MAX_CAPS;
-constexpr int DC_MAX_GRID = DEC_MAX_GRID;
-constexpr int DC_MAX_LAYERS = DEC_MAX_LAYERS;
-constexpr int DC_MAX_DCH = 12;       // down-projection chunks per lane per output row (K * I <= 6144)
+constexpr int CH_STREAM = 8;                          // streaming wavefronts per workgroup
+constexpr int CH_WAVES = CH_STREAM + 1;               // + the exchange wavefront
+constexpr int CH_THREADS = CH_WAVES * 64;
+constexpr int CH_MAX_KI = 6144;                       // K * I activations of one layer
+constexpr int CH_ITEMS = 3;                           // activations per streaming wavefront (at most)
+constexpr int CH_MAX_R = 1;                           // router segments per streaming wavefront (at most)
+constexpr int CH_POLL = 32;                           // exchange words per lane and polling pass
 
-struct DecodeArgs {
+struct ChainArgs {
     const void *const *layers;   // [L][4] device pointers: w_router, w_gate, w_up, w_down
     const bf16_t *x;             // [T_total, H]
     int64_t steps_total, step0, n_steps;
@@ -49,7 +81,7 @@ struct DecodeArgs {
     int32_t *out_idx;            // [L, T_total, K]
     float *out_w;                // [L, T_total, K]
     int n_caps;
-    int caps[DC_MAX_CAPS];
+    int caps[DEC_MAX_CAPS];
     unsigned long long expert_bytes;
     uint32_t *lru_state;         // [L, N] last use (global step + 1), 0 = never
     uint8_t *out_overlap;        // [L, T_total]
@@ -57,283 +89,509 @@ struct DecodeArgs {
     unsigned long long *sum_overlap;   // [L]
     unsigned long long *total_miss;    // [n_caps, L]
     unsigned long long *bytes_fetched; // [n_caps, L]
-    unsigned long long *logit_part;   // [N * H / DC_SEG] (phase tag << 32) | float bits
-    float *hbuf;                 // [K * I]
-    uint32_t *bar;               // grid barrier flags, one per workgroup, zero at launch
+    unsigned long long *logit_x;  // [copies] x logit_stride words: (tag << 32) | float bits, one per router segment
+    unsigned long long *h_x;      // [copies] x word_stride words: 3 x bf16 | tag16 << 48, activations
+    unsigned long long *y_x;      // [copies] x word_stride words: 3 x bf16 | tag16 << 48, output values
+    int logit_stride, word_stride;
     uint32_t *abort_flag;        // zero at launch
     unsigned long long spin_limit;   // wall-clock ticks (100 MHz) a single wait may last
 };
 
-template <int XCH>
-__global__ __launch_bounds__(DC_THREADS) void decode_kernel(const DecodeArgs a)
+// Workgroup barrier that orders LDS traffic only (a full __syncthreads would also wait for every
+// weight load in flight, which is exactly what must keep flying).
+#define CH_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+
+// 16-bit tag of a layer-step (never 0, the value of a cleared word).  A word is rewritten every
+// layer-step, so one that is 65535 layer-steps old cannot survive to be mistaken for a new one.
+__device__ __forceinline__ uint32_t ch_tag16(uint32_t tag) { return tag % 65535u + 1u; }
+
+__device__ __forceinline__ unsigned long long ch_poll(const unsigned long long *p)
 {
-    __shared__ float hl[DC_MAX_KI];
-    __shared__ float lz[128];      // logits of the current layer-step
-    __shared__ float lpart[128 * 16];   // their per-segment partial sums (H <= 4096)
-    __shared__ int rank_part[DC_WAVES][128];
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One 8-byte word into every XCD's copy of an exchange array: lane c of the wavefront stores copy c.
+__device__ __forceinline__ void ch_publish(unsigned long long *base, int stride, int copies, int index,
+                                           unsigned long long word, int lane)
+{
+    if (lane < copies)
+        __hip_atomic_store(base + (size_t)lane * stride + index, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Exchange wavefront: polls words [0, n) of `src` until every one carries `tag16` in its top 16 bits,
+// then hands each to `sink(index, word)`.  All polls of a pass of up to 64 x CH_POLL words are in
+// flight together; the pass is repeated until every word is there, the abort word is raised or the
+// wait limit passes.  Returns false when the grid is aborting.
+template <class Sink>
+__device__ __forceinline__ bool ch_gather16(const ChainArgs &a, const unsigned long long *src, int n, uint32_t tag16,
+                                            Sink sink)
+{
+    // (the lane number is taken from a value the optimiser cannot see through, so that the poll addresses
+    // are formed here from one base and constant offsets instead of being kept in registers for the
+    // whole kernel)
+    int lane = threadIdx.x & 63;
+    asm volatile("" : "+v"(lane));
+    for (int base = 0; base < n; base += 64 * CH_POLL) {
+        // Words past n are read as well (the launcher keeps 64 x CH_POLL words readable behind every array)
+        // and simply not looked at: every lane then polls base + lane + 64 k for constant k.  A pass that
+        // finds a word missing is repeated as a whole after a short pause: straight-line code, and with the
+        // wait for the own workgroup in front of it a repeat is the exception.
+        const unsigned long long *p = src + base + lane;
+        unsigned long long w[CH_POLL];
+        unsigned long long t0 = 0;
+        bool timing = false;
+        for (;;) {
+#pragma unroll
+            for (int k = 0; k < CH_POLL; ++k) w[k] = ch_poll(p + k * 64);
+            bool missing = false;
+#pragma unroll
+            for (int k = 0; k < CH_POLL; ++k)
+                missing |= base + k * 64 + lane < n && (uint32_t)(w[k] >> 48) != tag16;
+            if (!__any(missing)) break;
+            if (!timing) { t0 = wall_clock64(); timing = true; }
+            const uint32_t ab = __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (ab || wall_clock64() - t0 > a.spin_limit) {
+                if (!ab) __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                return false;
+            }
+            __builtin_amdgcn_s_sleep(4);
+        }
+#pragma unroll
+        for (int k = 0; k < CH_POLL; ++k) {
+            const int q = base + k * 64 + lane;
+            if (q < n) sink(q, w[k]);
+        }
+    }
+    return true;
+}
+
+// XCH: 16-byte chunks per lane of one hidden row (hidden / 512).  DCH: 16-byte chunks per lane of one
+// down-projection output row over the K selected experts (K * inter / 512, rounded up to a supported
+// count).  RPW: output rows per streaming wavefront.  All three fix the number of loads per unit of
+// work at compile time.
+template <int XCH, int DCH, int RPW>
+__global__ __launch_bounds__(CH_THREADS) void decode_chain_kernel(const ChainArgs a)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t hl[CH_MAX_KI];   // activations of the layer (bf16)
+    __shared__ __attribute__((aligned(16))) bf16_t xs[4096];        // the step's input row
     __shared__ int sel_e[8];
     __shared__ float sel_w[8];
-    __shared__ float sel_z[9];
-    __shared__ int bar_ok;
+    __shared__ int leave_lds;            // set by the exchange wavefront when a wait ran out: the workgroup returns
+    __shared__ uint32_t arrivals;        // publications of this workgroup's streaming wavefronts so far (3 per layer-step each)
+    __shared__ float lp[CH_STREAM];      // router products of this workgroup's streaming wavefronts (one segment each)
+    __shared__ bf16_t ys[CH_STREAM * RPW];   // output values of this workgroup's streaming wavefronts
+    __shared__ unsigned long long wtab[DEC_MAX_LAYERS * 4];   // the launch's weight-pointer table
     __shared__ TraceLds ts;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool exchange = wave == CH_STREAM;
     const int G = gridDim.x;
-    const int W = G * DC_WAVES;                 // wavefronts in the grid
-    const int gw = blockIdx.x * DC_WAVES + wave;  // this wavefront's global index
-    const int H = a.H, N = a.N, I = a.I, K = a.K;
-    const int segs = H / DC_SEG;
+    const int copies = (G % DEC_GROUPS == 0) ? DEC_GROUPS : 1;   // workgroup b runs on XCD b % 8 and polls that copy
+    const int my_copy = blockIdx.x % copies;
+    const int W = G * CH_STREAM;                                   // streaming wavefronts in the grid
+    const int gw = blockIdx.x * CH_STREAM + wave;                  // this streaming wavefront's index
+    const int H = a.H, N = a.N, I = a.I, K = a.K, L = a.n_layers;
+    const int segs = H / DEC_SEG;
     const int KI = K * I;
-    const int items_per_wave = (KI + W - 1) / W;
-    const int rows_per_wave = (H + W - 1) / W;
-    const int dchunks = KI / 8;                 // 16-byte chunks of one output row's K down rows
+    const int n_items1 = N * segs;                  // router work items: (expert, 256-wide segment)
+    const int ipw = (KI + W - 1) / W;               // activations per streaming wavefront (<= CH_ITEMS)
+    const int wpw = (ipw + 2) / 3;                  // exchange words per streaming wavefront
+    const int n_hwords = W * wpw;
+    constexpr int YW = (CH_STREAM * RPW + 2) / 3;   // exchange words of a workgroup's output values (3 per word)
+    const int n_ywords = G * YW;
+    const int lgs = segs < CH_STREAM ? segs : CH_STREAM;   // router segments summed into one exchange word
+    const int lwpe = segs / lgs;                    // exchange words per expert (1, or 2 when hidden = 4096)
+    const int dchunks = KI / 8;
     const int chunks_per_row = I / 8;
-    const bool stats_wave = blockIdx.x == G - 1 && wave == DC_WAVES - 1;
-    const int n_items1 = N * segs;              // router work items: (expert, 256-wide segment)
-    uint32_t phase = 0;
+    const bool stats_wave = blockIdx.x == G - 1 && exchange;
+    const unsigned long long *const my_logits = a.logit_x + (size_t)my_copy * a.logit_stride;
+    const unsigned long long *const my_h = a.h_x + (size_t)my_copy * a.word_stride;
+    const unsigned long long *const my_y = a.y_x + (size_t)my_copy * a.word_stride;
+    // chunk q of a wavefront's down-row work is chunk q % chunks_per_row of expert slot q / chunks_per_row;
+    // the quotient by multiplication (exact for q < 2^16, chunks_per_row <= 2^16)
+    const uint32_t cpr_magic = (uint32_t)((0x100000000ull + (unsigned)chunks_per_row - 1) / (unsigned)chunks_per_row);
+#define CH_SLOT_OF(q) ((int)__umulhi((uint32_t)(q), cpr_magic))
 
-    if (blockIdx.x == G - 1) {                  // trace state -> LDS
-        for (int q = tid; q < a.n_layers * 128; q += DC_THREADS) {
+    if (blockIdx.x == G - 1) {                      // trace state -> LDS
+        for (int q = tid; q < L * 128; q += CH_THREADS) {
             const int l = q >> 7, e = q & 127;
             ts.last[l][e] = (e < N) ? a.lru_state[l * N + e] : 0u;
         }
-        for (int q = tid; q < a.n_layers; q += DC_THREADS) {
+        for (int q = tid; q < L; q += CH_THREADS) {
             ts.sum_ov[q] = a.sum_overlap[q];
-            for (int c = 0; c < a.n_caps; ++c) ts.tot[c][q] = a.total_miss[c * a.n_layers + q];
+            for (int c = 0; c < a.n_caps; ++c) ts.tot[c][q] = a.total_miss[c * L + q];
         }
     }
+    if (tid == 0) { leave_lds = 0; arrivals = 0u; }
+    // the weight pointers of all layers -> LDS (a read from there costs a tenth of a scalar load from memory,
+    // and four of those in a row stood between the selection and the first weight request)
+    for (int q = tid; q < L * 4; q += CH_THREADS) wtab[q] = reinterpret_cast<const unsigned long long *>(a.layers)[q];
     __syncthreads();
+#define CH_WPTR(idx) reinterpret_cast<const void *>(((unsigned long long)__builtin_amdgcn_readfirstlane((int)(wtab[idx] >> 32)) << 32) | (unsigned)__builtin_amdgcn_readfirstlane((int)(uint32_t)wtab[idx]))
+    uint32_t arrivals_due = 0;           // exchange wavefront: the count `arrivals` reaches with the next publication round
 
-    // the router row segment of this wavefront's first work item of the NEXT layer is fetched ahead
-    floatx4_t wr_pf = {0.f, 0.f, 0.f, 0.f};
-    const int e1 = gw / segs, k1 = (gw - e1 * segs) * DC_SEG + lane * 4;
-    if (gw < n_items1)
-        wr_pf = load_global<floatx4_t>(static_cast<const float *>(table_ptr(a.layers, 0)) + (int64_t)e1 * H + k1);
+    // ---- per-wavefront constants of the streaming wavefronts ----------------------------------------
+    const int item0 = gw * ipw;                     // first activation (expert slot j = item / I, index i = item % I)
+    const int row0 = gw * RPW;                      // first output row
+
+    // router segments of the layer-step that comes next, requested a layer ahead (streaming wavefronts)
+    floatx4_t wr[CH_MAX_R];
+#pragma unroll
+    for (int r = 0; r < CH_MAX_R; ++r) wr[r] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#define CH_LOAD_ROUTER(layer_)                                                                        \
+    {                                                                                                 \
+        const float *w_router_ = static_cast<const float *>(CH_WPTR((layer_) * 4));                   \
+        _Pragma("unroll") for (int r = 0; r < CH_MAX_R; ++r) {                                         \
+            const int item_ = gw + r * W;                                                             \
+            if (item_ < n_items1) {                                                                   \
+                const int e_ = item_ / segs;                                                          \
+                const uint32_t off_ = (uint32_t)(e_ * H + (item_ - e_ * segs) * DEC_SEG) * 4u;        \
+                wr[r] = load_global<floatx4_t>(reinterpret_cast<const char *>(w_router_) + off_ + (uint32_t)lane * 16u); \
+            }                                                                                         \
+        }                                                                                             \
+    }
+    if (!exchange) CH_LOAD_ROUTER(0)
+
+    // A streaming wavefront has published its words of a round (router products, activations or output
+    // values): one LDS increment.  The exchange wavefront polls the other workgroups' words only once its
+    // own workgroup's eight have published: compute units run a layer-step in near lockstep, so until
+    // then most words are missing everywhere, and 256 wavefronts re-polling them would load the same
+    // memory channels the weights stream through.
+#define CH_ARRIVE() { if (lane == 0) __hip_atomic_fetch_add(&arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+#define CH_AWAIT_OWN(ok_)                                                                             \
+    {                                                                                                 \
+        arrivals_due += CH_STREAM;                                                                    \
+        unsigned long long t0_ = 0;                                                                   \
+        bool timing_ = false;                                                                         \
+        while ((int32_t)(__hip_atomic_load(&arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - arrivals_due) < 0) { \
+            __builtin_amdgcn_s_sleep(2);                                                              \
+            if (!timing_) { t0_ = wall_clock64(); timing_ = true; }                                   \
+            else if (wall_clock64() - t0_ > a.spin_limit) {                                           \
+                __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);     \
+                ok_ = false;                                                                          \
+                break;                                                                                \
+            }                                                                                         \
+        }                                                                                             \
+    }
 
 #pragma unroll 1
     for (int64_t s = 0; s < a.n_steps; ++s) {
         const int64_t g = a.step0 + s;
         const bf16_t *xg = a.x + g * H;
-#pragma unroll 1
-        for (int layer = 0; layer < a.n_layers; ++layer) {
-            const float *w_router = static_cast<const float *>(table_ptr(a.layers, layer * 4 + 0));
-            const bf16_t *w_gate = static_cast<const bf16_t *>(table_ptr(a.layers, layer * 4 + 1));
-            const bf16_t *w_up = static_cast<const bf16_t *>(table_ptr(a.layers, layer * 4 + 2));
-            const bf16_t *w_down = static_cast<const bf16_t *>(table_ptr(a.layers, layer * 4 + 3));
+        // The step's input row -> LDS.  Its last readers (the gate / up products of the previous step's last
+        // layer) are behind that layer's activation barrier, which every wavefront has passed.
+        for (int k = tid; k < H / 8; k += CH_THREADS)
+            *reinterpret_cast<u32x4_t *>(&xs[k * 8]) = *reinterpret_cast<const u32x4_t *>(xg + k * 8);
 
-            // ---- phase 1: partial router logits --------------------------------------------------
 #pragma unroll 1
-            for (int item = gw; item < n_items1; item += W) {
-                const int e = item / segs, sg = item - e * segs;
-                const int k0 = sg * DC_SEG + lane * 4;
-                floatx4_t wv = wr_pf;
-                if (item != gw) wv = load_global<floatx4_t>(w_router + (int64_t)e * H + k0);
-                const uint2 xb = *reinterpret_cast<const uint2 *>(xg + k0);
-                float p = wv.x * __uint_as_float(xb.x << 16);
-                p = fmaf(wv.y, __uint_as_float(xb.x & 0xFFFF0000u), p);
-                p = fmaf(wv.z, __uint_as_float(xb.y << 16), p);
-                p = fmaf(wv.w, __uint_as_float(xb.y & 0xFFFF0000u), p);
-                p = wave_sum(p);
-                if (lane == 0) put_tagged(&a.logit_part[item], p, phase + 1);
-            }
-            // this lane's share of x, widened once per layer-step: chunk c covers k = (c*64 + lane)*8 ..
-            float xr[XCH][8];
+        for (int layer = 0; layer < L; ++layer) {
+            const uint32_t n_ls = (uint32_t)(g * L + layer);      // number of this layer-step in the run
+            const uint32_t tag = n_ls + 1u;                       // 32-bit tag of its partial logits
+            const uint32_t t16 = ch_tag16(tag);                   // 16-bit tag of its activations and outputs
+            const bool first_of_launch = s == 0 && layer == 0;
+
+            // ---- 1. the previous layer-step is complete everywhere: the exchange wavefront gathers every
+            // output value of it (a decoder's next input row) ---------------------------------------------
+            if (exchange && !first_of_launch) {
+                const uint32_t prev16 = ch_tag16(tag - 1u);
+                bool ok = true;
+                CH_AWAIT_OWN(ok)
+                // this workgroup's output values of the previous layer-step (LDS) -> YW words in every copy
+                if (ok && lane < YW * copies) {
+                    const int k = lane / copies, cpy = lane - k * copies;
+                    unsigned long long word = (unsigned long long)prev16 << 48;
 #pragma unroll
-            for (int c = 0; c < XCH; ++c) {
-                const u32x4_t xb = *reinterpret_cast<const u32x4_t *>(xg + (c * 64 + lane) * 8);
-                xr[c][0] = __uint_as_float(xb.x << 16); xr[c][1] = __uint_as_float(xb.x & 0xFFFF0000u);
-                xr[c][2] = __uint_as_float(xb.y << 16); xr[c][3] = __uint_as_float(xb.y & 0xFFFF0000u);
-                xr[c][4] = __uint_as_float(xb.z << 16); xr[c][5] = __uint_as_float(xb.z & 0xFFFF0000u);
-                xr[c][6] = __uint_as_float(xb.w << 16); xr[c][7] = __uint_as_float(xb.w & 0xFFFF0000u);
+                    for (int v = 0; v < 3; ++v)
+                        if (3 * k + v < CH_STREAM * RPW) word |= (unsigned long long)ys[3 * k + v] << (16 * v);
+                    __hip_atomic_store(a.y_x + (size_t)cpy * a.word_stride + blockIdx.x * YW + k, word, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (ok) ok = ch_gather16(a, my_y, n_ywords, prev16, [](int, unsigned long long) {});
+                if (!ok && lane == 0) leave_lds = 1;
             }
-            // ---- first grid-wide rendezvous: the partial logits carry the phase number as a tag, so
-            // polling for them IS the barrier (one memory round trip once the last one is written) ------
-            ++phase;
-            if (!gather_tagged(a, lpart, n_items1, phase, &bar_ok)) return;
+            CH_LDS_BARRIER();
+            if (leave_lds) return;
 
-            // ---- top-k and softmax by rank counting (every workgroup, same result everywhere) -------
-            // Every wavefront sums all N logits (cheap) and counts, for its 1/8 of the experts q, how many
-            // beat expert e (larger logit, or equal logit and lower id); ranks 0..K-1 are the selection,
-            // already in descending-logit order.
-            {
+            // ---- 2. router: the streaming wavefronts dot their prefetched segments with the input row -------
+            if (!exchange) {
+#pragma unroll
+                for (int r = 0; r < CH_MAX_R; ++r) {
+                    const int item = gw + r * W;
+                    if (item < n_items1) {
+                        const int e = item / segs;
+                        const int k0 = (item - e * segs) * DEC_SEG + lane * 4;
+                        const uint2 xb = *reinterpret_cast<const uint2 *>(&xs[k0]);
+                        float p = wr[r].x * __uint_as_float(xb.x << 16);
+                        p = fmaf(wr[r].y, __uint_as_float(xb.x & 0xFFFF0000u), p);
+                        p = fmaf(wr[r].z, __uint_as_float(xb.y << 16), p);
+                        p = fmaf(wr[r].w, __uint_as_float(xb.y & 0xFFFF0000u), p);
+                        p = wave_sum(p);
+                        if (lane == 0) lp[wave] = p;
+                    }
+                }
+                CH_ARRIVE()
+            } else {
+                // ---- 3. the exchange wavefront gathers the partial logits (lane l: experts l and l + 64, whose
+                // segments are adjacent words), sums them in segment order, ranks them: K rounds of wavefront
+                // maximum, ties to the lower id; softmax weights --------------------------------------------------
                 const float NEG_INF = -__builtin_inff();
                 float v0 = NEG_INF, v1 = NEG_INF;
-                if (lane < N) {
-                    v0 = 0.f;
-                    for (int q = 0; q < segs; ++q) v0 += lpart[lane * segs + q];
-                }
-                if (lane + 64 < N) {
-                    v1 = 0.f;
-                    for (int q = 0; q < segs; ++q) v1 += lpart[(lane + 64) * segs + q];
-                }
-                if (wave == 0) { lz[lane] = v0; lz[lane + 64] = v1; }
-                // this wavefront compares against experts q = wave, wave + 8, ...; the logit of q sits in
-                // lane q & 63 (v0 or v1), so it is fetched with a lane read instead of LDS
-                int r0 = 0, r1 = 0;
-                for (int q = wave; q < N; q += DC_WAVES) {
-                    const float zq = __shfl((q < 64) ? v0 : v1, q & 63, 64);
-                    r0 += (zq > v0) || (zq == v0 && q < lane);
-                    r1 += (zq > v1) || (zq == v1 && q < lane + 64);
-                }
-                rank_part[wave][lane] = r0;
-                rank_part[wave][lane + 64] = r1;
-            }
-            __syncthreads();
-            if (wave == 0) {
-                const float v0 = lz[lane], v1 = lz[lane + 64];
-                int r0 = 0, r1 = 0;
-#pragma unroll
-                for (int w = 0; w < DC_WAVES; ++w) { r0 += rank_part[w][lane]; r1 += rank_part[w][lane + 64]; }
-                if (lane < N && r0 <= K) { sel_z[r0] = v0; if (r0 < K) sel_e[r0] = lane; }
-                if (lane + 64 < N && r1 <= K) { sel_z[r1] = v1; if (r1 < K) sel_e[r1] = lane + 64; }
-                const float zmax = sel_z[0];
-                const float den = wave_sum(((lane < N) ? expf(v0 - zmax) : 0.f) + ((lane + 64 < N) ? expf(v1 - zmax) : 0.f));
-                const float my_p = (lane < K) ? expf(sel_z[lane] - zmax) : 0.f;
-                float wgt = my_p / den;
-                if (a.renorm) wgt = my_p / wave_sum(my_p);
-                if (lane < K) {
-                    sel_w[lane] = wgt;
-                    if (blockIdx.x == 0) {
-                        const int64_t o = ((int64_t)layer * a.steps_total + g) * K + lane;
-                        a.out_idx[o] = sel_e[lane];
-                        a.out_w[o] = wgt;
+                bool ok = true;
+                CH_AWAIT_OWN(ok)
+                // This workgroup's eight router products are in LDS (streaming wavefront w holds item b * 8 + w,
+                // items of one expert are adjacent): sum each run of `lgs` of them in segment order and publish
+                // one word per run -- an eighth of the words every workgroup would otherwise have to poll.
+                if (ok && blockIdx.x * CH_STREAM < n_items1) {
+                    const int runs = CH_STREAM / lgs;
+                    if (lane < runs * copies) {
+                        const int run = lane / copies, cpy = lane - run * copies;
+                        float v = 0.f;
+                        for (int q = 0; q < lgs; ++q) v += lp[run * lgs + q];
+                        __hip_atomic_store(a.logit_x + (size_t)cpy * a.logit_stride + blockIdx.x * runs + run,
+                                           ((unsigned long long)tag << 32) | __float_as_uint(v), __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
                     }
                 }
-            }
-            __syncthreads();
-
-            // ---- phase 2: gate / up rows of the selected experts, SwiGLU -----------------------------
-            // Row bases are wave-uniform (scalar registers); a lane adds its own 32-bit offset.  Two
-            // register sets roll over the wavefront's activations (the loads of the next one or two are
-            // in flight while one is reduced), and the down-projection rows of phase 3 are requested
-            // right behind the last of them, so HBM keeps streaming across the coming barrier.
-            u32x4_t dv[DC_MAX_DCH];
-            const int row_first = gw * rows_per_wave;
-            const char *wd_bytes = reinterpret_cast<const char *>(w_down);
-#define DC_ISSUE_DOWN()                                                                              \
-    _Pragma("unroll") for (int c = 0; c < DC_MAX_DCH; ++c) {                                          \
-        const int q_ = c * 64 + lane;                                                                \
-        if (q_ < dchunks && row_first < H) {                                                         \
-            const int j_ = q_ / chunks_per_row, pos_ = (q_ - j_ * chunks_per_row) * 8;               \
-            const uint32_t off_ = (uint32_t)((((int64_t)sel_e[j_] * H + row_first) * I + pos_) * 2); \
-            dv[c] = load_global_stream<u32x4_t>(wd_bytes + off_);                             \
-        }                                                                                            \
-    }
-            {
-                const int item0 = gw * items_per_wave;
-                int nit = KI - item0;
-                if (nit > items_per_wave) nit = items_per_wave;
-                const int loff = lane * 8;
-                u32x4_t gA[XCH], uA[XCH], gB[XCH], uB[XCH];
-#define DC_LOAD_ITEM(gv, uv, it)                                                                     \
-    {                                                                                                \
-        const int item_ = item0 + (it);                                                              \
-        const int j_ = item_ / I, i_ = item_ - j_ * I;                                               \
-        const int e_ = __builtin_amdgcn_readfirstlane(sel_e[j_]);                                    \
-        const bf16_t *gp_ = w_gate + ((int64_t)e_ * I + i_) * H;                                     \
-        const bf16_t *up_ = w_up + ((int64_t)e_ * I + i_) * H;                                       \
-        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                             \
-            gv[c] = load_global_stream<u32x4_t>(gp_ + loff + c * 512);                        \
-            uv[c] = load_global_stream<u32x4_t>(up_ + loff + c * 512);                        \
-        }                                                                                            \
-    }
-#define DC_REDUCE_ITEM(gv, uv, it)                                                                   \
-    {                                                                                                \
-        float gs_ = 0.f, us_ = 0.f;                                                                  \
-        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                             \
-            gs_ = dot8(gv[c], xr[c], gs_);                                                           \
-            us_ = dot8(uv[c], xr[c], us_);                                                           \
-        }                                                                                            \
-        gs_ = wave_sum(gs_);                                                                         \
-        us_ = wave_sum(us_);                                                                         \
-        if (lane == 0) put_shared(&a.hbuf[item0 + (it)], gs_ / (1.0f + expf(-gs_)) * us_);           \
-    }
-                bool down_issued = false;
-                if (nit > 0) DC_LOAD_ITEM(gA, uA, 0)
-                if (nit > 1) DC_LOAD_ITEM(gB, uB, 1)
-                if (nit <= 2) { DC_ISSUE_DOWN() down_issued = true; }
-                // the statistics ride on the latency of the loads just issued
-                if (stats_wave) online_trace_stats(a, ts, layer, g, sel_e, lane);
-#pragma unroll 1
-                for (int it = 0; it < nit; it += 2) {
-                    DC_REDUCE_ITEM(gA, uA, it)
-                    if (it + 2 < nit) DC_LOAD_ITEM(gA, uA, it + 2)
-                    if (!down_issued && it + 3 >= nit) { DC_ISSUE_DOWN() down_issued = true; }
-                    if (it + 1 < nit) {
-                        DC_REDUCE_ITEM(gB, uB, it + 1)
-                        if (it + 3 < nit) DC_LOAD_ITEM(gB, uB, it + 3)
-                    }
-                }
-            }
-            if (!grid_barrier(a, ++phase, &bar_ok)) return;
-
-            // ---- phase 3: down projection; h is staged in LDS already multiplied by the gate weight ----
-            for (int q0 = tid; q0 < KI; q0 += DC_THREADS * 4) {
-                float hv[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {          // four loads in flight per thread
-                    const int q = q0 + u * DC_THREADS;
-                    hv[u] = (q < KI) ? get_shared(&a.hbuf[q]) : 0.f;
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int q = q0 + u * DC_THREADS;
-                    if (q < KI) hl[q] = hv[u] * sel_w[q / I];
-                }
-            }
-            // router row segment of the next layer-step, in flight across the last barrier
-            {
-                int nl = layer + 1;
-                if (nl == a.n_layers) nl = 0;
-                if (gw < n_items1)
-                    wr_pf = load_global<floatx4_t>(static_cast<const float *>(table_ptr(a.layers, nl * 4)) + (int64_t)e1 * H + k1);
-            }
-            __syncthreads();
-#pragma unroll 1
-            for (int rw = 0; rw < rows_per_wave; ++rw) {
-                const int o = row_first + rw;
-                if (o >= H) break;
-                float acc = 0.f;
-#pragma unroll
-                for (int c = 0; c < DC_MAX_DCH; ++c) {
-                    const int q = c * 64 + lane;
-                    if (q < dchunks) {
-                        u32x4_t wv = dv[c];
-                        if (rw > 0) {   // further rows of this wavefront are fetched on the spot
-                            const int j = q / chunks_per_row, pos = (q - j * chunks_per_row) * 8;
-                            const uint32_t off = (uint32_t)((((int64_t)sel_e[j] * H + o) * I + pos) * 2);
-                            wv = load_global_stream<u32x4_t>(wd_bytes + off);
+                if (ok) {
+                    int lane_p = threadIdx.x & 63;
+                    asm volatile("" : "+v"(lane_p));               // addresses formed here, not kept across the kernel
+                    const unsigned long long *p0 = my_logits + lane_p * lwpe;      // expert lane: words p0[0 .. lwpe)
+                    const unsigned long long *p1 = p0 + 64 * lwpe;                  // expert lane + 64
+                    const bool has0 = lane_p < N, has1 = lane_p + 64 < N;
+                    unsigned long long pw0[2], pw1[2];
+                    unsigned long long t0 = 0;
+                    bool timing = false;
+                    for (;;) {                 // the whole pass is repeated when a word is missing, as in ch_gather16
+                        pw0[0] = pw0[1] = pw1[0] = pw1[1] = 0ull;
+                        if (has0) {
+                            pw0[0] = ch_poll(p0);
+                            if (lwpe > 1) pw0[1] = ch_poll(p0 + 1);
                         }
-                        acc = dot8(wv, &hl[q * 8], acc);
+                        if (has1) {
+                            pw1[0] = ch_poll(p1);
+                            if (lwpe > 1) pw1[1] = ch_poll(p1 + 1);
+                        }
+                        bool missing = false;
+#pragma unroll
+                        for (int q = 0; q < 2; ++q) {
+                            missing |= has0 && q < lwpe && (uint32_t)(pw0[q] >> 32) != tag;
+                            missing |= has1 && q < lwpe && (uint32_t)(pw1[q] >> 32) != tag;
+                        }
+                        if (!__any(missing)) break;
+                        if (!timing) { t0 = wall_clock64(); timing = true; }
+                        const uint32_t ab = __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (ab || wall_clock64() - t0 > a.spin_limit) {
+                            if (!ab) __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            ok = false;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(4);
+                    }
+                    if (has0) {
+                        v0 = __uint_as_float((uint32_t)pw0[0]);
+                        if (lwpe > 1) v0 += __uint_as_float((uint32_t)pw0[1]);
+                    }
+                    if (has1) {
+                        v1 = __uint_as_float((uint32_t)pw1[0]);
+                        if (lwpe > 1) v1 += __uint_as_float((uint32_t)pw1[1]);
                     }
                 }
-                acc = wave_sum(acc);
-                if (lane == 0) a.y[(g * a.n_layers + layer) * H + o] = f32_to_bf16(acc);
+                if (!ok) {
+                    if (lane == 0) leave_lds = 1;
+                } else {
+                    float m0 = v0, m1 = v1, my_z = NEG_INF, zmax = 0.f;
+                    int my_e = 0;
+                    for (int j = 0; j < K; ++j) {
+                        const float m = wave_max(fmaxf(m0, m1));
+                        const unsigned long long b0 = __ballot(m0 == m), b1 = __ballot(m1 == m);
+                        const int e = b0 ? __ffsll((long long)b0) - 1 : 63 + __ffsll((long long)b1);
+                        if (j == 0) zmax = m;
+                        if (lane == j) { my_z = m; my_e = e; }
+                        if (e == lane) m0 = NEG_INF;
+                        if (e == lane + 64) m1 = NEG_INF;
+                    }
+                    const float den = wave_sum(((lane < N) ? expf(v0 - zmax) : 0.f) + ((lane + 64 < N) ? expf(v1 - zmax) : 0.f));
+                    const float my_p = (lane < K) ? expf(my_z - zmax) : 0.f;
+                    float wgt = my_p / den;
+                    if (a.renorm) wgt = my_p / wave_sum(my_p);
+                    if (lane < K) {
+                        sel_e[lane] = my_e;
+                        sel_w[lane] = wgt;
+                        if (blockIdx.x == 0) {
+                            const int64_t o = ((int64_t)layer * a.steps_total + g) * K + lane;
+                            a.out_idx[o] = my_e;
+                            a.out_w[o] = wgt;
+                        }
+                    }
+                }
             }
-            if (!grid_barrier(a, ++phase, &bar_ok)) return;
+            CH_LDS_BARRIER();                   // the selection is in LDS
+            if (leave_lds) return;
+
+            if (!exchange) {
+                // ---- 4. the gate and up rows of this wavefront's three activations are requested at once ------
+                const bf16_t *w_gate = static_cast<const bf16_t *>(CH_WPTR(layer * 4 + 1));
+                const bf16_t *w_up = static_cast<const bf16_t *>(CH_WPTR(layer * 4 + 2));
+                const char *w_down = static_cast<const char *>(CH_WPTR(layer * 4 + 3));
+                // the next layer-step's router segment first (it is consumed last, and every request that follows
+                // is unconditional, which keeps the compiler's wait counts exact)
+                {
+                    int nl = layer + 1;
+                    if (nl == L) nl = 0;
+                    CH_LOAD_ROUTER(nl)
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                u32x4_t gA[XCH], uA[XCH], gB[XCH], uB[XCH], gC[XCH], uC[XCH], dv[DCH];
+                // gate and up rows of activation number it_ of this wavefront (past the end: the layer's last
+                // activation again, its value is not published)
+#define CH_LOAD_ITEM(gv, uv, it_)                                                                     \
+    {                                                                                                 \
+        int item_ = item0 + (it_);                                                                    \
+        if (item_ >= KI) item_ = KI - 1;                                                              \
+        const int j_ = item_ / I, i_ = item_ - j_ * I;                                                \
+        const int e_ = __builtin_amdgcn_readfirstlane(sel_e[j_]);                                     \
+        const bf16_t *gp_ = w_gate + ((int64_t)e_ * I + i_) * H;                                      \
+        const bf16_t *up_ = w_up + ((int64_t)e_ * I + i_) * H;                                        \
+        int loff_ = (threadIdx.x & 63) * 8;                                                           \
+        asm volatile("" : "+v"(loff_));                                                               \
+        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
+            gv[c] = load_global_stream<u32x4_t>(gp_ + loff_ + c * 512);                               \
+            uv[c] = load_global_stream<u32x4_t>(up_ + loff_ + c * 512);                               \
+        }                                                                                             \
+    }
+                // chunks [c0, c1) of output row `row` (all K experts' pieces of it); a row past the end reads the
+                // tensor's first bytes
+#define CH_LOAD_DROW(row, c0, c1)                                                                     \
+    {                                                                                                 \
+        int lane_ = threadIdx.x & 63;                                                                 \
+        asm volatile("" : "+v"(lane_));   /* offsets are recomputed here, not kept in registers */     \
+        _Pragma("unroll") for (int c = (c0); c < (c1); ++c) {                                          \
+            int q_ = c * 64 + lane_;                          /* past the end: the last chunk again, */ \
+            if (q_ >= dchunks) q_ = dchunks - 1;              /* weighted 0 when the row is reduced  */ \
+            const int j_ = CH_SLOT_OF(q_);                                                            \
+            uint32_t off_ = (uint32_t)(((int64_t)sel_e[j_] * H + (row)) * I * 2) + (uint32_t)(q_ - j_ * chunks_per_row) * 16u; \
+            if ((row) >= H) off_ = 0;                                                                 \
+            dv[c] = load_global_stream<u32x4_t>(w_down + off_);                                       \
+        }                                                                                             \
+    }
+                const unsigned long long h_tag = (unsigned long long)t16 << 48;
+                unsigned long long h_word = h_tag;
+#define CH_REDUCE_ITEM(gv, uv, u)                                                                     \
+    {                                                                                                 \
+        int lane_ = threadIdx.x & 63;                                                                 \
+        asm volatile("" : "+v"(lane_));                                                               \
+        float gs_ = 0.f, us_ = 0.f;                                                                   \
+        _Pragma("unroll") for (int c = 0; c < XCH; ++c) {                                              \
+            const u32x4_t xq_ = *reinterpret_cast<const u32x4_t *>(&xs[(c * 64 + lane_) * 8]);        \
+            gs_ = dot8_bf16(gv[c], xq_, gs_);                                                         \
+            us_ = dot8_bf16(uv[c], xq_, us_);                                                         \
+        }                                                                                             \
+        gs_ = wave_sum(gs_);                                                                          \
+        us_ = wave_sum(us_);                                                                          \
+        h_word |= (unsigned long long)f32_to_bf16(gs_ / (1.0f + expf(-gs_)) * us_) << (16 * (u));     \
+    }
+                static_assert(CH_ITEMS == 3, "the sequence below is written out for three activations per wavefront");
+                // All gate / up rows go out before any row of the down projection, on every wavefront: the memory
+                // system serves requests roughly in the order they were made, and a down row requested early by a
+                // wavefront that is ahead would be served before gate / up rows of one that is behind, whose
+                // activation the whole grid waits for.
+                CH_LOAD_ITEM(gA, uA, 0)
+                __builtin_amdgcn_sched_barrier(0);
+                CH_LOAD_ITEM(gB, uB, 1)
+                __builtin_amdgcn_sched_barrier(0);
+                CH_LOAD_ITEM(gC, uC, 2)
+                __builtin_amdgcn_sched_barrier(0);
+                CH_REDUCE_ITEM(gA, uA, 0)
+                __builtin_amdgcn_sched_barrier(0);
+                CH_REDUCE_ITEM(gB, uB, 1)
+                __builtin_amdgcn_sched_barrier(0);
+                CH_REDUCE_ITEM(gC, uC, 2)
+                __builtin_amdgcn_sched_barrier(0);
+                // one word per wavefront (ipw <= 3): activations item0 .. item0 + ipw - 1 (the reader takes no more;
+                // a wavefront without activations of its own still publishes, its tag is waited for)
+                ch_publish(a.h_x, a.word_stride, copies, gw * wpw, h_word, lane);
+                CH_ARRIVE()
+                __builtin_amdgcn_sched_barrier(0);
+                // the down-projection row streams in while the activations are exchanged
+                CH_LOAD_DROW(row0, 0, DCH)
+                __builtin_amdgcn_sched_barrier(0);
+
+                // ---- 6. activations of the whole layer are in LDS (exchange wavefront): down projection ----------
+                CH_LDS_BARRIER();
+                if (leave_lds) return;
+#pragma unroll
+                for (int rw = 0; rw < RPW; ++rw) {
+                    const int o = row0 + rw;
+                    int lane_d = threadIdx.x & 63;
+                    asm volatile("" : "+v"(lane_d));       // (recomputed per row, not kept in registers across the layer)
+                    float acc = 0.f;
+#pragma unroll
+                    for (int c = 0; c < DCH; ++c) {
+                        const int q = c * 64 + lane_d;
+                        const int qc = q < dchunks ? q : dchunks - 1;
+                        const u32x4_t hq = *reinterpret_cast<const u32x4_t *>(&hl[qc * 8]);
+                        const float w_ = q < dchunks ? sel_w[CH_SLOT_OF(qc)] : 0.f;
+                        acc = fmaf(w_, dot8_bf16(dv[c], hq, 0.f), acc);
+                    }
+                    if (rw + 1 < RPW) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        CH_LOAD_DROW(o + 1, 0, DCH)
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    acc = wave_sum(acc);
+                    const bf16_t yb = f32_to_bf16(acc);
+                    if (lane == 0) {
+                        if (o < H) a.y[(g * L + layer) * H + o] = yb;
+                        ys[wave * RPW + rw] = yb;
+                    }
+                }
+                CH_ARRIVE()
+            } else {
+                // ---- 5. exchange wavefront: statistics of this layer-step (one wavefront of the grid), then the
+                // activations of every streaming wavefront -> LDS ------------------------------------------------
+                if (stats_wave) online_trace_stats(a, ts, layer, g, sel_e, lane);
+                bool ok = true;
+                CH_AWAIT_OWN(ok)
+                if (ok) ok = ch_gather16(a, my_h, n_hwords, t16, [&](int u, unsigned long long word) {
+                    const int wv = u / wpw, kk = u - wv * wpw;
+                    const int i0 = wv * ipw + 3 * kk;          // first activation in the word
+                    int nv = ipw - 3 * kk;                     // how many it holds
+                    if (nv > 3) nv = 3;
+                    if (nv > KI - i0) nv = KI - i0;
+                    if (nv > 0) hl[i0] = (bf16_t)word;
+                    if (nv > 1) hl[i0 + 1] = (bf16_t)(word >> 16);
+                    if (nv > 2) hl[i0 + 2] = (bf16_t)(word >> 32);
+                });
+                if (!ok && lane == 0) leave_lds = 1;
+                CH_LDS_BARRIER();
+                if (leave_lds) return;
+            }
         }
     }
 
+    // the last layer-step is complete everywhere before the kernel ends (the outputs are the caller's
+    // once the stream reaches the end of the call anyway; this keeps every workgroup's exit behind the
+    // last use of the exchange words)
     if (blockIdx.x == G - 1) {                  // trace state back to device memory
         __syncthreads();
-        for (int q = tid; q < a.n_layers * 128; q += DC_THREADS) {
+        for (int q = tid; q < L * 128; q += CH_THREADS) {
             const int l = q >> 7, e = q & 127;
             if (e < N) a.lru_state[l * N + e] = ts.last[l][e];
         }
-        for (int q = tid; q < a.n_layers; q += DC_THREADS) {
+        for (int q = tid; q < L; q += CH_THREADS) {
             a.sum_overlap[q] = ts.sum_ov[q];
             for (int c = 0; c < a.n_caps; ++c) {
-                a.total_miss[c * a.n_layers + q] = ts.tot[c][q];
-                a.bytes_fetched[c * a.n_layers + q] = ts.tot[c][q] * a.expert_bytes;
+                a.total_miss[c * L + q] = ts.tot[c][q];
+                a.bytes_fetched[c * L + q] = ts.tot[c][q] * a.expert_bytes;
             }
         }
     }
 }
 
-__global__ void decode_clear_flags(uint32_t *bar, int n, uint32_t *abort_flag, unsigned long long *tagged, int n_tagged)
+__global__ void decode_chain_clear(uint32_t *abort_flag, unsigned long long *tagged, int n_tagged)
 {
-    for (int q = threadIdx.x; q < n; q += blockDim.x) bar[q] = 0u;
-    for (int q = threadIdx.x; q < n_tagged; q += blockDim.x) tagged[q] = 0ull;   // tag 0 = no phase
+    for (int q = threadIdx.x; q < n_tagged; q += blockDim.x) tagged[q] = 0ull;   // tag 0 = no layer-step
     if (threadIdx.x == 0) *abort_flag = 0u;
 }
 
@@ -345,24 +603,44 @@ remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream)
 {
     if (d.H != 512 && d.H != 1024 && d.H != 2048 && d.H != 4096)
         return fail(REMOE_E_UNSUPPORTED, "decode supports hidden in {512, 1024, 2048, 4096} (got %d)", d.H);
-    if (d.I % 8 != 0 || d.K * d.I > DC_MAX_KI)
-        return fail(REMOE_E_UNSUPPORTED, "decode needs inter %% 8 == 0 and top_k * inter <= %d", DC_MAX_KI);
-    if (d.n_layers > DC_MAX_LAYERS)
-        return fail(REMOE_E_UNSUPPORTED, "decode keeps the trace state of at most %d layers (got %d)", DC_MAX_LAYERS, d.n_layers);
-    if (d.n_caps < 0 || d.n_caps > DC_MAX_CAPS)
-        return fail(REMOE_E_INVALID_ARG, "n_caps %d outside 0..%d", d.n_caps, DC_MAX_CAPS);
+    if (d.I % 8 != 0 || d.K * d.I > CH_MAX_KI)
+        return fail(REMOE_E_UNSUPPORTED, "decode needs inter %% 8 == 0 and top_k * inter <= %d", CH_MAX_KI);
+    if (d.n_layers > DEC_MAX_LAYERS)
+        return fail(REMOE_E_UNSUPPORTED, "decode keeps the trace state of at most %d layers (got %d)", DEC_MAX_LAYERS, d.n_layers);
+    if (d.n_caps < 0 || d.n_caps > DEC_MAX_CAPS)
+        return fail(REMOE_E_INVALID_ARG, "n_caps %d outside 0..%d", d.n_caps, DEC_MAX_CAPS);
+    if ((int64_t)d.N * d.H * d.I * 2 >= ((int64_t)1 << 32))
+        return fail(REMOE_E_UNSUPPORTED, "decode: one layer's down-projection tensor spans 4 GiB or more");
+    if ((int64_t)d.steps_total * d.n_layers + d.n_layers >= ((int64_t)1 << 32))
+        return fail(REMOE_E_UNSUPPORTED, "decode: steps_total * n_layers does not fit the 32-bit exchange tags");
     int dev = 0, n_cu = 0;
     REMOE_HIP_TRY(hipGetDevice(&dev));
     REMOE_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
     if (n_cu < 1) return fail(REMOE_E_HIP, "device reports no compute units");
     // one workgroup per compute unit, all resident at once (checked against the occupancy below)
     const int G = n_cu;
-    const int W = G * DC_WAVES;
-    if ((d.K * d.I / 8 + 63) / 64 > DC_MAX_DCH)
-        return fail(REMOE_E_UNSUPPORTED, "decode: top_k * inter too large for the register prefetch");
-    (void)W;
+    if (G > DEC_MAX_GRID) return fail(REMOE_E_UNSUPPORTED, "decode: %d compute units exceed the supported %d", G, DEC_MAX_GRID);
+    const int W = G * CH_STREAM;
+    const int KI = d.K * d.I;
+    const int ipw = (KI + W - 1) / W;
+    const int rpw = (d.H + W - 1) / W;
+    const int n_seg = d.N * (d.H / DEC_SEG);
+    const DecodeWsLayout wl = decode_ws_layout(d.H, d.N, d.I, d.K);
+    if (ipw > CH_ITEMS)
+        return fail(REMOE_E_UNSUPPORTED, "decode (layers chained): top_k * inter = %d is more than %d activations for each of "
+                    "the %d streaming wavefronts of this device", KI, CH_ITEMS, W);
+    const int rpw_t = d.H > 2048 ? 2 : 1;            // rows per wavefront the kernel is instantiated for
+    if (rpw > rpw_t)
+        return fail(REMOE_E_UNSUPPORTED, "decode (layers chained): hidden %d needs %d output rows per wavefront on this "
+                    "device, %d supported", d.H, rpw, rpw_t);
+    if (n_seg > CH_MAX_R * W || n_seg > wl.n_logit)
+        return fail(REMOE_E_UNSUPPORTED, "decode (layers chained): n_experts * hidden / 256 = %d router segments are more "
+                    "than %d wavefronts x %d", n_seg, W, CH_MAX_R);
+    if (W > wl.n_h)
+        return fail(REMOE_E_UNSUPPORTED, "decode (layers chained): %d streaming wavefronts exceed the %d exchange words "
+                    "of a ring slot", W, wl.n_h);
 
-    DecodeArgs a;
+    ChainArgs a;
     a.layers = d.layers;
     a.x = static_cast<const bf16_t *>(d.x);
     a.steps_total = d.steps_total;
@@ -374,7 +652,7 @@ remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream)
     a.out_idx = d.out_idx;
     a.out_w = d.out_w;
     a.n_caps = d.n_caps;
-    for (int c = 0; c < DC_MAX_CAPS; ++c) a.caps[c] = (c < d.n_caps) ? d.caps[c] : 0;
+    for (int c = 0; c < DEC_MAX_CAPS; ++c) a.caps[c] = (c < d.n_caps) ? d.caps[c] : 0;
     a.expert_bytes = d.expert_bytes;
     a.lru_state = d.lru_state;
     a.out_overlap = d.out_overlap;
@@ -383,40 +661,44 @@ remoe_status launch_decode(const DecodeLaunch &d, hipStream_t stream)
     a.total_miss = reinterpret_cast<unsigned long long *>(d.total_miss);
     a.bytes_fetched = reinterpret_cast<unsigned long long *>(d.bytes_fetched);
     char *ws = static_cast<char *>(d.workspace);
-    if (G > DC_MAX_GRID) return fail(REMOE_E_UNSUPPORTED, "decode: %d compute units exceed the barrier's %d flags", G, DC_MAX_GRID);
     a.abort_flag = reinterpret_cast<uint32_t *>(ws + 128);
-    a.bar = reinterpret_cast<uint32_t *>(ws + 256);
-    const DecodeWsLayout wl = decode_ws_layout(d.H, d.N, d.I, d.K);
-    a.logit_part = reinterpret_cast<unsigned long long *>(ws + wl.logit_off);
-    a.hbuf = reinterpret_cast<float *>(ws + wl.h_off);
+    // The workspace holds, per group of the layer-overlapped kernel, DEC_RING slots of partial logits and
+    // DEC_RING slots of activation words.  This kernel uses, per XCD copy, the first slot of a group's
+    // logit ring, and the first two slots of its word ring (activations, output values).
+    a.logit_x = reinterpret_cast<unsigned long long *>(ws + wl.logit_off);
+    a.logit_stride = DEC_RING * wl.n_logit;
+    a.h_x = reinterpret_cast<unsigned long long *>(ws + wl.h_off);
+    a.y_x = a.h_x + wl.n_h;
+    a.word_stride = DEC_RING * wl.n_h;
     a.spin_limit = d.spin_limit_ticks;
 
-    hipLaunchKernelGGL(decode_clear_flags, dim3(1), dim3(256), 0, stream, a.bar, G, a.abort_flag, a.logit_part,
-                       d.N * (d.H / DC_SEG));
+    // both regions are contiguous from logit_off to the end of the workspace
+    hipLaunchKernelGGL(decode_chain_clear, dim3(1), dim3(1024), 0, stream, a.abort_flag, a.logit_x,
+                       (int)((wl.total - wl.logit_off) / sizeof(unsigned long long)));
     void *params[] = {&a};
     const void *fn = nullptr;
+    const bool few = KI <= 4 * 512;                  // down-row chunks per lane: 4 or 12
     switch (d.H / 512) {
-    case 1: fn = reinterpret_cast<const void *>(decode_kernel<1>); break;
-    case 2: fn = reinterpret_cast<const void *>(decode_kernel<2>); break;
-    case 4: fn = reinterpret_cast<const void *>(decode_kernel<4>); break;
-    case 8: fn = reinterpret_cast<const void *>(decode_kernel<8>); break;
+    case 1: fn = few ? reinterpret_cast<const void *>(decode_chain_kernel<1, 4, 1>) : reinterpret_cast<const void *>(decode_chain_kernel<1, 12, 1>); break;
+    case 2: fn = few ? reinterpret_cast<const void *>(decode_chain_kernel<2, 4, 1>) : reinterpret_cast<const void *>(decode_chain_kernel<2, 12, 1>); break;
+    case 4: fn = few ? reinterpret_cast<const void *>(decode_chain_kernel<4, 4, 1>) : reinterpret_cast<const void *>(decode_chain_kernel<4, 12, 1>); break;
+    case 8: fn = few ? reinterpret_cast<const void *>(decode_chain_kernel<8, 4, 2>) : reinterpret_cast<const void *>(decode_chain_kernel<8, 12, 2>); break;
     default: return fail(REMOE_E_UNSUPPORTED, "decode supports hidden in {512, 1024, 2048, 4096} (got %d)", d.H);
     }
-    // The grid barrier needs every workgroup resident.  An ordinary launch of one workgroup per
-    // compute unit gives that once the occupancy query confirms a workgroup fits; should other work
-    // hold compute units for long, the bounded waits end the kernel with the abort word set instead
-    // of hanging.  (A cooperative launch would check the same, but kernel tracing tools on this
-    // software stack crash at process exit after one.)
-    // Unused dynamic LDS lifts the workgroup above half a compute unit's 160 KB, so that no two
-    // workgroups share a compute unit while another one idles.
+    // Every workgroup must be resident (the exchanges wait for all of them).  An ordinary launch of one
+    // workgroup per compute unit gives that once the occupancy query confirms a workgroup fits; should
+    // other work hold compute units for long, the bounded waits end the kernel with the abort word set
+    // instead of hanging.  (A cooperative launch would check the same, but kernel tracing tools on this
+    // software stack crash at process exit after one.)  Unused dynamic LDS lifts the workgroup above
+    // half a compute unit's 160 KB, so that no two workgroups share a compute unit while another idles.
     hipFuncAttributes attr;
     REMOE_HIP_TRY(hipFuncGetAttributes(&attr, fn));
     const size_t half_lds = 80 * 1024 + 256;
     const size_t pad = attr.sharedSizeBytes < half_lds ? half_lds - attr.sharedSizeBytes : 0;
     int per_cu = 0;
-    REMOE_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, DC_THREADS, pad));
+    REMOE_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, CH_THREADS, pad));
     if (per_cu < 1) return fail(REMOE_E_UNSUPPORTED, "decode: a workgroup does not fit one compute unit");
-    REMOE_HIP_TRY(hipLaunchKernel(fn, dim3(G), dim3(DC_THREADS), params, pad, stream));
+    REMOE_HIP_TRY(hipLaunchKernel(fn, dim3(G), dim3(CH_THREADS), params, pad, stream));
     return REMOE_OK;
 }
 
