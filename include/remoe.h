@@ -72,7 +72,10 @@ size_t remoe_workspace_bytes(const remoe_layer_desc *desc, int64_t n_tokens);
  *   out_margin [T]       fp32 logit_(K) - logit_(K+1) (+inf when K == N_r), or NULL
  *   out_probs  [T, N_r]  fp32 P_t, or NULL
  *
- * Products and sums are fp32 (fp32 matrix cores).  T may be 0 (nothing is launched).
+ * The logits carry fp32 accuracy.  fp32 hidden states are multiplied on the fp32 matrix cores.
+ * bf16 hidden states are multiplied on the bf16 matrix cores against the gate matrix split into
+ * three bf16 pieces per weight (hi + mid + lo, 24 significand bits in all), so every product is
+ * exact in fp32 and the sums are fp32.  T may be 0 (nothing is launched).
  * Only hidden, n_experts, top_k, renorm and dtype of `desc` are read.
  */
 remoe_status moe_route(const remoe_layer_desc *desc, const void *x, int64_t n_tokens,
@@ -167,7 +170,15 @@ remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps,
  *                   layers of a step do not depend on each other and both orders give the same result:
  *                   REMOE_DECODE_CHAINED    a layer starts only after the previous layer has finished
  *                                           on every compute unit, as in a decoder whose layers feed
- *                                           each other (three grid-wide waits per layer-step);
+ *                                           each other.  Per layer-step the grid exchanges three sets
+ *                                           of values (router logits, the K * I activations, the H
+ *                                           output values) as tagged words that every workgroup
+ *                                           publishes and a dedicated wavefront per workgroup collects;
+ *                                           there is no grid-wide barrier.  With W = 8 * compute
+ *                                           units it needs ceil(top_k * inter / W) <= 3,
+ *                                           ceil(hidden / W) <= 1 (<= 2 for hidden = 4096) and
+ *                                           n_experts * hidden / 256 <= W; other shapes are refused
+ *                                           with REMOE_E_UNSUPPORTED;
  *                   REMOE_DECODE_PIPELINED  the layers of a step overlap.  The compute units are split
  *                                           into 8 groups (one per XCD); group x owns layers x, x + 8,
  *                                           ... and runs them as a software pipeline: while one of its
@@ -199,7 +210,7 @@ remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps,
  *                   byte 128 is an abort flag: non-zero after the
  *                   call has completed means a wait inside the kernel exceeded `spin_limit_us` and
  *                   the outputs of this call are invalid (every workgroup still exits).
- *   spin_limit_us   upper bound of a single grid-barrier wait in microseconds (0 = 2 seconds)
+ *   spin_limit_us   upper bound of a single wait for other workgroups' values in microseconds (0 = 2 seconds)
  *
  * The kernel is persistent: one workgroup per compute unit, all of which must be resident at once,
  * so other work that holds compute units for long while it runs can trip the wait limit.  Calls
@@ -259,8 +270,12 @@ remoe_status moe_decode_static(const remoe_layer_desc *desc, int32_t n_layers,
  *   out_total_miss[s] = sum_t out_miss   (#uMiss)      out_total_uniq[s] = sum_t out_uniq
  *   out_bytes[s]      = out_total_miss[s] * expert_bytes       (uHR = 1 - total_miss / total_uniq)
  *
- * After the step every requested expert is held; while more than `capacity` are held, the one its
- * policy ranks last is dropped (the paper names the policies only; these are the rules taken):
+ * After the step every requested expert is held (App. A: the cache admits what the step fetched, and
+ * what it used is resident when the next step starts); while more than `capacity` are held, one
+ * expert is dropped: the one its policy ranks last among the held experts that this step did NOT
+ * request, and only when no such expert is left (more distinct requests than `capacity`) the one
+ * ranked last among the requested ones.  The rankings (the paper names the policies only; these are
+ * the rules taken):
  *   REMOE_CACHE_LRU     least recently used; inside one step the higher id counts as later
  *   REMOE_CACHE_FIFO    earliest fetched (a hit does not renew); inside one step the higher id is later
  *   REMOE_CACHE_LFU     fewest requesting steps so far in the trace (kept across evictions), then
@@ -367,7 +382,7 @@ remoe_status remoe_loss_forward(const float *probs, const float *probs_ref, cons
 
 /*
  * remoe_loss_backward -- gradient of the weighted sum of the regularisers above with respect to the
- * router logits (the backward pass of the gate-only fine-tuning step, Sec. 4.1 step 6; Eq. 3, 6):
+ * router logits (the backward pass of the gate-only fine-tuning step, Sec. 4.1 step 3; Eq. 3, 6):
  *
  *   L[s] = coef[0] L_Reuse + coef[1] L_Trust + coef[2] L_Smooth + coef[3] L_Lag + coef[4] L_WS,
  *   dlogits[s, t, k] = dL[s] / dz[s, t, k]   with P_t = softmax(z_t):

@@ -6,11 +6,12 @@
 // unique misses |U_t \ C_t| and the token hits against the resident set BEFORE the step, and |U_t|
 // (App. E.2, "Per-step hits and misses"); per trace the totals that give #uMiss and uHR.
 // These policies carry state from step to step (unlike LRU, whose resident set is a function of
-// the last requests alone), so a trace is walked in order: one wavefront per trace, lane l owning
-// experts l and l + 64 with their resident bit and retention key in registers.  After a step every
-// requested expert is held; while more than C are held, the one with the smallest key among those
-// the step did not request is dropped (two wavefront-wide minimum reductions: primary key, then
-// secondary key, which ends in the expert id and is therefore unique).  Keys (larger = kept longer):
+// the last requests alone), so a trace is walked in order: one wavefront per trace, the resident set
+// a 128-bit mask in wave-uniform registers, lane l holding the retention keys of experts l and
+// l + 64.  After a step every requested expert is held; while more than C are held, the one with the
+// smallest key among those the step did not request is dropped (a wavefront-wide minimum of the
+// secondary key, which ends in the expert id and therefore names the victim; LFU takes the minimum
+// of its primary key first).  Keys (larger = kept longer):
 //   LRU    (step of last use, id)                 FIFO  (step of last fetch, id)
 //   LFU    requests so far, then (step of last use, id)
 //   Belady (steps_total - step of next request, 127 - id): the next request farthest ahead goes first
@@ -46,34 +47,33 @@ __device__ __forceinline__ void stage_rows(const int32_t *__restrict__ table, in
 }
 
 // Belady: nxt[t, j] = first step after t that requests expert idx[t, j] again, or T (never).
+// A backward walk, one wavefront per trace: seen[e] (LDS) is the earliest request of expert e among
+// the steps already walked; lane j looks slot j's expert up and then enters the step itself.  One
+// wavefront's LDS accesses are served in program order, so the look-ups of a step see the table as
+// the later steps left it; a repeated id reads and writes the same values twice.
 __global__ __launch_bounds__(64) void next_use_kernel(const int32_t *__restrict__ idx, int64_t T, int K, int N,
                                                       int32_t *__restrict__ nxt)
 {
     __shared__ int32_t ids[CP_BATCH * CP_MAX_K];
     __shared__ int32_t outs[CP_BATCH * CP_MAX_K];
+    __shared__ int32_t seen[128];
     const int64_t s = blockIdx.x;
     const int lane = threadIdx.x;
     const int32_t *tr = idx + s * T * K;
     int32_t *no = nxt + s * T * K;
-    int32_t seen0 = (int32_t)T, seen1 = (int32_t)T;      // next request of experts lane, lane + 64 seen so far
+    seen[lane] = (int32_t)T;
+    seen[lane + 64] = (int32_t)T;
     for (int64_t hi = T; hi > 0; hi -= CP_BATCH) {
         const int64_t t0 = hi >= CP_BATCH ? hi - CP_BATCH : 0;
         const int n = (int)(hi - t0);
         stage_rows(tr, t0, n, K, ids);
         __syncthreads();
         for (int tt = n - 1; tt >= 0; --tt) {
-            int32_t mine = (int32_t)T;
-            for (int j = 0; j < K; ++j) {
-                const int e = ids[tt * K + j];
-                int32_t v = (int32_t)T;
-                if (e >= 0 && e < N) v = __shfl(e < 64 ? seen0 : seen1, e & 63, 64);
-                if (lane == j) mine = v;
-            }
-            if (lane < K) outs[tt * K + lane] = mine;
-            for (int j = 0; j < K; ++j) {
-                const int e = ids[tt * K + j];
-                if (e == lane) seen0 = (int32_t)(t0 + tt);
-                if (e == lane + 64) seen1 = (int32_t)(t0 + tt);
+            if (lane < K) {
+                const int e = ids[tt * K + lane];
+                const bool valid = e >= 0 && e < N;
+                outs[tt * K + lane] = valid ? seen[e] : (int32_t)T;
+                if (valid) seen[e] = (int32_t)(t0 + tt);
             }
         }
         __syncthreads();
@@ -82,6 +82,27 @@ __global__ __launch_bounds__(64) void next_use_kernel(const int32_t *__restrict_
     }
 }
 
+// lane `l` of a per-lane register (l wave-uniform)
+__device__ __forceinline__ uint32_t get_lane(uint32_t reg, int l)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (uint32_t)__builtin_amdgcn_readlane((int)reg, l);
+#else
+    (void)l;
+    return reg;
+#endif
+}
+__device__ __forceinline__ bool bit_of(unsigned long long lo, unsigned long long hi, int e)
+{
+    return (((e < 64 ? lo : hi) >> (e & 63)) & 1ull) != 0ull;
+}
+
+// The walk is sequential per trace and one wavefront has nothing to hide a dependent instruction's
+// latency behind, so the step is kept short: the sets (resident, requested, evictable) are 128-bit
+// masks in wave-uniform registers and all set arithmetic is scalar; only the retention keys are
+// per lane.  A batch of 64 steps is staged in LDS and lane l first builds the request mask of step
+// l (one pass, all steps at once); the walk then fetches a step's mask with four lane reads.  A key
+// ends in the expert id, so the wavefront minimum names its victim without a search.
 template <int POLICY>
 __global__ __launch_bounds__(64) void cache_policy_kernel(const int32_t *__restrict__ idx, int64_t T, int K, int N, int C,
                                                           unsigned long long expert_bytes,
@@ -94,43 +115,49 @@ __global__ __launch_bounds__(64) void cache_policy_kernel(const int32_t *__restr
 {
     __shared__ int32_t ids[CP_BATCH * CP_MAX_K];
     __shared__ int32_t nus[(POLICY == REMOE_CACHE_BELADY) ? CP_BATCH * CP_MAX_K : 1];
-    __shared__ uint8_t o_miss[CP_BATCH], o_uniq[CP_BATCH], o_hit[CP_BATCH];
+    __shared__ uint32_t kb[(POLICY == REMOE_CACHE_BELADY) ? 128 : 1];
     const int64_t s = blockIdx.x;
     const int lane = threadIdx.x;
     const int32_t *tr = idx + s * T * K;
-    bool res0 = false, res1 = false;
-    uint32_t khi0 = 0, khi1 = 0, klo0 = 0, klo1 = 0;
+    unsigned long long res_lo = 0ull, res_hi = 0ull;          // resident experts 0..63, 64..127 (wave-uniform)
+    uint32_t khi0 = 0, khi1 = 0, klo0 = 0, klo1 = 0;          // keys of experts lane, lane + 64
     unsigned long long total = 0, total_u = 0;
     for (int64_t t0 = 0; t0 < T; t0 += CP_BATCH) {
         const int n = (int)((T - t0 < CP_BATCH) ? T - t0 : CP_BATCH);
         stage_rows(tr, t0, n, K, ids);
         if (POLICY == REMOE_CACHE_BELADY) stage_rows(nxt + s * T * K, t0, n, K, nus);
         __syncthreads();
-        for (int tt = 0; tt < n; ++tt) {
-            const uint32_t t = (uint32_t)(t0 + tt);
-            bool req0 = false, req1 = false;
-            uint32_t nu0 = (uint32_t)T, nu1 = (uint32_t)T;
-            int hit_tok = 0;
+        // request mask of step t0 + lane
+        unsigned long long m_lo = 0ull, m_hi = 0ull;
+        if (lane < n) {
             for (int j = 0; j < K; ++j) {
-                const int e = ids[tt * K + j];
-                const bool in0 = e == lane, in1 = e == lane + 64 && e < N;
-                req0 |= in0 && e < N;
-                req1 |= in1;
-                hit_tok += (__ballot((in0 && res0) || (in1 && res1)) != 0ull) ? 1 : 0;
-                if (POLICY == REMOE_CACHE_BELADY) {
-                    if (in0) nu0 = (uint32_t)nus[tt * K + j];
-                    if (in1) nu1 = (uint32_t)nus[tt * K + j];
+                const int e = ids[lane * K + j];
+                if (e >= 0 && e < N) {
+                    if (e < 64) m_lo |= 1ull << e;
+                    else m_hi |= 1ull << (e - 64);
                 }
             }
-            const int n_u = __popcll(__ballot(req0)) + __popcll(__ballot(req1));
-            const int miss = __popcll(__ballot(req0 && !res0)) + __popcll(__ballot(req1 && !res1));
+        }
+        const uint32_t m0 = (uint32_t)m_lo, m1 = (uint32_t)(m_lo >> 32), m2 = (uint32_t)m_hi, m3 = (uint32_t)(m_hi >> 32);
+        uint32_t o_miss = 0, o_uniq = 0, o_hit = 0;           // results of step t0 + lane
+        for (int tt = 0; tt < n; ++tt) {
+            const uint32_t t = (uint32_t)(t0 + tt);
+            const unsigned long long req_lo = ((unsigned long long)get_lane(m1, tt) << 32) | get_lane(m0, tt);
+            const unsigned long long req_hi = ((unsigned long long)get_lane(m3, tt) << 32) | get_lane(m2, tt);
+            // token hits count a repeated id every time: lane j looks at slot j
+            const int ej = lane < K ? ids[tt * K + lane] : -1;
+            const int hit_tok = __popcll(__ballot(ej >= 0 && ej < N && bit_of(res_lo, res_hi, ej)));
+            const int n_u = __popcll(req_lo) + __popcll(req_hi);
+            const int miss = __popcll(req_lo & ~res_lo) + __popcll(req_hi & ~res_hi);
             // serve the step: every requested expert is held now; refresh its key
+            const bool req0 = ((req_lo >> lane) & 1ull) != 0ull, req1 = ((req_hi >> lane) & 1ull) != 0ull;
             const uint32_t stamp = ((t + 1u) << 7);
             if (POLICY == REMOE_CACHE_LRU || POLICY == REMOE_CACHE_LFU) {
                 if (req0) klo0 = stamp | (uint32_t)lane;
                 if (req1) klo1 = stamp | (uint32_t)(lane + 64);
             }
             if (POLICY == REMOE_CACHE_FIFO) {
+                const bool res0 = ((res_lo >> lane) & 1ull) != 0ull, res1 = ((res_hi >> lane) & 1ull) != 0ull;
                 if (req0 && !res0) klo0 = stamp | (uint32_t)lane;
                 if (req1 && !res1) klo1 = stamp | (uint32_t)(lane + 64);
             }
@@ -139,20 +166,25 @@ __global__ __launch_bounds__(64) void cache_policy_kernel(const int32_t *__restr
                 khi1 += req1 ? 1u : 0u;
             }
             if (POLICY == REMOE_CACHE_BELADY) {
-                if (req0) klo0 = (((uint32_t)T - nu0) << 7) | (uint32_t)(127 - lane);
-                if (req1) klo1 = (((uint32_t)T - nu1) << 7) | (uint32_t)(127 - (lane + 64));
+                // lane j posts the key of slot j's expert, the lanes that own a requested expert pick theirs
+                // up (one wavefront: its LDS accesses are served in program order; a repeated id posts the
+                // same key twice)
+                if (ej >= 0 && ej < N) kb[ej] = (((uint32_t)T - (uint32_t)nus[tt * K + lane]) << 7) | (uint32_t)(127 - ej);
+                if (req0) klo0 = kb[lane];
+                if (req1) klo1 = kb[lane + 64];
             }
-            res0 |= req0;
-            res1 |= req1;
-            int held = __popcll(__ballot(res0)) + __popcll(__ballot(res1));
+            res_lo |= req_lo;
+            res_hi |= req_hi;
+            int held = __popcll(res_lo) + __popcll(res_hi);
+            // Victims come from the held experts this step did not request: an expert served in a step
+            // stays until the step is over (App. A, step atomicity and admission: E_t is part of the
+            // next resident set whenever C >= K).  Only a step with more distinct requests than C
+            // leaves none of those, and then the ranking runs over the requested ones.
+            unsigned long long free_lo = res_lo & ~req_lo, free_hi = res_hi & ~req_hi;
             while (held > C) {
-                // Victims come from the held experts this step did not request: an expert served in a step
-                // stays until the step is over (App. A, step atomicity and admission: E_t is part of the
-                // next resident set whenever C >= K).  Only a step with more distinct requests than C
-                // leaves none of those, and then the ranking runs over the requested ones.
-                const bool free0 = res0 && !req0, free1 = res1 && !req1;
-                const bool any_free = (__ballot(free0) | __ballot(free1)) != 0ull;
-                bool c0 = any_free ? free0 : res0, c1 = any_free ? free1 : res1;
+                const bool any_free = (free_lo | free_hi) != 0ull;
+                const unsigned long long c_lo = any_free ? free_lo : res_lo, c_hi = any_free ? free_hi : res_hi;
+                bool c0 = ((c_lo >> lane) & 1ull) != 0ull, c1 = ((c_hi >> lane) & 1ull) != 0ull;
                 if (POLICY == REMOE_CACHE_LFU) {
                     const uint32_t a0 = c0 ? khi0 : CP_NONE, a1 = c1 ? khi1 : CP_NONE;
                     const uint32_t mhi = wave_min_u32(a0 < a1 ? a0 : a1);
@@ -161,25 +193,26 @@ __global__ __launch_bounds__(64) void cache_policy_kernel(const int32_t *__restr
                 }
                 const uint32_t b0 = c0 ? klo0 : CP_NONE, b1 = c1 ? klo1 : CP_NONE;
                 const uint32_t mlo = wave_min_u32(b0 < b1 ? b0 : b1);
-                if (c0 && klo0 == mlo) res0 = false;
-                if (c1 && klo1 == mlo) res1 = false;
+                const int victim = (POLICY == REMOE_CACHE_BELADY) ? 127 - (int)(mlo & 127u) : (int)(mlo & 127u);
+                const unsigned long long keep = ~(1ull << (victim & 63));
+                if (victim < 64) { res_lo &= keep; free_lo &= keep; }
+                else { res_hi &= keep; free_hi &= keep; }
                 --held;
             }
-            if (lane == 0) {
-                o_miss[tt] = (uint8_t)miss;
-                o_uniq[tt] = (uint8_t)n_u;
-                o_hit[tt] = (uint8_t)hit_tok;
+            if (lane == tt) {
+                o_miss = (uint32_t)miss;
+                o_uniq = (uint32_t)n_u;
+                o_hit = (uint32_t)hit_tok;
             }
             total += (unsigned long long)miss;
             total_u += (unsigned long long)n_u;
         }
-        __syncthreads();
         if (lane < n) {
-            out_miss[s * T + t0 + lane] = o_miss[lane];
-            out_uniq[s * T + t0 + lane] = o_uniq[lane];
-            out_hit_tok[s * T + t0 + lane] = o_hit[lane];
+            out_miss[s * T + t0 + lane] = (uint8_t)o_miss;
+            out_uniq[s * T + t0 + lane] = (uint8_t)o_uniq;
+            out_hit_tok[s * T + t0 + lane] = (uint8_t)o_hit;
         }
-        __syncthreads();
+        __syncthreads();       // the staged rows are replaced next
     }
     if (lane == 0) {
         out_total_miss[s] = total;
@@ -203,8 +236,8 @@ __global__ __launch_bounds__(64) void reroute_kernel(const float *__restrict__ p
     const int lane = threadIdx.x;
     const float *pr = probs + s * T * N;
     const float NEG_INF = -__builtin_inff();
-    bool res0 = false, res1 = false;
-    uint32_t key0 = 0, key1 = 0;
+    unsigned long long res_lo = 0ull, res_hi = 0ull;      // resident experts (wave-uniform masks)
+    uint32_t key0 = 0, key1 = 0;                          // (step of last use + 1, id) of experts lane, lane + 64
     unsigned long long total = 0;
     float q0[RR_AHEAD], q1[RR_AHEAD];
 #pragma unroll
@@ -223,39 +256,56 @@ __global__ __launch_bounds__(64) void reroute_kernel(const float *__restrict__ p
             q0[a] = (tn < T && lane < N) ? pr[tn * N + lane] : 0.f;
             q1[a] = (tn < T && lane + 64 < N) ? pr[tn * N + lane + 64] : 0.f;
 
+            const bool res0 = ((res_lo >> lane) & 1ull) != 0ull, res1 = ((res_hi >> lane) & 1ull) != 0ull;
             float m0 = lane < N ? (res0 ? p0 * factor : p0) : NEG_INF;
             float m1 = lane + 64 < N ? (res1 ? p1 * factor : p1) : NEG_INF;
-            bool sel0 = false, sel1 = false;
+            unsigned long long sel_lo = 0ull, sel_hi = 0ull;
             int my_e = 0;
-            float my_p = 0.f;
             for (int j = 0; j < K; ++j) {
                 const float m = wave_max(fmaxf(m0, m1));
                 const unsigned long long b0 = __ballot(m0 == m), b1 = __ballot(m1 == m);
                 const int e = b0 ? __ffsll((long long)b0) - 1 : 63 + __ffsll((long long)b1);
-                const float pe = __shfl(e < 64 ? p0 : p1, e & 63, 64);
-                if (lane == j) { my_e = e; my_p = pe; }
-                if (e == lane) { sel0 = true; m0 = NEG_INF; }
-                if (e == lane + 64) { sel1 = true; m1 = NEG_INF; }
+                if (lane == j) my_e = e;
+                if (e == lane) m0 = NEG_INF;
+                if (e == lane + 64) m1 = NEG_INF;
+                if (e < 64) sel_lo |= 1ull << e;
+                else sel_hi |= 1ull << (e - 64);
             }
+            // the unmodified probability of lane j's expert, fetched once for all K places
+            const float pe_lo = __shfl(p0, my_e & 63, 64), pe_hi = __shfl(p1, my_e & 63, 64);
+            const float my_p = lane < K ? (my_e < 64 ? pe_lo : pe_hi) : 0.f;
             float wgt = my_p;
-            if (renorm) wgt = my_p / wave_sum(lane < K ? my_p : 0.f);
+            if (renorm) wgt = my_p / wave_sum(my_p);
             if (lane < K) {
                 out_idx[(s * T + t) * K + lane] = my_e;
                 out_w[(s * T + t) * K + lane] = wgt;
             }
             // LRU: misses against the state before the step, then the chosen experts become the most recent
-            const int miss = __popcll(__ballot(sel0 && !res0)) + __popcll(__ballot(sel1 && !res1));
+            const int miss = __popcll(sel_lo & ~res_lo) + __popcll(sel_hi & ~res_hi);
             const uint32_t stamp = ((uint32_t)(t + 1) << 7);
-            if (sel0) key0 = stamp | (uint32_t)lane;
-            if (sel1) key1 = stamp | (uint32_t)(lane + 64);
-            res0 |= sel0;
-            res1 |= sel1;
-            int held = __popcll(__ballot(res0)) + __popcll(__ballot(res1));
+            if ((sel_lo >> lane) & 1ull) key0 = stamp | (uint32_t)lane;
+            if ((sel_hi >> lane) & 1ull) key1 = stamp | (uint32_t)(lane + 64);
+            res_lo |= sel_lo;
+            res_hi |= sel_hi;
+            int held = __popcll(res_lo) + __popcll(res_hi);
+            const int n_sel = __popcll(sel_lo) + __popcll(sel_hi);
+            if (n_sel >= C) {
+                // the step alone fills the cache (C = 4 under top-6 routing in App. G): everything older goes,
+                // and of the step's experts, all equally recent, the C highest ids stay
+                res_lo = sel_lo;
+                res_hi = sel_hi;
+                for (int d = n_sel - C; d > 0; --d) {
+                    if (res_lo) res_lo &= res_lo - 1ull;
+                    else res_hi &= res_hi - 1ull;
+                }
+                held = C;
+            }
             while (held > C) {
-                const uint32_t b0 = res0 ? key0 : CP_NONE, b1 = res1 ? key1 : CP_NONE;
-                const uint32_t mk = wave_min_u32(b0 < b1 ? b0 : b1);
-                if (res0 && key0 == mk) res0 = false;
-                if (res1 && key1 == mk) res1 = false;
+                const uint32_t b0 = ((res_lo >> lane) & 1ull) ? key0 : CP_NONE, b1 = ((res_hi >> lane) & 1ull) ? key1 : CP_NONE;
+                const uint32_t mk = wave_min_u32(b0 < b1 ? b0 : b1);     // a key ends in its expert's id
+                const int victim = (int)(mk & 127u);
+                if (victim < 64) res_lo &= ~(1ull << victim);
+                else res_hi &= ~(1ull << (victim - 64));
                 --held;
             }
             if (lane == 0) out_miss[s * T + t] = (uint8_t)miss;
