@@ -47,6 +47,11 @@ def parse_args():
                     help="qwen3_prefill only: skip the M = 1 decode measurement on the resident weights")
     ap.add_argument("--decode-steps", type=int, default=256,
                     help="qwen3_prefill only: timed decode steps per layer order (plus 32 warm-up and 128 profiled)")
+    ap.add_argument("--data-dependence-probe", type=int, default=0, metavar="REPS",
+                    help="batched configs: afterwards run layer 0 REPS times with its weights and REPS times with "
+                         "all-zero expert weights (same routing, same instruction stream) and report both kernel "
+                         "times: a matrix kernel that speeds up on zeros is held back by the clock the chip can "
+                         "sustain on the operands' bit activity, not by its schedule")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
     ap.add_argument("--cpu-sample-layers", type=int, default=12)
     return ap.parse_args()
@@ -234,6 +239,10 @@ def main():
     if cfg.name == "qwen3_prefill" and not args.no_decode_leg:
         result["decode"] = decode_leg(args, L, weights, desc)
 
+    if args.data_dependence_probe > 0:
+        result["data_dependence_probe"] = data_dependence_probe(args.data_dependence_probe, desc, x, weights[0],
+                                                                y[0], idx[0], gw[0], ws)
+
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, cfg, L, x, weights, y, idx, gw)
@@ -266,6 +275,48 @@ def decode_leg(args, L, weights, desc):
                         % (dcfg.seed, dcfg.rhos[-1], list(dcfg.capacities), L))
     figs["target"] = "chained.roofline.frac >= 0.60 of the 8 TB/s HBM peak (<= 16 us per layer-step)"
     return figs
+
+
+def data_dependence_probe(reps, desc, x, w, y, idx, gw, ws):
+    """Layer 0, `reps` calls each: with its weights, then with a zeroed copy of the three expert tensors.
+    The router weights and the input stay, so routing, tile lists and every kernel's instruction
+    stream are identical; only the operand values of the two expert GEMMs (and what flows from them)
+    change.  A third run zeroes the input as well.  Returns the per-kernel averages (HIP events)."""
+    import torch
+
+    import paper_2605_27081_amd as remoe
+
+    def run(wg, wu, wd, xin=x):
+        for _ in range(3):
+            remoe.moe_forward(desc, xin, w["w_router"], wg, wu, wd, w["ws_gate"], w["ws_up"], w["ws_down"],
+                              w["ws_scale"], y, idx, gw, ws)
+        torch.cuda.synchronize()
+        remoe.remoe_profile_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            remoe.moe_forward(desc, xin, w["w_router"], wg, wu, wd, w["ws_gate"], w["ws_up"], w["ws_down"],
+                              w["ws_scale"], y, idx, gw, ws)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / reps * 1e3
+        remoe.remoe_profile_enable(False)
+        out = {"ms_per_layer": round(ms, 4)}
+        for k, name in enumerate(remoe.PROF_KINDS):
+            t, n = remoe.remoe_profile_read(k, reset=True)
+            if n:
+                out[name] = round(t / n, 4)
+        return out
+
+    real = run(w["w_gate"], w["w_up"], w["w_down"])
+    zg, zu, zd = (torch.zeros_like(w[k]) for k in ("w_gate", "w_up", "w_down"))
+    zero = run(zg, zu, zd)
+    # all operands zero: every token then routes to experts 0 .. K-1 (equal logits, ties to the lower id),
+    # i.e. the same number of row tiles spread over K experts instead of N_r
+    zero_all = run(zg, zu, zd, torch.zeros_like(x))
+    del zg, zu, zd
+    return {"reps": reps, "real_weights_ms": real, "zero_expert_weights_ms": zero, "all_zero_ms": zero_all,
+            "gate_up_speedup_on_zeros": round(real["gate_up"] / zero["gate_up"], 3),
+            "down_speedup_on_zeros": round(real["down"] / zero["down"], 3),
+            "note": "same launches, tile lists and instructions in both runs; the zeros run leaves y = 0"}
 
 
 def cpu_baseline(args, cfg, L, x, weights, y, idx, gw):
