@@ -89,6 +89,8 @@ def _check_decode(desc, layers, x, caps, expert_bytes, out, renorm):
     (1, 17, 512, 8, 64, 8, False, [2, 8, 9, 3], [17]),              # K = N, C < K, four capacities
     (20, 9, 512, 32, 128, 4, True, [8], [4, 5]),                    # groups of compute units with 3 and with 2 layers
     (64, 5, 512, 16, 64, 2, True, [4, 16], [5]),                    # the largest layer count
+    (2, 6, 4096, 32, 128, 4, True, [8], [6]),                       # the widest row: two output rows per wavefront, two logit words per expert
+    (2, 7, 1024, 16, 768, 4, False, [4, 8], [3, 4]),                # long down rows (12 chunks per lane) on a narrow layer
 ])
 def test_decode_matches_oracle(L, T, H, N, I, K, renorm, caps, pieces, order):
     _say(f"decode order={order} L={L} T={T} H={H} N={N} I={I} K={K} caps={caps} pieces={pieces}")
