@@ -28,14 +28,14 @@
 //     8-byte word), so a reader needs no separate flag: it polls until the tags match.  Every
 //     value is published once per XCD (eight copies, one store instruction), and a workgroup polls
 //     its own XCD's copy: 32 readers per copy instead of 256 on the same few memory channels.
-//   * As soon as the selection of a layer is known, a streaming wavefront requests everything it
-//     will need for the rest of the layer: the gate and up rows of its three activations (two
-//     register sets, the third activation's rows requested when the first is reduced), its row of
-//     the down projection from all K experts, and before them its router segment of the NEXT
-//     layer (the only data of the next layer that does not depend on this layer's output).  The
-//     loops are straight-line code with a fixed number of loads, so the compiler's wait counts let
-//     one set be reduced while the later requests stay in flight; the down rows are already on
-//     their way while h is being exchanged.
+//   * As soon as the selection of a layer is known, a streaming wavefront requests its router
+//     segment of the NEXT layer (the only data of the next layer that does not depend on this
+//     layer's output) and the gate and up rows of all three of its activations (three register
+//     sets).  Its row of the down projection, from all K experts, is requested as soon as its
+//     activations are published: every wavefront's gate / up rows are then ahead of every down row
+//     in the memory system's queues, and the down rows are on their way while h is being
+//     exchanged.  The loops are straight-line code with a fixed number of loads, so the compiler's
+//     wait counts let one set be reduced while the later requests stay in flight.
 //   * A layer ends with every wavefront publishing its output value(s); the exchange wavefronts
 //     gather them all (in a decoder they are the next layer's input row) before the router
 //     products of the next layer are formed from the prefetched router segments.  The same gather
