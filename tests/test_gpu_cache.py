@@ -4,6 +4,8 @@ Integer results (misses, hits, totals, bytes, sums, histogram, percentiles, load
 compared bit for bit; the two fp64 balance figures to 1e-12 (the kernel adds the per-expert terms
 in a tree, the oracle one after the other).
 """
+import time
+
 import pytest
 import torch
 
@@ -85,7 +87,11 @@ def test_cache_full_length_trace_sampled():
     tot = {}
     for p in POLICY:
         got = _gpu_cache(idx, cfg.n_experts, 32, p, cfg.expert_bytes)
+        t0 = time.perf_counter()
         ref = oracle.cache_policy(idx[:2], cfg.n_experts, 32, p, cfg.expert_bytes)
+        dt = time.perf_counter() - t0
+        # the oracle's rate on its two traces, to set beside bench_extras.py's figure for the kernel
+        _say(f"oracle cache_policy[{p}]: {2 * cfg.seq_len / dt:.3g} trace-steps/s (2 traces x {cfg.seq_len} steps in {dt * 1e3:.1f} ms)")
         assert torch.equal(got["miss"][:2], ref["miss"]) and torch.equal(got["total_miss"][:2], ref["total_miss"])
         tot[p] = got["total_miss"]
     for p in ("lru", "fifo", "lfu"):
