@@ -216,6 +216,24 @@ def main():
                     "timed_in": "a separate pass of %d steps with per-kernel HIP events on (%.3f ms per step)"
                                 % (prof_steps, elapsed_prof / prof_steps * 1e3)}
 
+    # the other kernels of a layer against the roofline that bounds each (algorithmic work per launch over
+    # its average duration in the profiled pass); routed experts only, bf16 layers
+    others = {}
+    if cfg.dtype == "bf16":
+        es = 2
+        work = {
+            "down": ("mfma", 2.0 * T * K * cfg.inter * H, BF16_MFMA_PEAK_TFLOPS, 1e12, "TFLOP/s"),
+            # K (+1 with a shared expert) rows of H values read per token, one written
+            "combine": ("hbm", float(T) * (K + (2 if cfg.shared_inter else 1)) * H * es, HBM_PEAK_GBS, 1e9, "GB/s"),
+            # the hidden states once and the gate matrix once; the routing out
+            "route": ("hbm", float(T) * H * es + N * H * 4.0 + T * K * 8.0, HBM_PEAK_GBS, 1e9, "GB/s"),
+        }
+        for name, (bound, amount, peak, scale, unit) in work.items():
+            if name in prof:
+                ach = amount / (prof[name]["ms_avg"] * 1e-3) / scale
+                others[name] = {"bound": bound, "achieved": round(ach, 1), "peak": peak, "unit": unit,
+                                "frac": round(ach / peak, 4), "avg_launch_ms": round(prof[name]["ms_avg"], 4)}
+
     eor = float(ov_sum.sum()) / (K * (Ts - 1) * n_tr) if Ts > 1 else float("nan")
     total_miss = int(miss_tot.sum())
     result = {
@@ -229,7 +247,8 @@ def main():
         "roofline": roofline,
         "layer": {"useful_tflops": round(layer_tflops, 2),
                   "frac_of_bf16_mfma_peak": round(layer_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
-                  "kernels_ms_avg": {k: round(v["ms_avg"], 4) for k, v in prof.items()}},
+                  "kernels_ms_avg": {k: round(v["ms_avg"], 4) for k, v in prof.items()},
+                  "other_kernels": others},
         "trace": {"eor": round(eor, 5), "lru_misses": total_miss,
                   "bytes_fetched": int(miss_bytes.sum())},
         "setup": {"weights_gib": round(wbytes / 2**30, 2), "generate_s": round(gen_s, 1)},
