@@ -193,7 +193,7 @@ remoe_status lru_simulate(const int32_t *idx, int64_t n_seq, int64_t n_steps,
  *                                           other shapes are refused with REMOE_E_UNSUPPORTED.
  *
  *   desc            bf16 layers without shared expert; hidden in {512, 1024, 2048, 4096},
- *                   inter % 8 == 0, top_k * inter <= 6144
+ *                   inter % 64 == 0 (as for every bf16 layer), top_k * inter <= 6144
  *   layer_weights   DEVICE array [n_layers][4] of device pointers: w_router [N_r,H] fp32,
  *                   w_gate [N_r,I,H], w_up [N_r,I,H], w_down [N_r,H,I] (bf16)
  *   x               [steps_total, H] bf16; step g reads row g (every layer sees the same row)

@@ -373,14 +373,23 @@ __global__ __launch_bounds__(DP_THREADS) void decode_pipe_kernel(const PipeArgs 
             if (doT && wave == (it & (DP_WAVES - 1))) {
                 const float NEG_INF = -__builtin_inff();
                 const float *lp = lpart[it & 1];
+                // An expert's segment products are added in segment order in runs of at most eight, then the
+                // runs in order (one run up to hidden = 2048, two at 4096): the association the chained
+                // kernel's per-workgroup sums have, so that both orders produce the same logits bit for bit.
                 float v0 = NEG_INF, v1 = NEG_INF;
                 if (lane < N) {
-                    v0 = 0.f;
-                    for (int q = 0; q < segs; ++q) v0 += lp[lane * segs + q];
+                    for (int r0 = 0; r0 < segs; r0 += 8) {
+                        float run = 0.f;
+                        for (int q = r0; q < segs && q < r0 + 8; ++q) run += lp[lane * segs + q];
+                        v0 = r0 ? v0 + run : run;
+                    }
                 }
                 if (lane + 64 < N) {
-                    v1 = 0.f;
-                    for (int q = 0; q < segs; ++q) v1 += lp[(lane + 64) * segs + q];
+                    for (int r0 = 0; r0 < segs; r0 += 8) {
+                        float run = 0.f;
+                        for (int q = r0; q < segs && q < r0 + 8; ++q) run += lp[(lane + 64) * segs + q];
+                        v1 = r0 ? v1 + run : run;
+                    }
                 }
                 float m0 = v0, m1 = v1, my_z = NEG_INF, zmax = 0.f;
                 int my_e = 0;
